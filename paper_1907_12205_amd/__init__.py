@@ -1,0 +1,11 @@
+"""MI355X-native DETOX parameter-server step: thin Python binding over libdetox.so.
+
+Every function here only marshals arguments (torch tensors -> device pointers, sizes, the
+current HIP stream) into the C ABI declared in include/detox.h; all arithmetic runs in the
+hand-written gfx950 kernels.  There is no CPU fallback: importing works without a GPU (so the
+library's exports can be checked), calling anything needs one.
+"""
+from .binding import (  # noqa: F401
+    AGG, DetoxError, OP, detox_block_mean, detox_filter_block_mean, detox_majority_filter,
+    detox_step, lib, library_path, robust_bulyan, robust_coord_median, robust_geomedian,
+    robust_multikrum, robust_pairwise_sqdist, strerror, trace, workspace_bytes)

@@ -1,0 +1,374 @@
+// C ABI of libdetox (declared in include/detox.h): argument validation, workspace carving and
+// the order in which the kernels of one call are enqueued.  No arithmetic of the method lives
+// here; every step runs in the kernels of filter.hip, gram.hip, select.hip and sortnet.hip.
+#include <vector>
+
+#include "../../include/detox.h"
+#include "detox_internal.h"
+
+namespace detox {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+struct TraceRec {
+    const char *name;
+    hipEvent_t start, stop;
+};
+bool g_trace_on = false;
+std::vector<TraceRec> g_trace;
+
+int status_of(hipError_t e)
+{
+    if (e == hipSuccess) return DETOX_OK;
+    g_last_hip_error = (int)e;
+    return DETOX_EDEVICE;
+}
+
+constexpr size_t kAlign = 256;
+size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Hands out 256-byte aligned pieces of the caller's workspace.
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+    template <class T>
+    T *take(size_t count)
+    {
+        T *p = reinterpret_cast<T *>(base + off);
+        off += round_up(count * sizeof(T));
+        return p;
+    }
+};
+
+size_t filter_ws_bytes(int64_t groups) { return round_up((size_t)groups * sizeof(unsigned long long)); }
+
+// Gram partials + Gram matrix + the count x count scratch of the selection kernels.
+size_t aggregator_ws_bytes(int64_t count)
+{
+    if (count < 1 || count > kMaxCount) return 0;
+    const size_t c2 = (size_t)(count * count);
+    return round_up(gram_partial_bytes(count)) + round_up(c2 * sizeof(double)) * 3 +
+           round_up(c2 * sizeof(int32_t)) + round_up((size_t)count * sizeof(double)) * 2;
+}
+
+struct AggWs {
+    void *partials;
+    double *Gm;
+    SelectScratch sc;
+};
+
+AggWs carve_aggregator(void *ws, int64_t count)
+{
+    Carver c(ws);
+    AggWs a;
+    const size_t c2 = (size_t)(count * count);
+    a.partials = c.take<char>(gram_partial_bytes(count));
+    a.Gm = c.take<double>(c2);
+    a.sc.D = c.take<double>(c2);
+    a.sc.sorted = c.take<double>(c2);
+    a.sc.sorted_idx = c.take<int32_t>(c2);
+    a.sc.scores = c.take<double>((size_t)count);
+    a.sc.weights = c.take<double>((size_t)count);
+    return a;
+}
+
+bool ws_ok(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return true;
+    return ws != nullptr && reinterpret_cast<uintptr_t>(ws) % kAlign == 0 && have >= need;
+}
+
+bool matrix_ok(const float *X, int64_t rows, int64_t d, int64_t ld)
+{
+    return X != nullptr && rows > 0 && d > 0 && ld >= d;
+}
+
+int multikrum_impl(const float *X, int64_t count, int64_t d, int64_t ld, int f, int m, float *out,
+                   int32_t *selected, double *scores, void *ws, hipStream_t s)
+{
+    AggWs a = carve_aggregator(ws, count);
+    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+    if (e == hipSuccess) e = launch_multikrum_select(a.Gm, count, f, m, a.sc, selected, scores, s);
+    if (e == hipSuccess) e = launch_rows_mean(X, count, d, ld, selected, m, out, s);
+    return status_of(e);
+}
+
+int bulyan_impl(const float *X, int64_t count, int64_t d, int64_t ld, int f, float *out,
+                int32_t *selected, void *ws, hipStream_t s)
+{
+    AggWs a = carve_aggregator(ws, count);
+    const int theta = (int)count - 2 * f, beta = theta - 2 * f;
+    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+    if (e == hipSuccess) e = launch_bulyan_select(a.Gm, count, f, a.sc, selected, s);
+    if (e == hipSuccess) e = launch_bulyan_trim(X, count, d, ld, selected, theta, beta, out, s);
+    return status_of(e);
+}
+
+int geomedian_impl(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
+                   float *out, void *ws, hipStream_t s)
+{
+    AggWs a = carve_aggregator(ws, count);
+    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, true, s);
+    if (e == hipSuccess) e = launch_weiszfeld(a.Gm, count, iters, eps, a.sc.weights, s);
+    if (e == hipSuccess) e = launch_weighted_sum(X, count, d, ld, a.sc.weights, out, s);
+    return status_of(e);
+}
+
+int check_filter_args(const float *G, int64_t n, int64_t d, int64_t ld, int r)
+{
+    if (!matrix_ok(G, n, d, ld) || r < 1 || r > kMaxR || n % r != 0) return DETOX_EINVAL;
+    if (n / r > 65535 || n > INT32_MAX) return DETOX_EINVAL;
+    return DETOX_OK;
+}
+
+}  // namespace
+
+bool trace_enabled() { return g_trace_on; }
+
+void trace_begin(const char *name, hipStream_t s)
+{
+    TraceRec r;
+    r.name = name;
+    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+    (void)hipEventRecord(r.start, s);
+    g_trace.push_back(r);
+}
+
+void trace_end(hipStream_t s)
+{
+    if (!g_trace.empty()) (void)hipEventRecord(g_trace.back().stop, s);
+}
+
+int num_compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
+}
+
+}  // namespace detox
+
+using namespace detox;
+
+extern "C" {
+
+const char *detox_strerror(int status)
+{
+    switch (status) {
+    case DETOX_OK: return "success";
+    case DETOX_EINVAL: return "invalid argument (null pointer, bad size, ld < d, r does not divide n, or beyond the limits of this build)";
+    case DETOX_EPRECOND: return "aggregator precondition violated (Multi-Krum needs count >= 2f+3 and 1 <= m <= count-f; Bulyan needs count >= 4f+3)";
+    case DETOX_EWORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
+    case DETOX_EDEVICE: return "HIP runtime error (see detox_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+int detox_last_hip_error(void) { return g_last_hip_error; }
+
+size_t detox_workspace_bytes(int op, int64_t count, int64_t d, int64_t aux)
+{
+    (void)d;
+    if (count < 1) return 0;
+    switch (op) {
+    case DETOX_OP_FILTER: return filter_ws_bytes(count);
+    case DETOX_OP_PAIRWISE_SQDIST:
+    case DETOX_OP_MULTIKRUM:
+    case DETOX_OP_BULYAN:
+    case DETOX_OP_GEOMEDIAN: return aggregator_ws_bytes(count);
+    case DETOX_OP_STEP: {
+        if (aux < 1 || aux > kMaxCount) return 0;
+        return filter_ws_bytes(count) + aggregator_ws_bytes(aux);
+    }
+    default: return 0;
+    }
+}
+
+int detox_majority_filter(const float *G, int64_t n, int64_t d, int64_t ld, int r,
+                          const int32_t *group_rows, int32_t *winner, float *Z, int64_t ldz,
+                          void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_filter_args(G, n, d, ld, r);
+    if (rc) return rc;
+    if (!winner || (Z && ldz < d)) return DETOX_EINVAL;
+    const int64_t groups = n / r;
+    if (!ws_ok(ws, ws_bytes, filter_ws_bytes(groups))) return DETOX_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
+                   static_cast<unsigned long long *>(ws), winner};
+    hipError_t e = launch_filter(p, false, s);
+    if (e == hipSuccess && Z)
+        e = launch_block_mean(G, d, ld, winner, groups, groups, nullptr, Z, ldz, true, false, s);
+    return status_of(e);
+}
+
+int detox_block_mean(const float *G, int64_t d, int64_t ld, const int32_t *winner,
+                     int64_t n_votes, int64_t B, const int32_t *vote_perm, float *Zhat,
+                     int64_t ldo, void *stream)
+{
+    if (!G || !winner || !Zhat || d <= 0 || ld < d || ldo < d || n_votes < 1 || B < 1 ||
+        B > n_votes || B > 65535)
+        return DETOX_EINVAL;
+    return status_of(launch_block_mean(G, d, ld, winner, n_votes, B, vote_perm, Zhat, ldo, false,
+                                       false, static_cast<hipStream_t>(stream)));
+}
+
+int detox_filter_block_mean(const float *G, int64_t n, int64_t d, int64_t ld, int r,
+                            const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
+                            int32_t *winner, float *Zhat, int64_t ldo, void *ws, size_t ws_bytes,
+                            void *stream)
+{
+    int rc = check_filter_args(G, n, d, ld, r);
+    if (rc) return rc;
+    const int64_t groups = n / r;
+    if (!winner || !Zhat || ldo < d || B < 1 || B > groups) return DETOX_EINVAL;
+    if (!ws_ok(ws, ws_bytes, filter_ws_bytes(groups))) return DETOX_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
+                   static_cast<unsigned long long *>(ws), winner};
+    hipError_t e = launch_filter(p, true, s);
+    if (e == hipSuccess)
+        e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
+    return status_of(e);
+}
+
+int robust_pairwise_sqdist(const float *X, int64_t count, int64_t d, int64_t ld, double *D,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !D || count > kMaxCount) return DETOX_EINVAL;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    AggWs a = carve_aggregator(ws, count);
+    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+    if (e == hipSuccess) e = launch_sqdist_from_gram(a.Gm, count, D, s);
+    return status_of(e);
+}
+
+int robust_multikrum(const float *X, int64_t count, int64_t d, int64_t ld, int f, int m,
+                     float *out, int32_t *selected, double *scores, void *ws, size_t ws_bytes,
+                     void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !out || !selected || count > kMaxCount || f < 0)
+        return DETOX_EINVAL;
+    if (count < 2 * (int64_t)f + 3 || m < 1 || m > count - f) return DETOX_EPRECOND;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    return multikrum_impl(X, count, d, ld, f, m, out, selected, scores, ws,
+                          static_cast<hipStream_t>(stream));
+}
+
+int robust_bulyan(const float *X, int64_t count, int64_t d, int64_t ld, int f, float *out,
+                  int32_t *selected, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !out || !selected || count > kMaxCount || f < 0)
+        return DETOX_EINVAL;
+    if (count < 4 * (int64_t)f + 3) return DETOX_EPRECOND;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    return bulyan_impl(X, count, d, ld, f, out, selected, ws, static_cast<hipStream_t>(stream));
+}
+
+int robust_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, float *out,
+                        void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount) return DETOX_EINVAL;
+    return status_of(launch_coord_median(X, count, d, ld, out, static_cast<hipStream_t>(stream)));
+}
+
+int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
+                     float *out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount || iters < 0 || !(eps > 0.0))
+        return DETOX_EINVAL;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    return geomedian_impl(X, count, d, ld, iters, eps, out, ws, static_cast<hipStream_t>(stream));
+}
+
+int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
+               const int32_t *group_rows, int64_t B, const int32_t *vote_perm, int agg, int f,
+               int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
+               int32_t *selected, float *out, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_filter_args(G, n, d, ld, r);
+    if (rc) return rc;
+    const int64_t groups = n / r;
+    if (!winner || !Zhat || !out || ldo < d || B < 1 || B > groups || B > kMaxCount || q < 0)
+        return DETOX_EINVAL;
+    if (agg < DETOX_AGG_MULTIKRUM || agg > DETOX_AGG_GEOMEDIAN) return DETOX_EINVAL;
+    if (agg == DETOX_AGG_MULTIKRUM || agg == DETOX_AGG_BULYAN) {
+        if (!selected) return DETOX_EINVAL;
+        if (f < 0) {
+            // Byzantine votes that can survive the filter: each needs (r+1)/2 Byzantine members
+            const int64_t survive = q / ((r + 1) / 2);
+            const int64_t cap = agg == DETOX_AGG_MULTIKRUM ? (B - 3) / 2 : (B - 3) / 4;
+            if (B < 3) return DETOX_EPRECOND;
+            f = (int)(survive < cap ? survive : cap);
+        }
+        if (agg == DETOX_AGG_MULTIKRUM) {
+            if (m < 0) m = (int)B - f;
+            if (B < 2 * (int64_t)f + 3 || m < 1 || m > B - f) return DETOX_EPRECOND;
+        } else if (B < 4 * (int64_t)f + 3) {
+            return DETOX_EPRECOND;
+        }
+    }
+    if (agg == DETOX_AGG_GEOMEDIAN && (iters < 0 || !(eps > 0.0))) return DETOX_EINVAL;
+    const size_t fbytes = filter_ws_bytes(groups);
+    const size_t abytes = agg == DETOX_AGG_COORD_MEDIAN ? 0 : aggregator_ws_bytes(B);
+    if (!ws_ok(ws, ws_bytes, fbytes + abytes)) return DETOX_EWORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
+                   static_cast<unsigned long long *>(ws), winner};
+    hipError_t e = launch_filter(p, true, s);
+    if (e == hipSuccess)
+        e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
+    if (e != hipSuccess) return status_of(e);
+    void *aws = static_cast<char *>(ws) + fbytes;
+    switch (agg) {
+    case DETOX_AGG_MULTIKRUM:
+        return multikrum_impl(Zhat, B, d, ldo, f, m, out, selected, nullptr, aws, s);
+    case DETOX_AGG_BULYAN: return bulyan_impl(Zhat, B, d, ldo, f, out, selected, aws, s);
+    case DETOX_AGG_COORD_MEDIAN: return status_of(launch_coord_median(Zhat, B, d, ldo, out, s));
+    default: return geomedian_impl(Zhat, B, d, ldo, iters, eps, out, aws, s);
+    }
+}
+
+void detox_trace_enable(int on)
+{
+    g_trace_on = on != 0;
+    if (!g_trace_on) {
+        for (auto &r : g_trace) {
+            (void)hipEventDestroy(r.start);
+            (void)hipEventDestroy(r.stop);
+        }
+        g_trace.clear();
+    }
+}
+
+int detox_trace_read(detox_trace_record *records, int cap)
+{
+    int k = 0;
+    for (auto &r : g_trace) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) ms = -1.0f;
+        if (records && k < cap) {
+            records[k].kernel = r.name;
+            records[k].ms = ms;
+            ++k;
+        }
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_trace.clear();
+    return k;
+}
+
+}  // extern "C"

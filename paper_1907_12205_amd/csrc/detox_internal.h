@@ -1,0 +1,105 @@
+// Internal declarations shared by the HIP translation units of libdetox.
+// Nothing here is part of the public C ABI (see include/detox.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace detox {
+
+constexpr int kBlock = 256;            // threads per workgroup of the streaming kernels
+constexpr int kWave = 64;              // gfx950 wavefront
+constexpr int kMaxR = 11;              // node-group size limit (pair flags fit 64 bits)
+constexpr int kMaxCount = 128;         // rows per robust aggregation
+constexpr int kGramGrid = 512;         // workgroups of the persistent Gram kernels
+constexpr int kGramWaves = kGramGrid * (kBlock / kWave);
+
+// ---- tracing -------------------------------------------------------------
+// While tracing is on, TraceScope brackets a launch with two events on its stream.
+bool trace_enabled();
+void trace_begin(const char *name, hipStream_t s);
+void trace_end(hipStream_t s);
+struct TraceScope {
+    hipStream_t s;
+    bool on;
+    TraceScope(const char *name, hipStream_t st) : s(st), on(trace_enabled())
+    {
+        if (on) trace_begin(name, s);
+    }
+    ~TraceScope()
+    {
+        if (on) trace_end(s);
+    }
+};
+
+int num_compute_units();  // of the current device (cached)
+
+// Widest vector (4, 2 or 1 fp32) every row of a matrix can be accessed with.
+inline int row_vec_width(const void *base, int64_t ld)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(base);
+    if (a % 16 == 0 && ld % 4 == 0) return 4;
+    if (a % 8 == 0 && ld % 2 == 0) return 2;
+    return 1;
+}
+
+// ---- filter.hip ------------------------------------------------------------
+struct FilterParams {
+    const float *G;
+    int64_t d, ld;
+    int r;
+    const int32_t *group_rows;   // dev or null
+    const int32_t *vote_perm;    // dev or null
+    int64_t n_votes;             // number of node groups
+    int64_t B;                   // number of vote groups (== n_votes when no mean is formed)
+    float *Zhat;                 // dev, B x d, or null
+    int64_t ldo;
+    unsigned long long *flags;   // dev, n_votes words of pair-mismatch bits
+    int32_t *winner;             // dev, n_votes
+};
+// flags <- 0; one pass over G (pair flags, and block means when mean != 0); winner from flags.
+hipError_t launch_filter(const FilterParams &p, bool mean, hipStream_t s);
+// Zhat_b = mean of the votes of block b, read through `winner`.
+//   copy: blocks of one vote copied bit for bit; only_bad: touch only blocks holding winner = -1.
+hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_t *winner,
+                             int64_t n_votes, int64_t B, const int32_t *vote_perm, float *Zhat,
+                             int64_t ldo, bool copy, bool only_bad, hipStream_t s);
+
+// ---- gram.hip --------------------------------------------------------------
+size_t gram_partial_bytes(int64_t count);
+// Gram matrix Gm[a][b] = <x_a, x_b> (count x count doubles, full, symmetric).
+//   high_precision: products and sums in fp64 throughout (count <= 8 always runs this way).
+hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, void *partials,
+                       double *Gm, bool high_precision, hipStream_t s);
+
+// ---- select.hip ------------------------------------------------------------
+struct SelectScratch {   // all dev, carved from the caller's workspace
+    double *D;           // count x count squared distances
+    double *sorted;      // count x count: each row's distances to the others, ascending
+    int32_t *sorted_idx; // count x count: the row indices in that order
+    double *scores;      // count
+    double *weights;     // count
+};
+hipError_t launch_sqdist_from_gram(const double *Gm, int64_t count, double *D, hipStream_t s);
+hipError_t launch_multikrum_select(const double *Gm, int64_t count, int f, int m,
+                                   const SelectScratch &sc, int32_t *selected, double *scores_out,
+                                   hipStream_t s);
+hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const SelectScratch &sc,
+                                int32_t *selected, hipStream_t s);
+hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double eps,
+                            double *weights, hipStream_t s);
+// out[c] = fp32( sum_i (double) X[rows[i]][c] / m ), rows read from device memory in list order.
+hipError_t launch_rows_mean(const float *X, int64_t count, int64_t d, int64_t ld,
+                            const int32_t *rows, int m, float *out, hipStream_t s);
+// out[c] = fp32( sum_j weights[j] * (double) X[j][c] ).
+hipError_t launch_weighted_sum(const float *X, int64_t count, int64_t d, int64_t ld,
+                               const double *weights, float *out, hipStream_t s);
+
+// ---- sortnet.hip -----------------------------------------------------------
+hipError_t launch_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, float *out,
+                               hipStream_t s);
+// Per coordinate: median of the theta listed rows, mean of the beta values closest to it.
+hipError_t launch_bulyan_trim(const float *X, int64_t count, int64_t d, int64_t ld,
+                              const int32_t *rows, int theta, int beta, float *out, hipStream_t s);
+
+}  // namespace detox

@@ -1,0 +1,327 @@
+// Gram matrix of a row set, <x_a, x_b> over d, as a split-d reduction: the data-touching half of
+// the pairwise squared distances behind Krum / Multi-Krum / Bulyan (the O(p^2 d) term of
+// Section 4, "Improved speed") and of the Gram-space Weiszfeld iteration.
+//
+//   count <= 8 : fp64 FMAs on the vector ALUs, all pairs held in registers per thread.
+//   count  > 8 : fp32 MFMA 16x16x4 tiles (upper triangle of the tile grid), one accumulator set
+//                per wavefront over a strided share of the columns.
+// Either way every workgroup / wavefront writes its partial sums to the workspace and a second
+// kernel adds them in a fixed order in fp64.  No atomics: results repeat bit for bit, and rows
+// that are bit-identical produce bit-identical Gram entries (same products, same order).
+#include "detox_internal.h"
+
+namespace detox {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxGramWaves = 4096;   // upper bound used to size the workspace
+
+__host__ __device__ constexpr int tiles_for(int T) { return T * (T + 1) / 2; }
+
+// ---------------------------------------------------------------------------------------
+// count <= 8: fp64 on the vector ALUs
+// ---------------------------------------------------------------------------------------
+template <int VEC>
+__device__ inline void load_row_guarded(const float *p, int valid, float (&w)[VEC])
+{
+    if (valid == VEC) {
+        if constexpr (VEC == 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(p);
+            w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
+        } else if constexpr (VEC == 2) {
+            const float2 t = *reinterpret_cast<const float2 *>(p);
+            w[0] = t.x, w[1] = t.y;
+        } else {
+            w[0] = p[0];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) w[i] = i < valid ? p[i] : 0.0f;
+    }
+}
+
+__device__ inline double wave_sum_fixed(double v)
+{
+    // fixed butterfly: the same tree for every call, so equal inputs give equal sums
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    return v;
+}
+
+template <int C, int VEC>
+__global__ __launch_bounds__(kBlock) void gram_small_kernel(const float *X, int64_t d, int64_t ld,
+                                                            double *partials)
+{
+    constexpr int NP = C * (C + 1) / 2;
+    double acc[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) acc[i] = 0.0;
+    const int64_t chunks = (d + (int64_t)kBlock * VEC - 1) / ((int64_t)kBlock * VEC);
+    for (int64_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
+        const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
+        const int64_t left = d - col;
+        if (left <= 0) continue;
+        const int valid = left >= VEC ? VEC : (int)left;
+        float x[C][VEC];
+#pragma unroll
+        for (int a = 0; a < C; ++a) load_row_guarded<VEC>(X + a * ld + col, valid, x[a]);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            double xd[C];
+#pragma unroll
+            for (int a = 0; a < C; ++a) xd[a] = (double)x[a][i];
+            int pair = 0;
+#pragma unroll
+            for (int a = 0; a < C; ++a)
+#pragma unroll
+                for (int b = a; b < C; ++b, ++pair) acc[pair] = fma(xd[a], xd[b], acc[pair]);
+        }
+    }
+    __shared__ double red[kBlock / kWave][NP];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const double s = wave_sum_fixed(acc[i]);
+        if (lane == 0) red[wave][i] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < NP) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kBlock / kWave; ++w) s += red[w][threadIdx.x];
+        partials[(int64_t)blockIdx.x * NP + threadIdx.x] = s;
+    }
+}
+
+__global__ void gram_small_reduce_kernel(const double *partials, int blocks, int count, double *Gm)
+{
+    const int np = count * (count + 1) / 2;
+    const int pair = blockIdx.x * blockDim.x + threadIdx.x;
+    if (pair >= np) return;
+    double s = 0.0;
+    for (int w = 0; w < blocks; ++w) s += partials[(int64_t)w * np + pair];
+    int a = 0, rest = pair;
+    while (rest >= count - a) {
+        rest -= count - a;
+        ++a;
+    }
+    const int b = a + rest;
+    Gm[a * count + b] = s;
+    Gm[b * count + a] = s;
+}
+
+// ---------------------------------------------------------------------------------------
+// count > 8: fp32 MFMA.  V_MFMA_F32_16X16X4_F32 takes A (16x4) with lane l holding
+// A[l%16][l/16] and B (4x16) with lane l holding B[l/16][l%16]; for a Gram tile both operands
+// are slices of X in the same layout, so one register per row tile feeds both sides.  The k
+// index is a summation index: lane (i, kk) reads 4 consecutive columns of its own row with one
+// 16-byte load and the four components serve four successive MFMA steps.  The accumulator of
+// tile (ti, tj) holds C[4*(l/16)+v][l%16] in component v of lane l.
+// ---------------------------------------------------------------------------------------
+template <int T, bool ALIGNED>
+__device__ inline void gram_load_step(const float *const (&rowp)[T], int64_t c0, int kk,
+                                      int64_t d, bool guarded, float4 (&buf)[T][2])
+{
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int64_t c = c0 + 16 * u + 4 * kk;
+            const float *q = rowp[t] + c;
+            if (!guarded) {
+                if constexpr (ALIGNED) {
+                    buf[t][u] = *reinterpret_cast<const float4 *>(q);
+                } else {
+                    buf[t][u] = make_float4(q[0], q[1], q[2], q[3]);
+                }
+            } else {
+                buf[t][u] = make_float4(c + 0 < d ? q[0] : 0.0f, c + 1 < d ? q[1] : 0.0f,
+                                        c + 2 < d ? q[2] : 0.0f, c + 3 < d ? q[3] : 0.0f);
+            }
+        }
+}
+
+template <int T>
+__device__ inline void gram_mfma_step(const float4 (&buf)[T][2], f32x4 (&acc)[tiles_for(T)])
+{
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float a[T];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const float4 v = buf[t][u];
+                a[t] = s == 0 ? v.x : (s == 1 ? v.y : (s == 2 ? v.z : v.w));
+            }
+            int tile = 0;
+#pragma unroll
+            for (int ti = 0; ti < T; ++ti)
+#pragma unroll
+                for (int tj = ti; tj < T; ++tj, ++tile)
+                    acc[tile] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti], a[tj], acc[tile], 0, 0, 0);
+        }
+}
+
+template <int T, bool ALIGNED>
+__global__ __launch_bounds__(kBlock) void gram_mfma_kernel(const float *X, int count, int64_t d,
+                                                           int64_t ld, float *partials)
+{
+    constexpr int NT = tiles_for(T);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int i = lane & 15, kk = lane >> 4;
+    const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const int64_t waves = (int64_t)gridDim.x * (kBlock / kWave);
+
+    const float *rowp[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        int row = 16 * t + i;
+        row = row < count ? row : count - 1;   // padded rows re-read the last row; never reported
+        rowp[t] = X + (int64_t)row * ld;
+    }
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int64_t full_steps = d / 32;   // 32 columns per step
+    float4 cur[T][2], nxt[T][2];
+    int64_t step = wave;
+    if (step < full_steps) gram_load_step<T, ALIGNED>(rowp, step * 32, kk, d, false, cur);
+    while (step < full_steps) {
+        const int64_t next = step + waves;
+        if (next < full_steps) gram_load_step<T, ALIGNED>(rowp, next * 32, kk, d, false, nxt);
+        gram_mfma_step<T>(cur, acc);
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) cur[t][u] = nxt[t][u];
+        step = next;
+    }
+    // the ragged last step (d % 32 columns) goes to one wavefront
+    if ((d % 32) != 0 && wave == full_steps % waves) {
+        gram_load_step<T, ALIGNED>(rowp, full_steps * 32, kk, d, true, cur);
+        gram_mfma_step<T>(cur, acc);
+    }
+    float *out = partials + wave * (int64_t)(NT * 256);
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) out[t * 256 + v * 64 + lane] = acc[t][v];
+}
+
+// Adds the per-wavefront tiles in wave order (fp64) and scatters them into the full matrix.
+__global__ void gram_mfma_reduce_kernel(const float *partials, int waves, int T, int count,
+                                        double *Gm)
+{
+    const int nt = tiles_for(T);
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nt * 256) return;
+    double s = 0.0;
+    for (int w = 0; w < waves; ++w) s += (double)partials[(int64_t)w * (nt * 256) + e];
+    const int tile = e / 256, v = (e % 256) / 64, lane = e % 64;
+    int ti = 0, rest = tile;
+    while (rest >= T - ti) {
+        rest -= T - ti;
+        ++ti;
+    }
+    const int tj = ti + rest;
+    const int row = 16 * ti + 4 * (lane / 16) + v, col = 16 * tj + (lane % 16);
+    if (row >= count || col >= count) return;
+    if (ti == tj && row > col) return;   // the mirror element writes both
+    Gm[row * count + col] = s;
+    Gm[col * count + row] = s;
+}
+
+template <int C>
+hipError_t launch_small(const float *X, int64_t d, int64_t ld, double *partials, int grid, int vec,
+                        hipStream_t s)
+{
+    TraceScope t("gram_f64", s);
+    if (vec == 4)
+        gram_small_kernel<C, 4><<<grid, kBlock, 0, s>>>(X, d, ld, partials);
+    else if (vec == 2)
+        gram_small_kernel<C, 2><<<grid, kBlock, 0, s>>>(X, d, ld, partials);
+    else
+        gram_small_kernel<C, 1><<<grid, kBlock, 0, s>>>(X, d, ld, partials);
+    return hipGetLastError();
+}
+
+template <int T>
+hipError_t launch_mfma(const float *X, int count, int64_t d, int64_t ld, float *partials, int grid,
+                       bool aligned, hipStream_t s)
+{
+    TraceScope t("gram_mfma_f32", s);
+    if (aligned)
+        gram_mfma_kernel<T, true><<<grid, kBlock, 0, s>>>(X, count, d, ld, partials);
+    else
+        gram_mfma_kernel<T, false><<<grid, kBlock, 0, s>>>(X, count, d, ld, partials);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t gram_partial_bytes(int64_t count)
+{
+    if (count <= 8) return (size_t)kMaxGramWaves * (size_t)(count * (count + 1) / 2) * sizeof(double);
+    const int T = (int)((count + 15) / 16);
+    return (size_t)kMaxGramWaves * (size_t)tiles_for(T) * 256 * sizeof(float);
+}
+
+hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, void *partials,
+                       double *Gm, bool /*high_precision*/, hipStream_t s)
+{
+    const int cus = num_compute_units();
+    const int vec = row_vec_width(X, ld);
+    hipError_t e;
+    if (count <= 8) {
+        const int64_t chunks = (d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
+        int grid = cus * 8;
+        if (grid > kMaxGramWaves) grid = kMaxGramWaves;
+        if (grid > chunks) grid = (int)chunks;
+        double *pp = static_cast<double *>(partials);
+        switch (count) {
+        case 1: e = launch_small<1>(X, d, ld, pp, grid, vec, s); break;
+        case 2: e = launch_small<2>(X, d, ld, pp, grid, vec, s); break;
+        case 3: e = launch_small<3>(X, d, ld, pp, grid, vec, s); break;
+        case 4: e = launch_small<4>(X, d, ld, pp, grid, vec, s); break;
+        case 5: e = launch_small<5>(X, d, ld, pp, grid, vec, s); break;
+        case 6: e = launch_small<6>(X, d, ld, pp, grid, vec, s); break;
+        case 7: e = launch_small<7>(X, d, ld, pp, grid, vec, s); break;
+        default: e = launch_small<8>(X, d, ld, pp, grid, vec, s); break;
+        }
+        if (e != hipSuccess) return e;
+        const int np = (int)(count * (count + 1) / 2);
+        TraceScope t("gram_reduce", s);
+        gram_small_reduce_kernel<<<(np + 63) / 64, 64, 0, s>>>(pp, grid, (int)count, Gm);
+        return hipGetLastError();
+    }
+    const int T = (int)((count + 15) / 16);
+    int grid = cus * (T <= 4 ? 4 : 2);
+    if (grid * (kBlock / kWave) > kMaxGramWaves) grid = kMaxGramWaves / (kBlock / kWave);
+    const int64_t steps = (d + 31) / 32;
+    const int64_t need = (steps + kBlock / kWave - 1) / (kBlock / kWave);
+    if (grid > need) grid = (int)need;
+    float *pp = static_cast<float *>(partials);
+    const bool aligned = vec == 4;
+    switch (T) {
+    case 1: e = launch_mfma<1>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 2: e = launch_mfma<2>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 3: e = launch_mfma<3>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 4: e = launch_mfma<4>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 5: e = launch_mfma<5>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 6: e = launch_mfma<6>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 7: e = launch_mfma<7>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 8: e = launch_mfma<8>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    const int elems = tiles_for(T) * 256;
+    TraceScope t("gram_reduce", s);
+    gram_mfma_reduce_kernel<<<(elems + 255) / 256, 256, 0, s>>>(pp, grid * (kBlock / kWave), T,
+                                                               (int)count, Gm);
+    return hipGetLastError();
+}
+
+}  // namespace detox

@@ -1,0 +1,155 @@
+"""GPU parity: robust aggregators against the CPU oracle.  Selections, medians: bit-exact.
+Means and geometric median: relative L2 error at most 1e-5."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import dev_matrix, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def dx():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1907_12205_amd as dx
+    return dx
+
+
+MEDIAN_COUNTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 13, 15, 16, 17, 21, 24, 25, 32, 35, 45, 56, 57, 64, 100, 105, 128]
+
+
+@pytest.mark.parametrize("count", MEDIAN_COUNTS)
+def test_coord_median(dx, count):
+    d = 3001 if count > 32 else 10007
+    X = workloads.distinct_rows(count, count, d)
+    X[:, 5] = 0.0; X[: count // 2, 5] = -0.0           # signed zeros
+    X[0, 9] = np.nan; X[-1, 11] = np.inf
+    X[:, 17] = X[0, 17]                                # all equal
+    ref = oracle.coord_median(X)
+    for ld, off in ((None, 0), ((d + 63) // 64 * 64, 0), (None, 1)):
+        got = host(dx.robust_coord_median(dev_matrix(X, ld, off)))
+        assert got.tobytes() == ref.tobytes(), (count, ld, off)
+
+
+def test_coord_median_integer_ties(dx):
+    X = workloads.integer_rows(5, 9, 5000, -2, 2)
+    assert host(dx.robust_coord_median(dev_matrix(X))).tobytes() == oracle.coord_median(X).tobytes()
+
+
+SQDIST_COUNTS = [1, 2, 5, 7, 8, 9, 15, 16, 17, 33, 45, 64, 105, 128]
+
+
+@pytest.mark.parametrize("count", SQDIST_COUNTS)
+def test_pairwise_sqdist(dx, count):
+    d = 20011
+    X = workloads.distinct_rows(1000 + count, count, d, sigma=0.03)
+    ref = oracle.pairwise_sqdist(X)
+    tol = 1e-12 if count <= 8 else 2e-6
+    for ld, off in ((None, 0), ((d + 63) // 64 * 64, 0), (None, 1)):
+        D = host(dx.robust_pairwise_sqdist(dev_matrix(X, ld, off)))
+        assert (D == D.T).all() and (np.diag(D) == 0).all()
+        assert np.abs(D - ref).max() <= tol * ref.max() + 1e-300, (count, ld, off)
+
+
+@pytest.mark.parametrize("count", [6, 15, 45, 105])
+def test_identical_rows_give_exact_zero_and_equal_distances(dx, count):
+    r = 3
+    base = workloads.distinct_rows(7, count // r, 9001, sigma=0.03)
+    X = np.repeat(base, r, axis=0)
+    D = host(dx.robust_pairwise_sqdist(dev_matrix(X)))
+    for a in range(X.shape[0]):
+        for b in range(X.shape[0]):
+            if a // r == b // r:
+                assert D[a, b] == 0.0
+                assert (D[a] == D[b]).all()
+            else:
+                assert D[a, b] > 0
+
+
+def test_integer_rows_distances_are_exact(dx):
+    for count in (5, 12, 45):
+        X = workloads.integer_rows(count, count, 4000)
+        D = host(dx.robust_pairwise_sqdist(dev_matrix(X)))
+        assert (D == oracle.pairwise_sqdist(X)).all()
+
+
+def _multikrum_case(dx, X, f, m):
+    ref_out, ref_sel, ref_scores = oracle.multikrum(X, f, m)
+    out, sel, scores = dx.robust_multikrum(dev_matrix(X), f, m)
+    assert host(sel).tolist() == ref_sel.tolist()
+    np.testing.assert_allclose(host(scores), ref_scores, rtol=3e-6, atol=1e-300)
+    assert rel_l2(host(out), ref_out) <= TOL
+    return ref_sel
+
+
+@pytest.mark.parametrize("count,f,m", [(5, 1, 3), (5, 1, 1), (7, 2, 5), (8, 0, 8), (15, 2, 13),
+                                        (16, 6, 1), (45, 5, 40), (45, 21, 3), (105, 10, 95), (128, 40, 7)])
+def test_multikrum_distinct_rows(dx, count, f, m):
+    X = workloads.distinct_rows(count * 7 + f, count, 30011, sigma=0.03)
+    X[count // 2] += 0.01                                # one row clearly farther than the rest
+    _multikrum_case(dx, X, f, m)
+
+
+@pytest.mark.parametrize("idx,d", [(2, 70001), (3, 50003), (5, 20002)])
+def test_multikrum_vanilla_on_replicated_matrix(dx, idx, d):
+    # replicas have exactly tied scores: the tie rule (lower row first) must hold on the GPU too
+    w = workloads.config(idx, d=d)
+    G = w.matrix()
+    for spec in w.vanilla:
+        if spec["aggregator"] != "multikrum":
+            continue
+        sel = _multikrum_case(dx, G, spec["f"], spec["m"])
+        assert not (set(sel.tolist()) & set(w.byz))
+
+
+def test_multikrum_integer_rows_with_ties(dx):
+    for seed in range(5):
+        X = workloads.integer_rows(seed, 9, 64, -2, 2)
+        _multikrum_case(dx, X, 2, 4)
+
+
+@pytest.mark.parametrize("count,f", [(7, 1), (15, 1), (15, 3), (11, 2), (45, 5), (45, 10), (16, 0), (105, 10), (128, 31)])
+def test_bulyan(dx, count, f):
+    X = workloads.distinct_rows(count * 3 + f, count, 20011, sigma=0.03)
+    ref_out, ref_sel = oracle.bulyan(X, f)
+    out, sel = dx.robust_bulyan(dev_matrix(X), f)
+    assert host(sel).tolist() == ref_sel.tolist()
+    assert rel_l2(host(out), ref_out) <= TOL
+
+
+def test_bulyan_on_replicated_matrix_and_heavy_tails(dx):
+    w = workloads.config(4, d=30011)
+    G = w.matrix()
+    ref_out, ref_sel = oracle.bulyan(G, 5)
+    out, sel = dx.robust_bulyan(dev_matrix(G), 5)
+    assert host(sel).tolist() == ref_sel.tolist()
+    assert rel_l2(host(out), ref_out) <= TOL
+
+
+@pytest.mark.parametrize("count", [1, 2, 3, 7, 8, 9, 21, 45])
+def test_geomedian(dx, count):
+    X = workloads.distinct_rows(50 + count, count, 20011, sigma=0.03)
+    if count >= 7:
+        X[1] = 100.0                                     # a far outlier
+    for iters in (0, 1, 50):
+        ref = oracle.geomedian(X, iters=iters, eps=1e-8)
+        got = host(dx.robust_geomedian(dev_matrix(X), iters=iters, eps=1e-8))
+        assert rel_l2(got, ref) <= TOL, (count, iters)
+
+
+def test_aggregators_accept_unaligned_rows(dx):
+    X = workloads.distinct_rows(3, 15, 5003, sigma=0.03)
+    ref_out, ref_sel, _ = oracle.multikrum(X, 2, 13)
+    ref_b, ref_bsel = oracle.bulyan(X, 1)
+    ref_g = oracle.geomedian(X)
+    for ld, off in ((5003, 1), (5004, 2), (5003, 0)):
+        Xd = dev_matrix(X, ld, off)
+        out, sel, _ = dx.robust_multikrum(Xd, 2, 13)
+        assert host(sel).tolist() == ref_sel.tolist() and rel_l2(host(out), ref_out) <= TOL
+        out, sel = dx.robust_bulyan(Xd, 1)
+        assert host(sel).tolist() == ref_bsel.tolist() and rel_l2(host(out), ref_b) <= TOL
+        assert rel_l2(host(dx.robust_geomedian(Xd)), ref_g) <= TOL

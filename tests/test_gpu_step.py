@@ -1,0 +1,101 @@
+"""GPU parity: the whole parameter-server step (filter -> block means -> aggregator) on the
+five workload shapes, against the oracle pipeline."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import dev_matrix, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def dx():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1907_12205_amd as dx
+    return dx
+
+
+def _run(dx, w, spec, ld=None):
+    G = w.matrix()
+    kw = {k: v for k, v in spec.items() if k not in ("B", "aggregator")}
+    ref_out, ref_w, ref_Zh = oracle.detox_step(G, w.r, spec["B"], spec["aggregator"], **kw)
+    b = dx.detox_step(dev_matrix(G, ld), w.r, w.q, spec["B"], spec["aggregator"], f=spec.get("f", -1),
+                      m=spec.get("m", -1), iters=spec.get("iters", 50), eps=spec.get("eps", 1e-8))
+    assert host(b.winner).tolist() == ref_w.tolist()
+    assert host(b.Zhat).tobytes() == ref_Zh.tobytes()
+    got = host(b.out)
+    if spec["aggregator"] == "coord_median":
+        assert got.tobytes() == ref_out.tobytes()
+    else:
+        assert rel_l2(got, ref_out) <= TOL
+    if spec["aggregator"] == "multikrum":
+        ref_sel = oracle.multikrum(ref_Zh, spec["f"], spec["m"])[1]
+        assert host(b.selected)[: spec["m"]].tolist() == ref_sel.tolist()
+    if spec["aggregator"] == "bulyan":
+        ref_sel = oracle.bulyan(ref_Zh, spec["f"])[1]
+        assert host(b.selected)[: len(ref_sel)].tolist() == ref_sel.tolist()
+
+
+@pytest.mark.parametrize("idx,d", [(1, 4096), (2, 1 << 20), (3, 300007), (4, 200003), (5, 100001)])
+def test_step_on_each_workload(dx, idx, d):
+    w = workloads.config(idx, d=d)
+    for spec in w.detox:
+        _run(dx, w, spec)
+        _run(dx, w, spec, ld=(d + 63) // 64 * 64)
+
+
+def test_step_derives_f_and_m(dx):
+    # q = 5, r = 3: at most 5 // 2 = 2 Byzantine votes survive the filter (Appendix B.1 uses
+    # the same count to state Bulyan's requirement 4*2+3 = 11 <= 15)
+    w = workloads.config(3, d=20011)
+    G = w.matrix()
+    Gd = dev_matrix(G)
+    ref_out, _, ref_Zh = oracle.detox_step(G, 3, 15, "bulyan", f=2)
+    b = dx.detox_step(Gd, 3, 5, 15, "bulyan")
+    assert rel_l2(host(b.out), ref_out) <= TOL
+    ref_out, _, _ = oracle.detox_step(G, 3, 5, "multikrum", f=1, m=4)     # capped by (5-3)/2
+    b = dx.detox_step(Gd, 3, 5, 5, "multikrum")
+    assert rel_l2(host(b.out), ref_out) <= TOL
+
+
+def test_step_output_ignores_byzantine_content(dx):
+    w = workloads.config(3, d=40009)
+    spec = w.detox[0]
+    a = host(dx.detox_step(dev_matrix(w.matrix()), 3, 5, spec["B"], "multikrum", f=1, m=3).out).copy()
+    rng = np.random.default_rng(0)
+    for i in list(w.byz):
+        w.byz[i] = rng.standard_normal(w.d).astype(np.float32)
+    b = host(dx.detox_step(dev_matrix(w.matrix()), 3, 5, spec["B"], "multikrum", f=1, m=3).out)
+    assert a.tobytes() == b.tobytes()
+
+
+def test_no_attack_is_the_plain_mean(dx):
+    w = workloads.config(3, d=40009)
+    w.byz.clear()
+    b = dx.detox_step(dev_matrix(w.matrix()), 3, 0, 5, "multikrum", f=0, m=5)
+    assert rel_l2(host(b.out), w.honest_mean()) <= TOL
+
+
+def test_full_size_resnet18_shape(dx):
+    """n = 45, r = 3, q = 5, d = 11,173,962 in the layout the benchmark times (rows padded to a
+    multiple of 64 floats): DETOX Multi-Krum and vanilla Multi-Krum against the oracle."""
+    w = workloads.config(3)
+    G = w.matrix()
+    ld = (w.d + 63) // 64 * 64
+    Gd = w.to_device(ld=ld)
+    spec = w.detox[0]
+    ref_out, ref_w, ref_Zh = oracle.detox_step(G, 3, spec["B"], "multikrum", f=spec["f"], m=spec["m"])
+    b = dx.detox_step(Gd, 3, 5, spec["B"], "multikrum", f=spec["f"], m=spec["m"])
+    assert host(b.winner).tolist() == ref_w.tolist()
+    assert host(b.Zhat).tobytes() == ref_Zh.tobytes()
+    assert rel_l2(host(b.out), ref_out) <= TOL
+    v = w.vanilla[0]
+    ref_out, ref_sel, ref_scores = oracle.multikrum(G, v["f"], v["m"])
+    out, sel, scores = dx.robust_multikrum(Gd, v["f"], v["m"])
+    assert host(sel).tolist() == ref_sel.tolist()
+    np.testing.assert_allclose(host(scores), ref_scores, rtol=3e-6)
+    assert rel_l2(host(out), ref_out) <= TOL
