@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the DETOX parameter-server step on one MI355X.
+
+Workload (the one the headline metric is quoted on): n = 45 nodes, r = 3, q = 5 Byzantine
+(ALIE attack), d = 11,173,962 fp32 (ResNet-18-sized), synthetic and seeded.  One "step" is one
+pass of the whole hot path over the resident n x d matrix:
+    majority-vote filter -> 15 votes -> 5 block means -> Multi-Krum(f=1, m=3) -> d-vector.
+The same run also times the vanilla comparison (Multi-Krum over all 45 rows, f=5, m=40), the
+dominant kernel on its own (per-kernel HIP events inside the library) and the CPU oracle on the
+host cores.  Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return start.elapsed_time(stop) / steps, wall_ms / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="workload index 1..5 (3 = headline)")
+    ap.add_argument("--d", type=int, default=None, help="override the dimension (debugging)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-vanilla", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs the parameter-server step on ONE GPU (the step has no "
+                 "inter-GPU part); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_1907_12205_amd as dx
+    import workloads
+    from paper_1907_12205_amd.binding import StepBuffers
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dx.lib()   # fails loudly if the HIP library has not been built
+
+    t0 = time.time()
+    w = workloads.config(args.config, d=args.d)
+    n, r, q, d = w.n, w.r, w.q, w.d
+    ld = (d + 63) // 64 * 64                       # rows padded to 256 bytes: 16-byte loads everywhere
+    G = w.to_device("cuda:0", ld=ld)
+    spec = w.detox[0]
+    B, agg = spec["B"], spec["aggregator"]
+    log(f"[bench] workload {w.name}: n={n} r={r} q={q} d={d} ld={ld} attack={w.attack} "
+        f"({n * d * 4 / 1e9:.3f} GB resident, generated in {time.time() - t0:.1f}s)")
+
+    buf = StepBuffers(n, d, r, B, G.device)
+    kw = dict(f=spec.get("f", -1), m=spec.get("m", -1), iters=spec.get("iters", 50), eps=spec.get("eps", 1e-8))
+
+    def detox_step():
+        dx.detox_step(G, r, q, B, agg, buffers=buf, **kw)
+
+    ms_step, wall_ms = time_steps(detox_step, args.steps, args.warmup, torch)
+    in_bytes = n * d * 4
+    value = in_bytes / (ms_step * 1e-3) / 1e9
+    log(f"[bench] DETOX step ({agg}, B={B}): {ms_step:.4f} ms/step (host wall {wall_ms:.4f}), "
+        f"{value:.1f} GB/s of gradients aggregated")
+
+    # ---- dominant kernel, timed by the library's own HIP events on the launch stream --------
+    with dx.trace() as tr:
+        for _ in range(args.steps):
+            detox_step()
+        recs = tr.records()
+    per_kernel = {}
+    for name, ms in recs:
+        per_kernel.setdefault(name, []).append(ms)
+    kernel_ms = {k: float(np.mean(v)) for k, v in per_kernel.items()}
+    dominant = max(kernel_ms, key=kernel_ms.get)
+    alg_rows = {"filter_block_mean": n + B}        # rows read + rows written by the fused pass
+    alg_bytes = alg_rows.get(dominant, n) * d * 4
+    achieved = alg_bytes / (kernel_ms[dominant] * 1e-3) / 1e9
+    log("[bench] per-kernel ms: " + ", ".join(f"{k}={v:.4f}" for k, v in kernel_ms.items()))
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": round(kernel_ms[dominant], 5)}
+    step_alg_bytes = (n + B + spec.get("m", 0) + 1) * d * 4 if agg == "multikrum" else None
+
+    # ---- vanilla comparison: the same aggregator over all n rows ------------------------------
+    vanilla = None
+    if w.vanilla and not args.no_vanilla:
+        v = w.vanilla[0]
+        out_v = torch.empty(d, dtype=torch.float32, device=G.device)
+        if v["aggregator"] == "multikrum":
+            ws_v = torch.empty(dx.workspace_bytes("multikrum", n, d), dtype=torch.uint8, device=G.device)
+            fn = lambda: dx.robust_multikrum(G, v["f"], v["m"], out=out_v, ws=ws_v, with_scores=False)
+            rows = n + v["m"] + 1
+        elif v["aggregator"] == "bulyan":
+            ws_v = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
+            fn = lambda: dx.robust_bulyan(G, v["f"], out=out_v, ws=ws_v)
+            rows = n + (n - 2 * v["f"]) + 1
+        else:
+            fn = lambda: dx.robust_coord_median(G, out=out_v)
+            rows = n + 1
+        ms_v, _ = time_steps(fn, args.steps, args.warmup, torch)
+        with dx.trace() as tr:
+            for _ in range(min(args.steps, 5)):
+                fn()
+            recs = tr.records()
+        vk = {}
+        for name, ms in recs:
+            vk.setdefault(name, []).append(ms)
+        vanilla = {"aggregator": v["aggregator"], **{k: v[k] for k in ("f", "m") if k in v},
+                   "ms_per_step": round(ms_v, 5), "GBps_aggregated": round(in_bytes / (ms_v * 1e-3) / 1e9, 1),
+                   "hbm_frac_algorithmic": round(rows * d * 4 / (ms_v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                   "kernel_ms": {k: round(float(np.mean(x)), 5) for k, x in vk.items()},
+                   "detox_speedup": round(ms_v / ms_step, 3)}
+        log(f"[bench] vanilla {v['aggregator']}: {ms_v:.4f} ms/step; DETOX is {ms_v / ms_step:.2f}x faster")
+
+    # ---- CPU oracle on the host cores (a reported baseline, not the target) ------------------
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+
+        Gh = w.matrix()
+        t1 = time.perf_counter()
+        okw = {k: v for k, v in spec.items() if k not in ("B", "aggregator")}
+        ref_out, ref_w, _ = oracle.detox_step(Gh, r, B, agg, **okw)
+        t_cpu = time.perf_counter() - t1
+        got = buf.out.cpu().numpy().astype(np.float64)
+        err = float(np.linalg.norm(got - ref_out) / max(np.linalg.norm(ref_out), 1e-300))
+        same_w = buf.winner.cpu().numpy().tolist() == ref_w.tolist()
+        cpu = {"value": round(in_bytes / t_cpu / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": f"the full workload ({n} x {d}), one repetition of the DETOX step",
+               "ms_per_step": round(t_cpu * 1e3, 2), "gpu_matches_oracle": bool(same_w and err <= 1e-5),
+               "rel_l2_vs_oracle": err}
+        log(f"[bench] CPU oracle: {t_cpu * 1e3:.1f} ms on {cpu['cores']} threads; GPU rel-L2 vs oracle {err:.2e}, "
+            f"votes equal: {same_w}")
+        if vanilla and w.vanilla[0]["aggregator"] == "multikrum" and n * d <= 6e8:
+            t1 = time.perf_counter()
+            oracle.multikrum(Gh, w.vanilla[0]["f"], w.vanilla[0]["m"])
+            cpu["vanilla_ms_per_step"] = round((time.perf_counter() - t1) * 1e3, 1)
+
+    line = {
+        "metric": "aggregated gradient GB/s and ms/step (DETOX vs vanilla), % HBM roofline",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: n={n}, r={r}, q={q}, d={d}, {w.attack}; filter -> {n // r} votes -> "
+                               f"{B} block means -> {agg}", "ld": ld, **{k: v for k, v in spec.items() if k != "aggregator"}},
+        "step_hbm_frac_algorithmic": (round(step_alg_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                      if step_alg_bytes else None),
+        "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
+        "roofline": roofline, "vanilla": vanilla, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

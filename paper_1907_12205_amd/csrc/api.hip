@@ -42,7 +42,7 @@ struct Carver {
     }
 };
 
-size_t filter_ws_bytes(int64_t groups) { return round_up((size_t)groups * sizeof(unsigned long long)); }
+size_t filter_bytes(int64_t groups) { return round_up(filter_ws_bytes(groups)); }
 
 // Gram partials + Gram matrix + the count x count scratch of the selection kernels.
 size_t aggregator_ws_bytes(int64_t count)
@@ -85,32 +85,48 @@ bool matrix_ok(const float *X, int64_t rows, int64_t d, int64_t ld)
     return X != nullptr && rows > 0 && d > 0 && ld >= d;
 }
 
+// Gram partials the filter pass accumulated for the block means (blocks = 0: none).
+struct FusedGram {
+    const double *partials = nullptr;
+    int blocks = 0;
+    const int *redo = nullptr;
+};
+
+hipError_t gram_for(const float *X, int64_t count, int64_t d, int64_t ld, const AggWs &a,
+                    const FusedGram &fg, hipStream_t s)
+{
+    if (fg.blocks > 0)
+        return launch_gram_after_filter(X, count, d, ld, a.partials, fg.partials, fg.blocks,
+                                        fg.redo, a.Gm, s);
+    return launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+}
+
 int multikrum_impl(const float *X, int64_t count, int64_t d, int64_t ld, int f, int m, float *out,
-                   int32_t *selected, double *scores, void *ws, hipStream_t s)
+                   int32_t *selected, double *scores, void *ws, const FusedGram &fg, hipStream_t s)
 {
     AggWs a = carve_aggregator(ws, count);
-    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+    hipError_t e = gram_for(X, count, d, ld, a, fg, s);
     if (e == hipSuccess) e = launch_multikrum_select(a.Gm, count, f, m, a.sc, selected, scores, s);
     if (e == hipSuccess) e = launch_rows_mean(X, count, d, ld, selected, m, out, s);
     return status_of(e);
 }
 
 int bulyan_impl(const float *X, int64_t count, int64_t d, int64_t ld, int f, float *out,
-                int32_t *selected, void *ws, hipStream_t s)
+                int32_t *selected, void *ws, const FusedGram &fg, hipStream_t s)
 {
     AggWs a = carve_aggregator(ws, count);
     const int theta = (int)count - 2 * f, beta = theta - 2 * f;
-    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+    hipError_t e = gram_for(X, count, d, ld, a, fg, s);
     if (e == hipSuccess) e = launch_bulyan_select(a.Gm, count, f, a.sc, selected, s);
     if (e == hipSuccess) e = launch_bulyan_trim(X, count, d, ld, selected, theta, beta, out, s);
     return status_of(e);
 }
 
 int geomedian_impl(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
-                   float *out, void *ws, hipStream_t s)
+                   float *out, void *ws, const FusedGram &fg, hipStream_t s)
 {
     AggWs a = carve_aggregator(ws, count);
-    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, true, s);
+    hipError_t e = gram_for(X, count, d, ld, a, fg, s);
     if (e == hipSuccess) e = launch_weiszfeld(a.Gm, count, iters, eps, a.sc.weights, s);
     if (e == hipSuccess) e = launch_weighted_sum(X, count, d, ld, a.sc.weights, out, s);
     return status_of(e);
@@ -181,14 +197,14 @@ size_t detox_workspace_bytes(int op, int64_t count, int64_t d, int64_t aux)
     (void)d;
     if (count < 1) return 0;
     switch (op) {
-    case DETOX_OP_FILTER: return filter_ws_bytes(count);
+    case DETOX_OP_FILTER: return filter_bytes(count);
     case DETOX_OP_PAIRWISE_SQDIST:
     case DETOX_OP_MULTIKRUM:
     case DETOX_OP_BULYAN:
     case DETOX_OP_GEOMEDIAN: return aggregator_ws_bytes(count);
     case DETOX_OP_STEP: {
         if (aux < 1 || aux > kMaxCount) return 0;
-        return filter_ws_bytes(count) + aggregator_ws_bytes(aux);
+        return filter_bytes(count) + aggregator_ws_bytes(aux);
     }
     default: return 0;
     }
@@ -202,11 +218,12 @@ int detox_majority_filter(const float *G, int64_t n, int64_t d, int64_t ld, int 
     if (rc) return rc;
     if (!winner || (Z && ldz < d)) return DETOX_EINVAL;
     const int64_t groups = n / r;
-    if (!ws_ok(ws, ws_bytes, filter_ws_bytes(groups))) return DETOX_EWORKSPACE;
+    if (!ws_ok(ws, ws_bytes, filter_bytes(groups))) return DETOX_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
-                   static_cast<unsigned long long *>(ws), winner};
-    hipError_t e = launch_filter(p, false, s);
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner};
+    hipError_t e = launch_filter(p, false, false, nullptr, s);
     if (e == hipSuccess && Z)
         e = launch_block_mean(G, d, ld, winner, groups, groups, nullptr, Z, ldz, true, false, s);
     return status_of(e);
@@ -232,11 +249,12 @@ int detox_filter_block_mean(const float *G, int64_t n, int64_t d, int64_t ld, in
     if (rc) return rc;
     const int64_t groups = n / r;
     if (!winner || !Zhat || ldo < d || B < 1 || B > groups) return DETOX_EINVAL;
-    if (!ws_ok(ws, ws_bytes, filter_ws_bytes(groups))) return DETOX_EWORKSPACE;
+    if (!ws_ok(ws, ws_bytes, filter_bytes(groups))) return DETOX_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
-                   static_cast<unsigned long long *>(ws), winner};
-    hipError_t e = launch_filter(p, true, s);
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner};
+    hipError_t e = launch_filter(p, true, false, nullptr, s);
     if (e == hipSuccess)
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     return status_of(e);
@@ -262,7 +280,7 @@ int robust_multikrum(const float *X, int64_t count, int64_t d, int64_t ld, int f
         return DETOX_EINVAL;
     if (count < 2 * (int64_t)f + 3 || m < 1 || m > count - f) return DETOX_EPRECOND;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
-    return multikrum_impl(X, count, d, ld, f, m, out, selected, scores, ws,
+    return multikrum_impl(X, count, d, ld, f, m, out, selected, scores, ws, FusedGram{},
                           static_cast<hipStream_t>(stream));
 }
 
@@ -273,7 +291,8 @@ int robust_bulyan(const float *X, int64_t count, int64_t d, int64_t ld, int f, f
         return DETOX_EINVAL;
     if (count < 4 * (int64_t)f + 3) return DETOX_EPRECOND;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
-    return bulyan_impl(X, count, d, ld, f, out, selected, ws, static_cast<hipStream_t>(stream));
+    return bulyan_impl(X, count, d, ld, f, out, selected, ws, FusedGram{},
+                       static_cast<hipStream_t>(stream));
 }
 
 int robust_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, float *out,
@@ -289,7 +308,8 @@ int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
     if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount || iters < 0 || !(eps > 0.0))
         return DETOX_EINVAL;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
-    return geomedian_impl(X, count, d, ld, iters, eps, out, ws, static_cast<hipStream_t>(stream));
+    return geomedian_impl(X, count, d, ld, iters, eps, out, ws, FusedGram{},
+                          static_cast<hipStream_t>(stream));
 }
 
 int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
@@ -320,24 +340,28 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
         }
     }
     if (agg == DETOX_AGG_GEOMEDIAN && (iters < 0 || !(eps > 0.0))) return DETOX_EINVAL;
-    const size_t fbytes = filter_ws_bytes(groups);
+    const size_t fbytes = filter_bytes(groups);
     const size_t abytes = agg == DETOX_AGG_COORD_MEDIAN ? 0 : aggregator_ws_bytes(B);
     if (!ws_ok(ws, ws_bytes, fbytes + abytes)) return DETOX_EWORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
-                   static_cast<unsigned long long *>(ws), winner};
-    hipError_t e = launch_filter(p, true, s);
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner};
+    FusedGram fg;
+    hipError_t e = launch_filter(p, true, agg != DETOX_AGG_COORD_MEDIAN, &fg.blocks, s);
+    fg.partials = fw.gram_partials;
+    fg.redo = fw.redo;
     if (e == hipSuccess)
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     if (e != hipSuccess) return status_of(e);
     void *aws = static_cast<char *>(ws) + fbytes;
     switch (agg) {
     case DETOX_AGG_MULTIKRUM:
-        return multikrum_impl(Zhat, B, d, ldo, f, m, out, selected, nullptr, aws, s);
-    case DETOX_AGG_BULYAN: return bulyan_impl(Zhat, B, d, ldo, f, out, selected, aws, s);
+        return multikrum_impl(Zhat, B, d, ldo, f, m, out, selected, nullptr, aws, fg, s);
+    case DETOX_AGG_BULYAN: return bulyan_impl(Zhat, B, d, ldo, f, out, selected, aws, fg, s);
     case DETOX_AGG_COORD_MEDIAN: return status_of(launch_coord_median(Zhat, B, d, ldo, out, s));
-    default: return geomedian_impl(Zhat, B, d, ldo, iters, eps, out, aws, s);
+    default: return geomedian_impl(Zhat, B, d, ldo, iters, eps, out, aws, fg, s);
     }
 }
 

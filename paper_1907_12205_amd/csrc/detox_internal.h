@@ -11,8 +11,8 @@ constexpr int kBlock = 256;            // threads per workgroup of the streaming
 constexpr int kWave = 64;              // gfx950 wavefront
 constexpr int kMaxR = 11;              // node-group size limit (pair flags fit 64 bits)
 constexpr int kMaxCount = 128;         // rows per robust aggregation
-constexpr int kGramGrid = 512;         // workgroups of the persistent Gram kernels
-constexpr int kGramWaves = kGramGrid * (kBlock / kWave);
+constexpr int kFusedMaxVotes = 1024;   // node groups the persistent filter kernel handles
+constexpr int kFusedMaxGrid = 2048;    // its largest grid (sizes the per-workgroup slots)
 
 // ---- tracing -------------------------------------------------------------
 // While tracing is on, TraceScope brackets a launch with two events on its stream.
@@ -54,11 +54,25 @@ struct FilterParams {
     int64_t B;                   // number of vote groups (== n_votes when no mean is formed)
     float *Zhat;                 // dev, B x d, or null
     int64_t ldo;
-    unsigned long long *flags;   // dev, n_votes words of pair-mismatch bits
-    int32_t *winner;             // dev, n_votes
+    unsigned long long *flags;          // dev, n_votes words of pair bits (general kernel)
+    unsigned long long *flag_partials;  // dev, kFusedMaxGrid x n_votes words (persistent kernel)
+    double *gram_partials;              // dev, kFusedMaxGrid x B(B+1)/2 (persistent kernel, B <= 8)
+    int *redo;                          // dev, 1 word: set when some group has no majority
+    int32_t *winner;                    // dev, n_votes
+    int dev = 0;
 };
-// flags <- 0; one pass over G (pair flags, and block means when mean != 0); winner from flags.
-hipError_t launch_filter(const FilterParams &p, bool mean, hipStream_t s);
+struct FilterWs {
+    int *redo;
+    unsigned long long *flags, *flag_partials;
+    double *gram_partials;
+};
+size_t filter_ws_bytes(int64_t n_votes);
+FilterWs carve_filter_ws(void *ws, int64_t n_votes);
+// One pass over G: pair bits (and block means when mean is set), then winner[] and *redo.
+//   want_gram: also accumulate the Gram matrix of the block means when the persistent kernel
+//   runs with B <= 8; *fused_blocks then receives the number of partial slots written (else 0).
+hipError_t launch_filter(FilterParams p, bool mean, bool want_gram, int *fused_blocks,
+                         hipStream_t s);
 // Zhat_b = mean of the votes of block b, read through `winner`.
 //   copy: blocks of one vote copied bit for bit; only_bad: touch only blocks holding winner = -1.
 hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_t *winner,
@@ -71,6 +85,12 @@ size_t gram_partial_bytes(int64_t count);
 //   high_precision: products and sums in fp64 throughout (count <= 8 always runs this way).
 hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, void *partials,
                        double *Gm, bool high_precision, hipStream_t s);
+// count <= 8 only: Gm from the partials the persistent filter kernel accumulated
+// (fused_partials, fused_blocks slots), unless *redo is set on the device, in which case the
+// Gram matrix is recomputed from X.  No host round trip either way.
+hipError_t launch_gram_after_filter(const float *X, int64_t count, int64_t d, int64_t ld,
+                                    void *partials, const double *fused_partials,
+                                    int fused_blocks, const int *redo, double *Gm, hipStream_t s);
 
 // ---- select.hip ------------------------------------------------------------
 struct SelectScratch {   // all dev, carved from the caller's workspace

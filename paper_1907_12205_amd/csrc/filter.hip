@@ -1,29 +1,42 @@
 // Filtering step and block means (Section 3; Algorithm 1 "Filtering step"; Algorithm 2 with
 // A0 = mean) as column-streaming kernels: every byte of the n x d matrix is read once, with
-// 16-byte loads that are contiguous across the wavefront.
+// 16-byte non-temporal loads that are contiguous across the wavefront.
+//
+// Whole-vector equality is decided from per-pair "differs somewhere" bits: pair (a,b), a<b, of a
+// node group of R members has bit number a*R - a(a+1)/2 + (b-a-1).  With block means enabled,
+// the per-coordinate majority value of each group is summed into the block mean in vote order
+// in the same pass.  A vector majority implies the same majority at every coordinate, so that
+// sum is right whenever every group of the block has a majority; the other blocks are
+// recomputed afterwards from the winners (block_mean_kernel, only_bad).
+//
+// Two kernels:
+//   fused_all_kernel : persistent workgroups, each thread walks ALL vote groups for its columns.
+//                      Pair bits go to a per-workgroup slot (no atomics, nothing to zero), and
+//                      for B <= 8 the Gram matrix of the block means is accumulated in fp64 on
+//                      the side, so Multi-Krum / Weiszfeld need no second pass over the means.
+//   filter_kernel    : grid.y = vote group; any B and any number of groups; pair bits are merged
+//                      into one zero-initialised word per group with integer atomic ORs.
+#include <cstdlib>
 #include "detox_internal.h"
 
 namespace detox {
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 template <int VEC>
-__device__ inline void load_bits(const float *p, uint32_t (&w)[VEC]);
-template <>
-__device__ inline void load_bits<4>(const float *p, uint32_t (&w)[4])
+__device__ inline void load_bits(const float *p, uint32_t (&w)[VEC])
 {
-    const uint4 t = *reinterpret_cast<const uint4 *>(p);
-    w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
-}
-template <>
-__device__ inline void load_bits<2>(const float *p, uint32_t (&w)[2])
-{
-    const uint2 t = *reinterpret_cast<const uint2 *>(p);
-    w[0] = t.x, w[1] = t.y;
-}
-template <>
-__device__ inline void load_bits<1>(const float *p, uint32_t (&w)[1])
-{
-    w[0] = *reinterpret_cast<const uint32_t *>(p);
+    if constexpr (VEC == 4) {
+        const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
+    } else if constexpr (VEC == 2) {
+        const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+        w[0] = t.x, w[1] = t.y;
+    } else {
+        w[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+    }
 }
 
 // Loads `valid` (<= VEC) words starting at p; the rest read as zero.
@@ -43,8 +56,15 @@ template <int VEC>
 __device__ inline void store_floats_guarded(float *p, int valid, const float (&v)[VEC])
 {
     if (valid == VEC) {
-        if constexpr (VEC == 4)
+        if constexpr (VEC == 4) {
+#ifdef DETOX_NT_STORE
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            const f32x4 t = {v[0], v[1], v[2], v[3]};
+            __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(p));
+#else
             *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+#endif
+        }
         else if constexpr (VEC == 2)
             *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
         else
@@ -56,110 +76,76 @@ __device__ inline void store_floats_guarded(float *p, int valid, const float (&v
     }
 }
 
-__global__ void fill_u64_kernel(unsigned long long *p, int64_t count)
+// Loads the R member rows of node group j at this thread's columns (zeros where invalid) and
+// returns the pairs that differ there.
+template <int R, int VEC>
+__device__ inline unsigned long long load_group(const FilterParams &p, int64_t j, int64_t col,
+                                                int valid, uint32_t (&x)[R][VEC])
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = 0ull;
-}
-
-// One workgroup = 256*VEC columns of one vote group b.  For every node group j of the block
-// the R member rows are compared pairwise, word by word; pair (a,b), a<b, has bit number
-// a*R - a(a+1)/2 + (b-a-1) in flags[j], set when the two rows differ anywhere.  With MEAN the
-// per-coordinate majority value of each group is summed into the block mean in vote order.
-// A vector majority implies the same majority at every coordinate, so the sum is right
-// whenever every group of the block has a majority; the other blocks are redone afterwards.
-template <int R, int VEC, bool MEAN>
-__global__ __launch_bounds__(kBlock) void filter_kernel(FilterParams p)
-{
-    const int64_t b = blockIdx.y;
-    const int64_t lo = (b * p.n_votes) / p.B, hi = ((b + 1) * p.n_votes) / p.B;
-    const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
-    const int64_t left = p.d - col;
-    const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
-    const int lane = threadIdx.x & (kWave - 1);
-
-    float acc[VEC];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-
-    for (int64_t pos = lo; pos < hi; ++pos) {
-        const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
-        uint32_t x[R][VEC];
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-            const int64_t row = p.group_rows ? p.group_rows[j * R + k] : j * R + k;
-            if (valid > 0) {
-                load_bits_guarded<VEC>(p.G + row * p.ld + col, valid, x[k]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) x[k][i] = 0u;
-            }
-        }
-        // which pairs differ in this thread's columns
-        unsigned long long bits = 0ull;
-        {
-            int pair = 0;
-#pragma unroll
-            for (int a = 0; a < R; ++a)
-#pragma unroll
-                for (int c = a + 1; c < R; ++c, ++pair) {
-                    uint32_t diff = 0u;
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) diff |= x[a][i] ^ x[c][i];
-                    if (diff) bits |= 1ull << pair;
-                }
-        }
-        if (__any(bits != 0ull)) {
-            // OR over the wavefront, then one conditional atomic per wavefront
-            unsigned long long wave_bits = 0ull;
-#pragma unroll
-            for (int pair = 0; pair < R * (R - 1) / 2; ++pair)
-                if (__any((bits >> pair) & 1ull)) wave_bits |= 1ull << pair;
-            if (lane == 0) {
-                const unsigned long long seen =
-                    __atomic_load_n(&p.flags[j], __ATOMIC_RELAXED);
-                if ((seen & wave_bits) != wave_bits) atomicOr(&p.flags[j], wave_bits);
-            }
-        }
-        if constexpr (MEAN) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                uint32_t v = 0u;
-                bool found = false;
-#pragma unroll
-                for (int a = 0; a <= R / 2; ++a) {   // a majority value shows among the first R/2+1
-                    int votes = 0;
-#pragma unroll
-                    for (int c = 0; c < R; ++c) votes += (x[a][i] == x[c][i]) ? 1 : 0;
-                    if (!found && 2 * votes > R) {
-                        v = x[a][i];
-                        found = true;
-                    }
-                }
-                const float fv = __uint_as_float(v);
-                acc[i] = (pos == lo) ? fv : __fadd_rn(acc[i], fv);
-            }
-        }
-    }
-    if constexpr (MEAN) {
+    for (int k = 0; k < R; ++k) {
+        const int64_t row = p.group_rows ? p.group_rows[j * R + k] : j * R + k;
         if (valid > 0) {
-            const float size = (float)(hi - lo);
-            float outv[VEC];
+            load_bits_guarded<VEC>(p.G + row * p.ld + col, valid, x[k]);
+        } else {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) outv[i] = __fdiv_rn(acc[i], size);
-            store_floats_guarded<VEC>(p.Zhat + b * p.ldo + col, valid, outv);
+            for (int i = 0; i < VEC; ++i) x[k][i] = 0u;
         }
+    }
+    unsigned long long bits = 0ull;
+    int pair = 0;
+#pragma unroll
+    for (int a = 0; a < R; ++a)
+#pragma unroll
+        for (int c = a + 1; c < R; ++c, ++pair) {
+            uint32_t diff = 0u;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) diff |= x[a][i] ^ x[c][i];
+            if (diff) bits |= 1ull << pair;
+        }
+    return bits;
+}
+
+// OR of `bits` over the wavefront (uniform result); cheap when nothing differs.
+template <int R>
+__device__ inline unsigned long long wave_or(unsigned long long bits)
+{
+    unsigned long long wave_bits = 0ull;
+    if (__any(bits != 0ull)) {
+#pragma unroll
+        for (int pair = 0; pair < R * (R - 1) / 2; ++pair)
+            if (__any((bits >> pair) & 1ull)) wave_bits |= 1ull << pair;
+    }
+    return wave_bits;
+}
+
+// Per coordinate: the value held by more than R/2 members (it shows among the first R/2+1), or 0.
+template <int R, int VEC>
+__device__ inline void majority_values(const uint32_t (&x)[R][VEC], float (&out)[VEC])
+{
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        uint32_t v = 0u;
+        bool found = false;
+#pragma unroll
+        for (int a = 0; a <= R / 2; ++a) {
+            int votes = 0;
+#pragma unroll
+            for (int c = 0; c < R; ++c) votes += (x[a][i] == x[c][i]) ? 1 : 0;
+            if (!found && 2 * votes > R) {
+                v = x[a][i];
+                found = true;
+            }
+        }
+        out[i] = __uint_as_float(v);
     }
 }
 
-// winner[j] from the pair flags: the first member (in group order) whose value is shared by
-// more than r/2 members wins; the reported row is the lowest row index holding that value.
-__global__ void filter_finalize_kernel(const unsigned long long *flags, const int32_t *group_rows,
-                                       int r, int64_t groups, int32_t *winner)
+// winner of one group from its pair bits: the first member (in group order) whose value is
+// shared by more than r/2 members wins; the reported row is the lowest row holding that value.
+__device__ inline int32_t winner_from_bits(unsigned long long bits, const int32_t *group_rows,
+                                           int r, int64_t j)
 {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= groups) return;
-    const unsigned long long bits = flags[j];
     int32_t win = -1;
     for (int a = 0; a < r && win < 0; ++a) {
         int votes = 0;
@@ -179,7 +165,197 @@ __global__ void filter_finalize_kernel(const unsigned long long *flags, const in
         }
         if (2 * votes > r) win = (int32_t)lowest;
     }
+    return win;
+}
+
+__device__ inline double wave_sum_fixed(double v)
+{
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Persistent kernel over all vote groups.  NB = number of vote groups when GRAM (compile time,
+// <= 8), otherwise 0 and B is read from the parameters.
+// ---------------------------------------------------------------------------------------
+template <int R, int VEC, int NB, bool MEAN>
+__global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
+{
+    constexpr bool GRAM = NB > 0;
+    constexpr int NP = GRAM ? NB * (NB + 1) / 2 : 1;
+    __shared__ unsigned long long sbits[kFusedMaxVotes];
+    __shared__ double red[kBlock / kWave][NP];
+    for (int j = threadIdx.x; j < p.n_votes; j += kBlock) sbits[j] = 0ull;
+    __syncthreads();
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t B = GRAM ? NB : p.B;
+    double gacc[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) gacc[i] = 0.0;
+
+    const int64_t chunks = (p.d + (int64_t)kBlock * VEC - 1) / ((int64_t)kBlock * VEC);
+    for (int64_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
+        const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
+        const int64_t left = p.d - col;
+        const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+        // one vote group: votes, pair bits, and (MEAN) its mean written to Zhat
+        auto do_block = [&](int64_t b, float (&acc)[VEC]) {
+            const int64_t lo = (b * p.n_votes) / B, hi = ((b + 1) * p.n_votes) / B;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+            for (int64_t pos = lo; pos < hi; ++pos) {
+                const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
+                uint32_t x[R][VEC];
+                const unsigned long long wave_bits = wave_or<R>(load_group<R, VEC>(p, j, col, valid, x));
+                if (wave_bits != 0ull && lane == 0) atomicOr(&sbits[j], wave_bits);   // LDS, integer
+                if constexpr (MEAN) {
+                    float v[VEC];
+                    majority_values<R, VEC>(x, v);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[i] = (pos == lo) ? v[i] : __fadd_rn(acc[i], v[i]);
+                }
+            }
+            if constexpr (MEAN) {
+                const float size = (float)(hi - lo);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] = (p.dev & 2) ? acc[i] * (1.0f / size) : __fdiv_rn(acc[i], size);
+                if (valid > 0 && !(p.dev & 1)) store_floats_guarded<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
+            }
+        };
+        float z[GRAM ? NB : 1][VEC];
+        if constexpr (GRAM) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) do_block(b, z[b]);
+        } else {
+            for (int64_t b = 0; b < B; ++b) do_block(b, z[0]);
+        }
+        if constexpr (GRAM) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                double zd[NB];
+#pragma unroll
+                for (int a = 0; a < NB; ++a) zd[a] = (i < valid) ? (double)z[a][i] : 0.0;
+                int pair = 0;
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+#pragma unroll
+                    for (int c = a; c < NB; ++c, ++pair) gacc[pair] = fma(zd[a], zd[c], gacc[pair]);
+            }
+        }
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < p.n_votes; j += kBlock)
+        p.flag_partials[(int64_t)blockIdx.x * p.n_votes + j] = sbits[j];
+    if constexpr (GRAM) {
+        const int wave = threadIdx.x / kWave;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const double s = wave_sum_fixed(gacc[i]);
+            if (lane == 0) red[wave][i] = s;
+        }
+        __syncthreads();
+        if (threadIdx.x < NP) {
+            double s = 0.0;
+#pragma unroll
+            for (int w = 0; w < kBlock / kWave; ++w) s += red[w][threadIdx.x];
+            p.gram_partials[(int64_t)blockIdx.x * NP + threadIdx.x] = s;
+        }
+    }
+}
+
+// One workgroup: ORs the per-workgroup pair bits, decides the winners, and reports whether any
+// group has no majority (*redo = 1) so that later kernels know the one-pass block means and
+// Gram partials of those blocks must be recomputed.
+__global__ __launch_bounds__(1024) void finalize_partials_kernel(const unsigned long long *partials,
+                                                                int blocks,
+                                                                const int32_t *group_rows, int r,
+                                                                int n_votes, int32_t *winner,
+                                                                int *redo)
+{
+    __shared__ unsigned long long sbits[kFusedMaxVotes];
+    for (int j = threadIdx.x; j < n_votes; j += blockDim.x) sbits[j] = 0ull;
+    __syncthreads();
+    // thread (j, slice): group j = tid % pad, every slices-th workgroup starting at tid / pad
+    int pad = 1;
+    while (pad < n_votes) pad *= 2;            // n_votes <= blockDim.x, so pad <= blockDim.x
+    const int slices = (int)blockDim.x / pad;
+    const int j0 = threadIdx.x % pad, slice = threadIdx.x / pad;
+    if (j0 < n_votes) {
+        unsigned long long bits = 0ull;
+#pragma unroll 8
+        for (int w = slice; w < blocks; w += slices) bits |= partials[(int64_t)w * n_votes + j0];
+        if (bits) atomicOr(&sbits[j0], bits);
+    }
+    __syncthreads();
+    int bad = 0;
+    for (int j = threadIdx.x; j < n_votes; j += blockDim.x) {
+        const int32_t win = winner_from_bits(sbits[j], group_rows, r, j);
+        winner[j] = win;
+        bad |= win < 0;
+    }
+    bad = __syncthreads_or(bad);
+    if (threadIdx.x == 0) *redo = bad ? 1 : 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// General kernel: one workgroup = 256*VEC columns of one vote group b (grid.y = B).
+// ---------------------------------------------------------------------------------------
+__global__ void fill_u64_kernel(unsigned long long *p, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0ull;
+}
+
+template <int R, int VEC, bool MEAN>
+__global__ __launch_bounds__(kBlock) void filter_kernel(FilterParams p)
+{
+    const int64_t b = blockIdx.y;
+    const int64_t lo = (b * p.n_votes) / p.B, hi = ((b + 1) * p.n_votes) / p.B;
+    const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+    const int64_t left = p.d - col;
+    const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+    const int lane = threadIdx.x & (kWave - 1);
+
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+
+    for (int64_t pos = lo; pos < hi; ++pos) {
+        const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
+        uint32_t x[R][VEC];
+        const unsigned long long wave_bits = wave_or<R>(load_group<R, VEC>(p, j, col, valid, x));
+        if (wave_bits != 0ull && lane == 0) {
+            // one conditional atomic per wavefront; skipped once the bits are known
+            const unsigned long long seen = __atomic_load_n(&p.flags[j], __ATOMIC_RELAXED);
+            if ((seen & wave_bits) != wave_bits) atomicOr(&p.flags[j], wave_bits);
+        }
+        if constexpr (MEAN) {
+            float v[VEC];
+            majority_values<R, VEC>(x, v);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = (pos == lo) ? v[i] : __fadd_rn(acc[i], v[i]);
+        }
+    }
+    if constexpr (MEAN) {
+        if (valid > 0) {
+            const float size = (float)(hi - lo);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = __fdiv_rn(acc[i], size);
+            store_floats_guarded<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
+        }
+    }
+}
+
+__global__ void filter_finalize_kernel(const unsigned long long *flags, const int32_t *group_rows,
+                                       int r, int64_t groups, int32_t *winner, int *redo)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= groups) return;
+    const int32_t win = winner_from_bits(flags[j], group_rows, r, j);
     winner[j] = win;
+    if (win < 0 && redo) atomicOr(redo, 1);
 }
 
 // Block means read through `winner` (Algorithm 2, A0 = mean).  grid.y = B, grid.x strides
@@ -231,8 +407,41 @@ __global__ __launch_bounds__(kBlock) void block_mean_kernel(const float *G, int6
     }
 }
 
+// ---- dispatch -----------------------------------------------------------------------------
+template <int R, int VEC, int NB>
+hipError_t launch_fused_rvn(const FilterParams &p, bool mean, int grid, hipStream_t s)
+{
+    if (mean) {
+        TraceScope t(NB > 0 ? "filter_block_mean_gram" : "filter_block_mean", s);
+        fused_all_kernel<R, VEC, NB, true><<<grid, kBlock, 0, s>>>(p);
+    } else {
+        if constexpr (NB == 0) {
+            TraceScope t("filter", s);
+            fused_all_kernel<R, VEC, 0, false><<<grid, kBlock, 0, s>>>(p);
+        }
+    }
+    return hipGetLastError();
+}
+
 template <int R, int VEC>
-hipError_t launch_filter_rv(const FilterParams &p, bool mean, hipStream_t s)
+hipError_t launch_fused_rv(const FilterParams &p, bool mean, int nb, int grid, hipStream_t s)
+{
+    switch (nb) {
+    case 0: return launch_fused_rvn<R, VEC, 0>(p, mean, grid, s);
+    case 1: return launch_fused_rvn<R, VEC, 1>(p, mean, grid, s);
+    case 2: return launch_fused_rvn<R, VEC, 2>(p, mean, grid, s);
+    case 3: return launch_fused_rvn<R, VEC, 3>(p, mean, grid, s);
+    case 4: return launch_fused_rvn<R, VEC, 4>(p, mean, grid, s);
+    case 5: return launch_fused_rvn<R, VEC, 5>(p, mean, grid, s);
+    case 6: return launch_fused_rvn<R, VEC, 6>(p, mean, grid, s);
+    case 7: return launch_fused_rvn<R, VEC, 7>(p, mean, grid, s);
+    case 8: return launch_fused_rvn<R, VEC, 8>(p, mean, grid, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <int R, int VEC>
+hipError_t launch_general_rv(const FilterParams &p, bool mean, hipStream_t s)
 {
     const int64_t chunks = (p.d + (int64_t)kBlock * VEC - 1) / ((int64_t)kBlock * VEC);
     const dim3 grid((unsigned)chunks, (unsigned)p.B);
@@ -247,47 +456,106 @@ hipError_t launch_filter_rv(const FilterParams &p, bool mean, hipStream_t s)
 }
 
 template <int R>
-hipError_t launch_filter_r(const FilterParams &p, bool mean, int vec, hipStream_t s)
+hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int nb, int grid, int vec,
+                    hipStream_t s)
 {
-    if (vec == 4) return launch_filter_rv<R, 4>(p, mean, s);
-    if (vec == 2) return launch_filter_rv<R, 2>(p, mean, s);
-    return launch_filter_rv<R, 1>(p, mean, s);
+    if (fused) {
+        if (vec == 4) return launch_fused_rv<R, 4>(p, mean, nb, grid, s);
+        if (vec == 2) return launch_fused_rv<R, 2>(p, mean, nb, grid, s);
+        return launch_fused_rv<R, 1>(p, mean, nb, grid, s);
+    }
+    if (vec == 4) return launch_general_rv<R, 4>(p, mean, s);
+    if (vec == 2) return launch_general_rv<R, 2>(p, mean, s);
+    return launch_general_rv<R, 1>(p, mean, s);
 }
 
 }  // namespace
 
-hipError_t launch_filter(const FilterParams &p, bool mean, hipStream_t s)
+// Workspace of the filter kernels: [redo word | n_votes flag words | per-workgroup flag slots |
+// per-workgroup Gram partials], each piece rounded up to 256 bytes.  Monotone in n_votes.
+namespace {
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+size_t slot_words(int64_t n_votes)
+{
+    return (size_t)kFusedMaxGrid * (size_t)(n_votes < kFusedMaxVotes ? n_votes : kFusedMaxVotes);
+}
+}  // namespace
+
+size_t filter_ws_bytes(int64_t n_votes)
+{
+    return 256 + up256((size_t)n_votes * sizeof(unsigned long long)) +
+           up256(slot_words(n_votes) * sizeof(unsigned long long)) +
+           up256((size_t)kFusedMaxGrid * 36 * sizeof(double));
+}
+
+FilterWs carve_filter_ws(void *ws, int64_t n_votes)
+{
+    char *base = static_cast<char *>(ws);
+    FilterWs w;
+    w.redo = reinterpret_cast<int *>(base);
+    size_t off = 256;
+    w.flags = reinterpret_cast<unsigned long long *>(base + off);
+    off += up256((size_t)n_votes * sizeof(unsigned long long));
+    w.flag_partials = reinterpret_cast<unsigned long long *>(base + off);
+    off += up256(slot_words(n_votes) * sizeof(unsigned long long));
+    w.gram_partials = reinterpret_cast<double *>(base + off);
+    return w;
+}
+
+hipError_t launch_filter(FilterParams p, bool mean, bool want_gram, int *fused_blocks,
+                         hipStream_t s)
 {
     int vec = row_vec_width(p.G, p.ld);
     if (mean) {
         const int vo = row_vec_width(p.Zhat, p.ldo);
         vec = vo < vec ? vo : vec;
     }
-    {
+    if (const char *e = getenv("DETOX_DEV_FLAGS")) p.dev = atoi(e);
+    const int64_t chunks = (p.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
+    // The persistent kernel serves the paper's regime: up to kFusedMaxVotes node groups cut into
+    // few vote groups.  A pure filter is the same kernel with every group its own block.
+    const bool fused = p.n_votes <= kFusedMaxVotes && (!mean || p.B <= 64);
+    const int nb = (fused && mean && want_gram && p.B <= 8) ? (int)p.B : 0;
+    if (fused_blocks) *fused_blocks = 0;
+    hipError_t e;
+    int grid = 0;
+    if (fused) {
+        grid = num_compute_units() * (p.n_votes <= 128 ? 4 : 2);
+        if (const char *e = getenv("DETOX_DEV_GRID_MULT")) grid = num_compute_units() * atoi(e);
+        if (grid > kFusedMaxGrid) grid = kFusedMaxGrid;
+        if (grid > chunks) grid = (int)chunks;
+    } else {
+        // the redo word (first 256 bytes of the workspace) and the flag words that follow it
         TraceScope t("fill_flags", s);
-        fill_u64_kernel<<<(unsigned)((p.n_votes + 255) / 256), 256, 0, s>>>(p.flags, p.n_votes);
+        const int64_t words = 32 + p.n_votes;
+        fill_u64_kernel<<<(unsigned)((words + 255) / 256), 256, 0, s>>>(
+            reinterpret_cast<unsigned long long *>(p.redo), words);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     switch (p.r) {
-    case 1: e = launch_filter_r<1>(p, mean, vec, s); break;
-    case 2: e = launch_filter_r<2>(p, mean, vec, s); break;
-    case 3: e = launch_filter_r<3>(p, mean, vec, s); break;
-    case 4: e = launch_filter_r<4>(p, mean, vec, s); break;
-    case 5: e = launch_filter_r<5>(p, mean, vec, s); break;
-    case 6: e = launch_filter_r<6>(p, mean, vec, s); break;
-    case 7: e = launch_filter_r<7>(p, mean, vec, s); break;
-    case 8: e = launch_filter_r<8>(p, mean, vec, s); break;
-    case 9: e = launch_filter_r<9>(p, mean, vec, s); break;
-    case 10: e = launch_filter_r<10>(p, mean, vec, s); break;
-    case 11: e = launch_filter_r<11>(p, mean, vec, s); break;
+    case 1: e = launch_r<1>(p, mean, fused, nb, grid, vec, s); break;
+    case 2: e = launch_r<2>(p, mean, fused, nb, grid, vec, s); break;
+    case 3: e = launch_r<3>(p, mean, fused, nb, grid, vec, s); break;
+    case 4: e = launch_r<4>(p, mean, fused, nb, grid, vec, s); break;
+    case 5: e = launch_r<5>(p, mean, fused, nb, grid, vec, s); break;
+    case 6: e = launch_r<6>(p, mean, fused, nb, grid, vec, s); break;
+    case 7: e = launch_r<7>(p, mean, fused, nb, grid, vec, s); break;
+    case 8: e = launch_r<8>(p, mean, fused, nb, grid, vec, s); break;
+    case 9: e = launch_r<9>(p, mean, fused, nb, grid, vec, s); break;
+    case 10: e = launch_r<10>(p, mean, fused, nb, grid, vec, s); break;
+    case 11: e = launch_r<11>(p, mean, fused, nb, grid, vec, s); break;
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    {
-        TraceScope t("filter_finalize", s);
+    TraceScope t("filter_finalize", s);
+    if (fused) {
+        finalize_partials_kernel<<<1, 1024, 0, s>>>(p.flag_partials, grid, p.group_rows, p.r,
+                                                    (int)p.n_votes, p.winner, p.redo);
+        if (fused_blocks && nb > 0) *fused_blocks = grid;
+    } else {
         filter_finalize_kernel<<<(unsigned)((p.n_votes + 255) / 256), 256, 0, s>>>(
-            p.flags, p.group_rows, p.r, p.n_votes, p.winner);
+            p.flags, p.group_rows, p.r, p.n_votes, p.winner, p.redo);
     }
     return hipGetLastError();
 }

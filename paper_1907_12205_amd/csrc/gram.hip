@@ -51,9 +51,10 @@ __device__ inline double wave_sum_fixed(double v)
 
 template <int C, int VEC>
 __global__ __launch_bounds__(kBlock) void gram_small_kernel(const float *X, int64_t d, int64_t ld,
-                                                            double *partials)
+                                                            double *partials, const int *run_if)
 {
     constexpr int NP = C * (C + 1) / 2;
+    if (run_if && *run_if == 0) return;   // uniform: the caller's partials are valid already
     double acc[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) acc[i] = 0.0;
@@ -94,21 +95,41 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(const float *X, int6
     }
 }
 
-__global__ void gram_small_reduce_kernel(const double *partials, int blocks, int count, double *Gm)
+// One workgroup per pair: thread t adds the partials of workgroups t, t+256, ... in that order,
+// then the 256 thread sums are added by a fixed tree.
+__global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double *partials,
+                                                                   int blocks, int count,
+                                                                   double *Gm,
+                                                                   const double *alt_partials,
+                                                                   int alt_blocks,
+                                                                   const int *use_main)
 {
-    const int np = count * (count + 1) / 2;
-    const int pair = blockIdx.x * blockDim.x + threadIdx.x;
-    if (pair >= np) return;
-    double s = 0.0;
-    for (int w = 0; w < blocks; ++w) s += partials[(int64_t)w * np + pair];
-    int a = 0, rest = pair;
-    while (rest >= count - a) {
-        rest -= count - a;
-        ++a;
+    // alt_partials: sums accumulated by the persistent filter kernel, valid unless *use_main
+    if (alt_partials && *use_main == 0) {
+        partials = alt_partials;
+        blocks = alt_blocks;
     }
-    const int b = a + rest;
-    Gm[a * count + b] = s;
-    Gm[b * count + a] = s;
+    const int np = count * (count + 1) / 2;
+    const int pair = blockIdx.x;
+    double s = 0.0;
+    for (int w = threadIdx.x; w < blocks; w += kBlock) s += partials[(int64_t)w * np + pair];
+    __shared__ double red[kBlock];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = kBlock / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        int a = 0, rest = pair;
+        while (rest >= count - a) {
+            rest -= count - a;
+            ++a;
+        }
+        const int b = a + rest;
+        Gm[a * count + b] = red[0];
+        Gm[b * count + a] = red[0];
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -211,15 +232,32 @@ __global__ __launch_bounds__(kBlock) void gram_mfma_kernel(const float *X, int c
         for (int v = 0; v < 4; ++v) out[t * 256 + v * 64 + lane] = acc[t][v];
 }
 
-// Adds the per-wavefront tiles in wave order (fp64) and scatters them into the full matrix.
-__global__ void gram_mfma_reduce_kernel(const float *partials, int waves, int T, int count,
-                                        double *Gm)
+// Adds the per-wavefront tiles in fp64, in two fixed-order levels: kReduceSlices contiguous
+// ranges of wavefronts are summed side by side (threads run along the tile elements, so every
+// load is coalesced), then the slice sums are added in slice order and scattered into the matrix.
+constexpr int kReduceSlices = 32;
+
+__global__ __launch_bounds__(kBlock) void gram_mfma_reduce1_kernel(const float *partials, int waves,
+                                                                   int elems, double *slices)
+{
+    const int e = blockIdx.x * kBlock + threadIdx.x;
+    if (e >= elems) return;
+    const int slice = blockIdx.y;
+    const int per = (waves + kReduceSlices - 1) / kReduceSlices;
+    const int w0 = slice * per, w1 = w0 + per < waves ? w0 + per : waves;
+    double s = 0.0;
+#pragma unroll 8
+    for (int w = w0; w < w1; ++w) s += (double)partials[(int64_t)w * elems + e];
+    slices[(int64_t)slice * elems + e] = s;
+}
+
+__global__ void gram_mfma_reduce2_kernel(const double *slices, int T, int count, double *Gm)
 {
     const int nt = tiles_for(T);
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= nt * 256) return;
     double s = 0.0;
-    for (int w = 0; w < waves; ++w) s += (double)partials[(int64_t)w * (nt * 256) + e];
+    for (int k = 0; k < kReduceSlices; ++k) s += slices[(int64_t)k * (nt * 256) + e];
     const int tile = e / 256, v = (e % 256) / 64, lane = e % 64;
     int ti = 0, rest = tile;
     while (rest >= T - ti) {
@@ -236,16 +274,38 @@ __global__ void gram_mfma_reduce_kernel(const float *partials, int waves, int T,
 
 template <int C>
 hipError_t launch_small(const float *X, int64_t d, int64_t ld, double *partials, int grid, int vec,
-                        hipStream_t s)
+                        const int *run_if, hipStream_t s)
 {
-    TraceScope t("gram_f64", s);
+    TraceScope t(run_if ? "gram_f64_if_redo" : "gram_f64", s);
     if (vec == 4)
-        gram_small_kernel<C, 4><<<grid, kBlock, 0, s>>>(X, d, ld, partials);
+        gram_small_kernel<C, 4><<<grid, kBlock, 0, s>>>(X, d, ld, partials, run_if);
     else if (vec == 2)
-        gram_small_kernel<C, 2><<<grid, kBlock, 0, s>>>(X, d, ld, partials);
+        gram_small_kernel<C, 2><<<grid, kBlock, 0, s>>>(X, d, ld, partials, run_if);
     else
-        gram_small_kernel<C, 1><<<grid, kBlock, 0, s>>>(X, d, ld, partials);
+        gram_small_kernel<C, 1><<<grid, kBlock, 0, s>>>(X, d, ld, partials, run_if);
     return hipGetLastError();
+}
+
+hipError_t launch_small_any(const float *X, int64_t count, int64_t d, int64_t ld, double *pp,
+                            const int *run_if, int *grid_out, hipStream_t s)
+{
+    const int vec = row_vec_width(X, ld);
+    const int64_t chunks = (d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
+    int grid = num_compute_units() * 8;
+    if (grid > kMaxGramWaves) grid = kMaxGramWaves;
+    if (grid > chunks) grid = (int)chunks;
+    *grid_out = grid;
+    switch (count) {
+    case 1: return launch_small<1>(X, d, ld, pp, grid, vec, run_if, s);
+    case 2: return launch_small<2>(X, d, ld, pp, grid, vec, run_if, s);
+    case 3: return launch_small<3>(X, d, ld, pp, grid, vec, run_if, s);
+    case 4: return launch_small<4>(X, d, ld, pp, grid, vec, run_if, s);
+    case 5: return launch_small<5>(X, d, ld, pp, grid, vec, run_if, s);
+    case 6: return launch_small<6>(X, d, ld, pp, grid, vec, run_if, s);
+    case 7: return launch_small<7>(X, d, ld, pp, grid, vec, run_if, s);
+    case 8: return launch_small<8>(X, d, ld, pp, grid, vec, run_if, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 template <int T>
@@ -266,7 +326,8 @@ size_t gram_partial_bytes(int64_t count)
 {
     if (count <= 8) return (size_t)kMaxGramWaves * (size_t)(count * (count + 1) / 2) * sizeof(double);
     const int T = (int)((count + 15) / 16);
-    return (size_t)kMaxGramWaves * (size_t)tiles_for(T) * 256 * sizeof(float);
+    return (size_t)kMaxGramWaves * (size_t)tiles_for(T) * 256 * sizeof(float) +
+           (size_t)kReduceSlices * (size_t)tiles_for(T) * 256 * sizeof(double);
 }
 
 hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, void *partials,
@@ -276,25 +337,13 @@ hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, voi
     const int vec = row_vec_width(X, ld);
     hipError_t e;
     if (count <= 8) {
-        const int64_t chunks = (d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
-        int grid = cus * 8;
-        if (grid > kMaxGramWaves) grid = kMaxGramWaves;
-        if (grid > chunks) grid = (int)chunks;
         double *pp = static_cast<double *>(partials);
-        switch (count) {
-        case 1: e = launch_small<1>(X, d, ld, pp, grid, vec, s); break;
-        case 2: e = launch_small<2>(X, d, ld, pp, grid, vec, s); break;
-        case 3: e = launch_small<3>(X, d, ld, pp, grid, vec, s); break;
-        case 4: e = launch_small<4>(X, d, ld, pp, grid, vec, s); break;
-        case 5: e = launch_small<5>(X, d, ld, pp, grid, vec, s); break;
-        case 6: e = launch_small<6>(X, d, ld, pp, grid, vec, s); break;
-        case 7: e = launch_small<7>(X, d, ld, pp, grid, vec, s); break;
-        default: e = launch_small<8>(X, d, ld, pp, grid, vec, s); break;
-        }
+        int grid = 0;
+        e = launch_small_any(X, count, d, ld, pp, nullptr, &grid, s);
         if (e != hipSuccess) return e;
         const int np = (int)(count * (count + 1) / 2);
         TraceScope t("gram_reduce", s);
-        gram_small_reduce_kernel<<<(np + 63) / 64, 64, 0, s>>>(pp, grid, (int)count, Gm);
+        gram_small_reduce_kernel<<<np, kBlock, 0, s>>>(pp, grid, (int)count, Gm, nullptr, 0, nullptr);
         return hipGetLastError();
     }
     const int T = (int)((count + 15) / 16);
@@ -318,9 +367,33 @@ hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, voi
     }
     if (e != hipSuccess) return e;
     const int elems = tiles_for(T) * 256;
+    // the slice sums live behind the largest possible set of wavefront partials
+    double *slices = reinterpret_cast<double *>(pp + (size_t)kMaxGramWaves * elems);
+    {
+        TraceScope t("gram_reduce", s);
+        gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
+            pp, grid * (kBlock / kWave), elems, slices);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    TraceScope t("gram_scatter", s);
+    gram_mfma_reduce2_kernel<<<(elems + 255) / 256, 256, 0, s>>>(slices, T, (int)count, Gm);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_after_filter(const float *X, int64_t count, int64_t d, int64_t ld,
+                                    void *partials, const double *fused_partials,
+                                    int fused_blocks, const int *redo, double *Gm, hipStream_t s)
+{
+    if (count < 1 || count > 8) return hipErrorInvalidValue;
+    double *pp = static_cast<double *>(partials);
+    int grid = 0;
+    hipError_t e = launch_small_any(X, count, d, ld, pp, redo, &grid, s);   // runs only if *redo
+    if (e != hipSuccess) return e;
+    const int np = (int)(count * (count + 1) / 2);
     TraceScope t("gram_reduce", s);
-    gram_mfma_reduce_kernel<<<(elems + 255) / 256, 256, 0, s>>>(pp, grid * (kBlock / kWave), T,
-                                                               (int)count, Gm);
+    gram_small_reduce_kernel<<<np, kBlock, 0, s>>>(pp, grid, (int)count, Gm, fused_partials,
+                                                   fused_blocks, redo);
     return hipGetLastError();
 }
 
