@@ -177,15 +177,22 @@ int robust_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, fl
 int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
                      float *out, void *ws, size_t ws_bytes, void *stream);
 
-/* The whole parameter-server step: filter -> B block means -> aggregator.
+/* The whole parameter-server step: filter -> B block means -> aggregator, with one pass over
+ * G.  The pass that votes also forms the block means; for B <= 8 it accumulates their Gram
+ * matrix (Multi-Krum, Bulyan, geometric median) or takes their coordinate-wise median on the
+ * fly.  If Zhat is NULL the block means are never written: kernels that need them later
+ * (averaging the selected means, Bulyan's trimming, the Weiszfeld combination) re-form them from
+ * the winner rows of G, with the same arithmetic and bit-identical values.  That is the faster
+ * mode; pass Zhat only if the means themselves are wanted.
  *   q          number of Byzantine nodes; used only when f < 0 to derive
  *              f = min(q / ((r+1)/2), largest f the aggregator admits for B rows)
  *   f, m       aggregator parameters; f < 0 and m < 0 mean "derive"
  *              (m = B - f)
  *   iters, eps Weiszfeld parameters (DETOX_AGG_GEOMEDIAN only)
  *   winner     dev, n/r int32, out
- *   Zhat       dev, B x d (ldo), out: the block means
- *   selected   dev, int32, out, or NULL: Multi-Krum: m entries; Bulyan: B-2f
+ *   Zhat       dev, B x d (ldo), out: the block means; or NULL (ldo ignored)
+ *   selected   dev, int32, out: Multi-Krum: m entries; Bulyan: B-2f entries (indices of
+ *              block means); may be NULL for the two median aggregators
  *   out        dev, d floats
  *   ws         DETOX_OP_STEP bytes (count = n, aux = B)                       */
 int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,

@@ -225,27 +225,32 @@ def robust_geomedian(X, iters: int = 50, eps: float = 1e-8, out=None, ws=None):
 class StepBuffers:
     """Outputs and workspace of detox_step, allocated once and reused across steps."""
 
-    def __init__(self, n, d, r, B, device, ldo: Optional[int] = None):
+    def __init__(self, n, d, r, B, device, ldo: Optional[int] = None, materialise: bool = True):
+        """materialise=False: the block means are not written to memory (Zhat = NULL)."""
         torch = _torch()
         ldo = ldo or ((d + 63) // 64 * 64)
         self.winner = torch.empty(n // r, dtype=torch.int32, device=device)
-        self.Zhat_buf = torch.empty((B, ldo), dtype=torch.float32, device=device)
-        self.Zhat = self.Zhat_buf[:, :d]
+        self.Zhat = None
+        if materialise:
+            self.Zhat_buf = torch.empty((B, ldo), dtype=torch.float32, device=device)
+            self.Zhat = self.Zhat_buf[:, :d]
         self.selected = torch.full((max(B, 1),), -1, dtype=torch.int32, device=device)
         self.out = torch.empty(d, dtype=torch.float32, device=device)
         self.ws = torch.empty(max(workspace_bytes("step", n, d, B), 256), dtype=torch.uint8, device=device)
 
 
 def detox_step(G, r: int, q: int, B: int, aggregator: str, f: int = -1, m: int = -1, iters: int = 50,
-               eps: float = 1e-8, group_rows=None, vote_perm=None, buffers: Optional[StepBuffers] = None):
-    """The whole step.  Returns the StepBuffers holding out, winner, Zhat and selected."""
+               eps: float = 1e-8, group_rows=None, vote_perm=None, buffers: Optional[StepBuffers] = None,
+               materialise: bool = True):
+    """The whole step.  Returns the StepBuffers holding out, winner, Zhat (or None) and selected."""
     p, n, d, ld = _matrix(G)
     gr, vp = _i32(group_rows, G.device), _i32(vote_perm, G.device)
     if buffers is None:
-        buffers = StepBuffers(n, d, max(r, 1), B, G.device)
+        buffers = StepBuffers(n, d, max(r, 1), B, G.device, materialise=materialise)
     b = buffers
     rc = lib().detox_step(p, n, d, ld, r, q, _ptr(gr), B, _ptr(vp), AGG[aggregator], f, m, iters, float(eps),
-                          _ptr(b.winner), _ptr(b.Zhat), b.Zhat.stride(0), _ptr(b.selected), _ptr(b.out),
+                          _ptr(b.winner), _ptr(b.Zhat), b.Zhat.stride(0) if b.Zhat is not None else 0,
+                          _ptr(b.selected), _ptr(b.out),
                           _ptr(b.ws), b.ws.numel(), _stream())
     _check(rc, "detox_step")
     return b

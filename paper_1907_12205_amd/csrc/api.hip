@@ -50,13 +50,15 @@ size_t aggregator_ws_bytes(int64_t count)
     if (count < 1 || count > kMaxCount) return 0;
     const size_t c2 = (size_t)(count * count);
     return round_up(gram_partial_bytes(count)) + round_up(c2 * sizeof(double)) * 3 +
-           round_up(c2 * sizeof(int32_t)) + round_up((size_t)count * sizeof(double)) * 2;
+           round_up(c2 * sizeof(int32_t)) + round_up((size_t)count * sizeof(double)) * 2 +
+           round_up((size_t)count * sizeof(int32_t));
 }
 
 struct AggWs {
     void *partials;
     double *Gm;
     SelectScratch sc;
+    int32_t *row_index;   // count entries: row table of a vote row set
 };
 
 AggWs carve_aggregator(void *ws, int64_t count)
@@ -71,6 +73,7 @@ AggWs carve_aggregator(void *ws, int64_t count)
     a.sc.sorted_idx = c.take<int32_t>(c2);
     a.sc.scores = c.take<double>((size_t)count);
     a.sc.weights = c.take<double>((size_t)count);
+    a.row_index = c.take<int32_t>((size_t)count);
     return a;
 }
 
@@ -92,43 +95,41 @@ struct FusedGram {
     const int *redo = nullptr;
 };
 
-hipError_t gram_for(const float *X, int64_t count, int64_t d, int64_t ld, const AggWs &a,
-                    const FusedGram &fg, hipStream_t s)
+hipError_t gram_for(const RowSet &rs, const AggWs &a, const FusedGram &fg, hipStream_t s)
 {
     if (fg.blocks > 0)
-        return launch_gram_after_filter(X, count, d, ld, a.partials, fg.partials, fg.blocks,
-                                        fg.redo, a.Gm, s);
-    return launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+        return launch_gram_after_filter(rs, a.partials, fg.partials, fg.blocks, fg.redo, a.Gm, s);
+    return launch_gram(rs, a.partials, a.Gm, s);
 }
 
-int multikrum_impl(const float *X, int64_t count, int64_t d, int64_t ld, int f, int m, float *out,
-                   int32_t *selected, double *scores, void *ws, const FusedGram &fg, hipStream_t s)
+int multikrum_impl(const RowSet &rs, int f, int m, float *out, int32_t *selected, double *scores,
+                   void *ws, const FusedGram &fg, hipStream_t s)
 {
-    AggWs a = carve_aggregator(ws, count);
-    hipError_t e = gram_for(X, count, d, ld, a, fg, s);
-    if (e == hipSuccess) e = launch_multikrum_select(a.Gm, count, f, m, a.sc, selected, scores, s);
-    if (e == hipSuccess) e = launch_rows_mean(X, count, d, ld, selected, m, out, s);
+    AggWs a = carve_aggregator(ws, rs.count);
+    hipError_t e = gram_for(rs, a, fg, s);
+    if (e == hipSuccess) e = launch_multikrum_select(a.Gm, rs.count, f, m, a.sc, selected, scores, s);
+    if (e == hipSuccess) e = launch_rows_mean(rs, selected, m, out, s);
     return status_of(e);
 }
 
-int bulyan_impl(const float *X, int64_t count, int64_t d, int64_t ld, int f, float *out,
-                int32_t *selected, void *ws, const FusedGram &fg, hipStream_t s)
+int bulyan_impl(const RowSet &rs, int f, float *out, int32_t *selected, void *ws,
+                const FusedGram &fg, hipStream_t s)
 {
-    AggWs a = carve_aggregator(ws, count);
-    const int theta = (int)count - 2 * f, beta = theta - 2 * f;
-    hipError_t e = gram_for(X, count, d, ld, a, fg, s);
-    if (e == hipSuccess) e = launch_bulyan_select(a.Gm, count, f, a.sc, selected, s);
-    if (e == hipSuccess) e = launch_bulyan_trim(X, count, d, ld, selected, theta, beta, out, s);
+    AggWs a = carve_aggregator(ws, rs.count);
+    const int theta = rs.count - 2 * f, beta = theta - 2 * f;
+    hipError_t e = gram_for(rs, a, fg, s);
+    if (e == hipSuccess) e = launch_bulyan_select(a.Gm, rs.count, f, a.sc, selected, s);
+    if (e == hipSuccess) e = launch_bulyan_trim(rs, selected, theta, beta, out, s);
     return status_of(e);
 }
 
-int geomedian_impl(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
-                   float *out, void *ws, const FusedGram &fg, hipStream_t s)
+int geomedian_impl(const RowSet &rs, int iters, double eps, float *out, void *ws,
+                   const FusedGram &fg, hipStream_t s)
 {
-    AggWs a = carve_aggregator(ws, count);
-    hipError_t e = gram_for(X, count, d, ld, a, fg, s);
-    if (e == hipSuccess) e = launch_weiszfeld(a.Gm, count, iters, eps, a.sc.weights, s);
-    if (e == hipSuccess) e = launch_weighted_sum(X, count, d, ld, a.sc.weights, out, s);
+    AggWs a = carve_aggregator(ws, rs.count);
+    hipError_t e = gram_for(rs, a, fg, s);
+    if (e == hipSuccess) e = launch_weiszfeld(a.Gm, rs.count, iters, eps, a.sc.weights, s);
+    if (e == hipSuccess) e = launch_weighted_sum(rs, a.sc.weights, out, s);
     return status_of(e);
 }
 
@@ -206,6 +207,8 @@ size_t detox_workspace_bytes(int op, int64_t count, int64_t d, int64_t aux)
         if (aux < 1 || aux > kMaxCount) return 0;
         return filter_bytes(count) + aggregator_ws_bytes(aux);
     }
+    case DETOX_OP_BLOCK_MEAN:
+    case DETOX_OP_COORD_MEDIAN: return 0;
     default: return 0;
     }
 }
@@ -222,8 +225,8 @@ int detox_majority_filter(const float *G, int64_t n, int64_t d, int64_t ld, int 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner};
-    hipError_t e = launch_filter(p, false, false, nullptr, s);
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
+    hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, s);
     if (e == hipSuccess && Z)
         e = launch_block_mean(G, d, ld, winner, groups, groups, nullptr, Z, ldz, true, false, s);
     return status_of(e);
@@ -253,8 +256,8 @@ int detox_filter_block_mean(const float *G, int64_t n, int64_t d, int64_t ld, in
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner};
-    hipError_t e = launch_filter(p, true, false, nullptr, s);
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
+    hipError_t e = launch_filter(p, FilterWant::kMeans, nullptr, s);
     if (e == hipSuccess)
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     return status_of(e);
@@ -267,7 +270,7 @@ int robust_pairwise_sqdist(const float *X, int64_t count, int64_t d, int64_t ld,
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     AggWs a = carve_aggregator(ws, count);
-    hipError_t e = launch_gram(X, count, d, ld, a.partials, a.Gm, false, s);
+    hipError_t e = launch_gram(direct_rows(X, count, d, ld), a.partials, a.Gm, s);
     if (e == hipSuccess) e = launch_sqdist_from_gram(a.Gm, count, D, s);
     return status_of(e);
 }
@@ -280,7 +283,7 @@ int robust_multikrum(const float *X, int64_t count, int64_t d, int64_t ld, int f
         return DETOX_EINVAL;
     if (count < 2 * (int64_t)f + 3 || m < 1 || m > count - f) return DETOX_EPRECOND;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
-    return multikrum_impl(X, count, d, ld, f, m, out, selected, scores, ws, FusedGram{},
+    return multikrum_impl(direct_rows(X, count, d, ld), f, m, out, selected, scores, ws, FusedGram{},
                           static_cast<hipStream_t>(stream));
 }
 
@@ -291,7 +294,7 @@ int robust_bulyan(const float *X, int64_t count, int64_t d, int64_t ld, int f, f
         return DETOX_EINVAL;
     if (count < 4 * (int64_t)f + 3) return DETOX_EPRECOND;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
-    return bulyan_impl(X, count, d, ld, f, out, selected, ws, FusedGram{},
+    return bulyan_impl(direct_rows(X, count, d, ld), f, out, selected, ws, FusedGram{},
                        static_cast<hipStream_t>(stream));
 }
 
@@ -299,7 +302,8 @@ int robust_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, fl
                         void *stream)
 {
     if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount) return DETOX_EINVAL;
-    return status_of(launch_coord_median(X, count, d, ld, out, static_cast<hipStream_t>(stream)));
+    return status_of(launch_coord_median(direct_rows(X, count, d, ld), out, nullptr,
+                                         static_cast<hipStream_t>(stream)));
 }
 
 int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
@@ -308,7 +312,7 @@ int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
     if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount || iters < 0 || !(eps > 0.0))
         return DETOX_EINVAL;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
-    return geomedian_impl(X, count, d, ld, iters, eps, out, ws, FusedGram{},
+    return geomedian_impl(direct_rows(X, count, d, ld), iters, eps, out, ws, FusedGram{},
                           static_cast<hipStream_t>(stream));
 }
 
@@ -320,8 +324,10 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     int rc = check_filter_args(G, n, d, ld, r);
     if (rc) return rc;
     const int64_t groups = n / r;
-    if (!winner || !Zhat || !out || ldo < d || B < 1 || B > groups || B > kMaxCount || q < 0)
+    if (!winner || !out || (Zhat && ldo < d) || B < 1 || B > groups || B > kMaxCount || q < 0)
         return DETOX_EINVAL;
+    // without Zhat the aggregator reads votes (B = n/r) or re-forms the means of few vote groups
+    if (!Zhat && B != groups && (B > 8 || groups > kFusedMaxVotes)) return DETOX_EINVAL;
     if (agg < DETOX_AGG_MULTIKRUM || agg > DETOX_AGG_GEOMEDIAN) return DETOX_EINVAL;
     if (agg == DETOX_AGG_MULTIKRUM || agg == DETOX_AGG_BULYAN) {
         if (!selected) return DETOX_EINVAL;
@@ -341,27 +347,54 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     }
     if (agg == DETOX_AGG_GEOMEDIAN && (iters < 0 || !(eps > 0.0))) return DETOX_EINVAL;
     const size_t fbytes = filter_bytes(groups);
-    const size_t abytes = agg == DETOX_AGG_COORD_MEDIAN ? 0 : aggregator_ws_bytes(B);
+    const size_t abytes = aggregator_ws_bytes(B);
     if (!ws_ok(ws, ws_bytes, fbytes + abytes)) return DETOX_EWORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner};
-    FusedGram fg;
-    hipError_t e = launch_filter(p, true, agg != DETOX_AGG_COORD_MEDIAN, &fg.blocks, s);
-    fg.partials = fw.gram_partials;
-    fg.redo = fw.redo;
-    if (e == hipSuccess)
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, out};
+    // One pass over G.  With Zhat the block means are also written out; without it they exist
+    // only in registers during this pass and are re-formed from the winners where a later
+    // kernel needs them (that is the faster way on this chip).
+    FilterWant want = agg == DETOX_AGG_COORD_MEDIAN ? FilterWant::kMedian : FilterWant::kGram;
+    if (Zhat == nullptr && (B > 8 || groups > kFusedMaxVotes)) want = FilterWant::kVotes;   // B = n/r
+    FilterDone done;
+    hipError_t e = launch_filter(p, want, &done, s);
+    if (e == hipSuccess && Zhat != nullptr)   // redo the blocks that hold a vote without majority
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     if (e != hipSuccess) return status_of(e);
+
+    // The rows the aggregator works on: the stored block means, or the same values formed on
+    // the fly from the winners.
     void *aws = static_cast<char *>(ws) + fbytes;
+    RowSet rs = direct_rows(Zhat, B, d, ldo);
+    if (!Zhat) {
+        if (B == groups) {
+            // every vote its own block: the rows are the winner rows themselves
+            const int32_t *index = winner;
+            if (vote_perm) {
+                int32_t *table = carve_aggregator(aws, B).row_index;
+                e = launch_compose_index(winner, vote_perm, (int)B, table, s);
+                if (e != hipSuccess) return status_of(e);
+                index = table;
+            }
+            rs = RowSet{G, d, ld, (int)B, index, nullptr, nullptr, 0};
+        } else {
+            rs = RowSet{G, d, ld, (int)B, nullptr, winner, vote_perm, (int)groups};
+        }
+    }
+    FusedGram fg;
+    fg.partials = fw.gram_partials;
+    fg.blocks = done.gram_blocks;
+    fg.redo = fw.redo;
     switch (agg) {
-    case DETOX_AGG_MULTIKRUM:
-        return multikrum_impl(Zhat, B, d, ldo, f, m, out, selected, nullptr, aws, fg, s);
-    case DETOX_AGG_BULYAN: return bulyan_impl(Zhat, B, d, ldo, f, out, selected, aws, fg, s);
-    case DETOX_AGG_COORD_MEDIAN: return status_of(launch_coord_median(Zhat, B, d, ldo, out, s));
-    default: return geomedian_impl(Zhat, B, d, ldo, iters, eps, out, aws, fg, s);
+    case DETOX_AGG_MULTIKRUM: return multikrum_impl(rs, f, m, out, selected, nullptr, aws, fg, s);
+    case DETOX_AGG_BULYAN: return bulyan_impl(rs, f, out, selected, aws, fg, s);
+    case DETOX_AGG_COORD_MEDIAN:
+        // already written by the filter pass unless some group had no majority
+        return status_of(launch_coord_median(rs, out, done.median_written ? fw.redo : nullptr, s));
+    default: return geomedian_impl(rs, iters, eps, out, aws, fg, s);
     }
 }
 

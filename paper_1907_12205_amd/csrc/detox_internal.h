@@ -43,6 +43,22 @@ inline int row_vec_width(const void *base, int64_t ld)
     return 1;
 }
 
+// A set of logical rows handed to an aggregator (see rows.cuh for the device side).
+struct RowSet {
+    const float *base;          // the matrix the rows are read from
+    int64_t d, ld;
+    int count;                  // number of logical rows
+    const int32_t *index;       // dev or null: logical row b = row index[b] of base (-1: zeros)
+    const int32_t *winner;      // dev or null; non-null: logical row b = mean of the votes of
+    const int32_t *vote_perm;   //   vote group b of `count`, read through winner[] (n_votes node
+    int n_votes;                //   groups, optional vote order); index is ignored then
+    bool means() const { return winner != nullptr; }
+};
+inline RowSet direct_rows(const float *X, int64_t count, int64_t d, int64_t ld)
+{
+    return RowSet{X, d, ld, (int)count, nullptr, nullptr, nullptr, 0};
+}
+
 // ---- filter.hip ------------------------------------------------------------
 struct FilterParams {
     const float *G;
@@ -59,7 +75,7 @@ struct FilterParams {
     double *gram_partials;              // dev, kFusedMaxGrid x B(B+1)/2 (persistent kernel, B <= 8)
     int *redo;                          // dev, 1 word: set when some group has no majority
     int32_t *winner;                    // dev, n_votes
-    int dev = 0;
+    float *out;                         // dev, d: the coordinate-wise median (median mode only)
 };
 struct FilterWs {
     int *redo;
@@ -68,11 +84,20 @@ struct FilterWs {
 };
 size_t filter_ws_bytes(int64_t n_votes);
 FilterWs carve_filter_ws(void *ws, int64_t n_votes);
-// One pass over G: pair bits (and block means when mean is set), then winner[] and *redo.
-//   want_gram: also accumulate the Gram matrix of the block means when the persistent kernel
-//   runs with B <= 8; *fused_blocks then receives the number of partial slots written (else 0).
-hipError_t launch_filter(FilterParams p, bool mean, bool want_gram, int *fused_blocks,
-                         hipStream_t s);
+// What one pass over G should produce besides winner[] and *redo.
+enum class FilterWant {
+    kVotes,    // nothing else
+    kMeans,    // block means in Zhat (must be non-null)
+    kGram,     // block means (in Zhat if non-null) and, when B <= 8, the Gram matrix of the means
+    kMedian    // block means (in Zhat if non-null) and, when B <= 8, their coordinate-wise median
+};
+struct FilterDone {
+    int gram_blocks = 0;          // > 0: Gram partial slots written (kGram honoured)
+    bool median_written = false;  // kMedian honoured: `out` holds the median unless *redo
+};
+// kGram / kMedian with B > 8 (or more than kFusedMaxVotes groups) degrade to kMeans; then Zhat
+// must be non-null (hipErrorInvalidValue otherwise).
+hipError_t launch_filter(FilterParams p, FilterWant want, FilterDone *done, hipStream_t s);
 // Zhat_b = mean of the votes of block b, read through `winner`.
 //   copy: blocks of one vote copied bit for bit; only_bad: touch only blocks holding winner = -1.
 hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_t *winner,
@@ -81,15 +106,12 @@ hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_
 
 // ---- gram.hip --------------------------------------------------------------
 size_t gram_partial_bytes(int64_t count);
-// Gram matrix Gm[a][b] = <x_a, x_b> (count x count doubles, full, symmetric).
-//   high_precision: products and sums in fp64 throughout (count <= 8 always runs this way).
-hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, void *partials,
-                       double *Gm, bool high_precision, hipStream_t s);
+// Gram matrix Gm[a][b] = <x_a, x_b> of the logical rows (count x count doubles, full, symmetric).
+hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s);
 // count <= 8 only: Gm from the partials the persistent filter kernel accumulated
 // (fused_partials, fused_blocks slots), unless *redo is set on the device, in which case the
-// Gram matrix is recomputed from X.  No host round trip either way.
-hipError_t launch_gram_after_filter(const float *X, int64_t count, int64_t d, int64_t ld,
-                                    void *partials, const double *fused_partials,
+// Gram matrix is recomputed from the rows.  No host round trip either way.
+hipError_t launch_gram_after_filter(const RowSet &rs, void *partials, const double *fused_partials,
                                     int fused_blocks, const int *redo, double *Gm, hipStream_t s);
 
 // ---- select.hip ------------------------------------------------------------
@@ -108,18 +130,19 @@ hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const Se
                                 int32_t *selected, hipStream_t s);
 hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double eps,
                             double *weights, hipStream_t s);
-// out[c] = fp32( sum_i (double) X[rows[i]][c] / m ), rows read from device memory in list order.
-hipError_t launch_rows_mean(const float *X, int64_t count, int64_t d, int64_t ld,
-                            const int32_t *rows, int m, float *out, hipStream_t s);
-// out[c] = fp32( sum_j weights[j] * (double) X[j][c] ).
-hipError_t launch_weighted_sum(const float *X, int64_t count, int64_t d, int64_t ld,
-                               const double *weights, float *out, hipStream_t s);
+// index[b] = winner[vote_perm[b]]: the row table of the votes taken in vote order.
+hipError_t launch_compose_index(const int32_t *winner, const int32_t *vote_perm, int n,
+                                int32_t *index, hipStream_t s);
+// out[c] = fp32( sum_i (double) row[rows[i]][c] / m ), logical rows listed in device memory.
+hipError_t launch_rows_mean(const RowSet &rs, const int32_t *rows, int m, float *out, hipStream_t s);
+// out[c] = fp32( sum_j weights[j] * (double) row[j][c] ) over all logical rows.
+hipError_t launch_weighted_sum(const RowSet &rs, const double *weights, float *out, hipStream_t s);
 
 // ---- sortnet.hip -----------------------------------------------------------
-hipError_t launch_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, float *out,
-                               hipStream_t s);
-// Per coordinate: median of the theta listed rows, mean of the beta values closest to it.
-hipError_t launch_bulyan_trim(const float *X, int64_t count, int64_t d, int64_t ld,
-                              const int32_t *rows, int theta, int beta, float *out, hipStream_t s);
+// Coordinate-wise median of all logical rows.  run_if (dev, may be null): skip unless *run_if.
+hipError_t launch_coord_median(const RowSet &rs, float *out, const int *run_if, hipStream_t s);
+// Per coordinate: median of the theta listed logical rows, mean of the beta values closest to it.
+hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int theta, int beta, float *out,
+                              hipStream_t s);
 
 }  // namespace detox

@@ -17,64 +17,12 @@
 //   filter_kernel    : grid.y = vote group; any B and any number of groups; pair bits are merged
 //                      into one zero-initialised word per group with integer atomic ORs.
 #include <cstdlib>
-#include "detox_internal.h"
+
+#include "rows.cuh"
+#include "sortnet.cuh"
 
 namespace detox {
 namespace {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-template <int VEC>
-__device__ inline void load_bits(const float *p, uint32_t (&w)[VEC])
-{
-    if constexpr (VEC == 4) {
-        const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-        w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
-    } else if constexpr (VEC == 2) {
-        const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
-        w[0] = t.x, w[1] = t.y;
-    } else {
-        w[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
-    }
-}
-
-// Loads `valid` (<= VEC) words starting at p; the rest read as zero.
-template <int VEC>
-__device__ inline void load_bits_guarded(const float *p, int valid, uint32_t (&w)[VEC])
-{
-    if (valid == VEC) {
-        load_bits<VEC>(p, w);
-    } else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i)
-            w[i] = i < valid ? reinterpret_cast<const uint32_t *>(p)[i] : 0u;
-    }
-}
-
-template <int VEC>
-__device__ inline void store_floats_guarded(float *p, int valid, const float (&v)[VEC])
-{
-    if (valid == VEC) {
-        if constexpr (VEC == 4) {
-#ifdef DETOX_NT_STORE
-            typedef float f32x4 __attribute__((ext_vector_type(4)));
-            const f32x4 t = {v[0], v[1], v[2], v[3]};
-            __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(p));
-#else
-            *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-#endif
-        }
-        else if constexpr (VEC == 2)
-            *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
-        else
-            p[0] = v[0];
-    } else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i)
-            if (i < valid) p[i] = v[i];
-    }
-}
 
 // Loads the R member rows of node group j at this thread's columns (zeros where invalid) and
 // returns the pairs that differ there.
@@ -86,7 +34,7 @@ __device__ inline unsigned long long load_group(const FilterParams &p, int64_t j
     for (int k = 0; k < R; ++k) {
         const int64_t row = p.group_rows ? p.group_rows[j * R + k] : j * R + k;
         if (valid > 0) {
-            load_bits_guarded<VEC>(p.G + row * p.ld + col, valid, x[k]);
+            load_words<VEC>(p.G + row * p.ld + col, valid, x[k]);
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) x[k][i] = 0u;
@@ -168,29 +116,32 @@ __device__ inline int32_t winner_from_bits(unsigned long long bits, const int32_
     return win;
 }
 
-__device__ inline double wave_sum_fixed(double v)
-{
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
-    return v;
-}
+// ---------------------------------------------------------------------------------------
+// Persistent kernel over all vote groups.  MODE:
+//   kFilterOnly : pair bits only.
+//   kMeans      : + block means written to Zhat (any B, read from the parameters; NB = 0).
+//   kGram       : + block means kept in registers (NB = B <= 8, compile time), their Gram matrix
+//                 accumulated in fp64 into per-workgroup partials; Zhat written only if non-null.
+//   kMedian     : + block means kept in registers (NB = B <= 8), their coordinate-wise median
+//                 written to `out` (the whole DETOX-median step in one pass over G); Zhat
+//                 written only if non-null.
+// ---------------------------------------------------------------------------------------
+enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3 };
 
-// ---------------------------------------------------------------------------------------
-// Persistent kernel over all vote groups.  NB = number of vote groups when GRAM (compile time,
-// <= 8), otherwise 0 and B is read from the parameters.
-// ---------------------------------------------------------------------------------------
-template <int R, int VEC, int NB, bool MEAN>
+template <int R, int VEC, int NB, int MODE>
 __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
 {
-    constexpr bool GRAM = NB > 0;
-    constexpr int NP = GRAM ? NB * (NB + 1) / 2 : 1;
+    constexpr bool MEAN = MODE != kFilterOnly;
+    constexpr bool REGS = MODE == kGram || MODE == kMedian;   // means of all blocks in registers
+    constexpr int NP = MODE == kGram ? NB * (NB + 1) / 2 : 1;
+    static_assert(!REGS || NB > 0, "register modes need the block count at compile time");
     __shared__ unsigned long long sbits[kFusedMaxVotes];
     __shared__ double red[kBlock / kWave][NP];
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock) sbits[j] = 0ull;
     __syncthreads();
 
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t B = GRAM ? NB : p.B;
+    const int64_t B = REGS ? NB : p.B;
     double gacc[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) gacc[i] = 0.0;
@@ -200,7 +151,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
         const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
         const int64_t left = p.d - col;
         const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
-        // one vote group: votes, pair bits, and (MEAN) its mean written to Zhat
+        // one vote group: votes, pair bits, and (MEAN) its mean
         auto do_block = [&](int64_t b, float (&acc)[VEC]) {
             const int64_t lo = (b * p.n_votes) / B, hi = ((b + 1) * p.n_votes) / B;
 #pragma unroll
@@ -220,18 +171,19 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
             if constexpr (MEAN) {
                 const float size = (float)(hi - lo);
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[i] = (p.dev & 2) ? acc[i] * (1.0f / size) : __fdiv_rn(acc[i], size);
-                if (valid > 0 && !(p.dev & 1)) store_floats_guarded<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
+                for (int i = 0; i < VEC; ++i) acc[i] = __fdiv_rn(acc[i], size);
+                if (p.Zhat != nullptr && valid > 0)
+                    store_floats<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
             }
         };
-        float z[GRAM ? NB : 1][VEC];
-        if constexpr (GRAM) {
+        float z[REGS ? NB : 1][VEC];
+        if constexpr (REGS) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) do_block(b, z[b]);
         } else {
             for (int64_t b = 0; b < B; ++b) do_block(b, z[0]);
         }
-        if constexpr (GRAM) {
+        if constexpr (MODE == kGram) {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
                 double zd[NB];
@@ -244,11 +196,23 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
                     for (int c = a; c < NB; ++c, ++pair) gacc[pair] = fma(zd[a], zd[c], gacc[pair]);
             }
         }
+        if constexpr (MODE == kMedian) {
+            uint32_t k[NB][VEC];
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) k[a][i] = order_key(__float_as_uint(z[a][i]));
+            sort_keys<NB, VEC>(k);
+            float med[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) med[i] = median_of_sorted<NB, VEC>(k, i);
+            if (valid > 0) store_floats<VEC>(p.out + col, valid, med);
+        }
     }
     __syncthreads();
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock)
         p.flag_partials[(int64_t)blockIdx.x * p.n_votes + j] = sbits[j];
-    if constexpr (GRAM) {
+    if constexpr (MODE == kGram) {
         const int wave = threadIdx.x / kWave;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
@@ -343,7 +307,7 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(FilterParams p)
             const float size = (float)(hi - lo);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] = __fdiv_rn(acc[i], size);
-            store_floats_guarded<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
+            store_floats<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
         }
     }
 }
@@ -388,7 +352,7 @@ __global__ __launch_bounds__(kBlock) void block_mean_kernel(const float *G, int6
             const int32_t w = winner[vote_perm ? vote_perm[pos] : pos];
             uint32_t x[VEC];
             if (w >= 0) {
-                load_bits_guarded<VEC>(G + (int64_t)w * ld + col, valid, x);
+                load_words<VEC>(G + (int64_t)w * ld + col, valid, x);
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) x[i] = 0u;
@@ -403,39 +367,47 @@ __global__ __launch_bounds__(kBlock) void block_mean_kernel(const float *G, int6
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] = __fdiv_rn(acc[i], size);
         }
-        store_floats_guarded<VEC>(Zhat + b * ldo + col, valid, acc);
+        store_floats<VEC>(Zhat + b * ldo + col, valid, acc);
     }
 }
 
 // ---- dispatch -----------------------------------------------------------------------------
 template <int R, int VEC, int NB>
-hipError_t launch_fused_rvn(const FilterParams &p, bool mean, int grid, hipStream_t s)
+hipError_t launch_fused_rvn(const FilterParams &p, int mode, int grid, hipStream_t s)
 {
-    if (mean) {
-        TraceScope t(NB > 0 ? "filter_block_mean_gram" : "filter_block_mean", s);
-        fused_all_kernel<R, VEC, NB, true><<<grid, kBlock, 0, s>>>(p);
-    } else {
-        if constexpr (NB == 0) {
+    if constexpr (NB == 0) {
+        if (mode == kMeans) {
+            TraceScope t("filter_block_mean", s);
+            fused_all_kernel<R, VEC, 0, kMeans><<<grid, kBlock, 0, s>>>(p);
+        } else {
             TraceScope t("filter", s);
-            fused_all_kernel<R, VEC, 0, false><<<grid, kBlock, 0, s>>>(p);
+            fused_all_kernel<R, VEC, 0, kFilterOnly><<<grid, kBlock, 0, s>>>(p);
+        }
+    } else {
+        if (mode == kMedian) {
+            TraceScope t("filter_block_mean_median", s);
+            fused_all_kernel<R, VEC, NB, kMedian><<<grid, kBlock, 0, s>>>(p);
+        } else {
+            TraceScope t("filter_block_mean_gram", s);
+            fused_all_kernel<R, VEC, NB, kGram><<<grid, kBlock, 0, s>>>(p);
         }
     }
     return hipGetLastError();
 }
 
 template <int R, int VEC>
-hipError_t launch_fused_rv(const FilterParams &p, bool mean, int nb, int grid, hipStream_t s)
+hipError_t launch_fused_rv(const FilterParams &p, int mode, int nb, int grid, hipStream_t s)
 {
     switch (nb) {
-    case 0: return launch_fused_rvn<R, VEC, 0>(p, mean, grid, s);
-    case 1: return launch_fused_rvn<R, VEC, 1>(p, mean, grid, s);
-    case 2: return launch_fused_rvn<R, VEC, 2>(p, mean, grid, s);
-    case 3: return launch_fused_rvn<R, VEC, 3>(p, mean, grid, s);
-    case 4: return launch_fused_rvn<R, VEC, 4>(p, mean, grid, s);
-    case 5: return launch_fused_rvn<R, VEC, 5>(p, mean, grid, s);
-    case 6: return launch_fused_rvn<R, VEC, 6>(p, mean, grid, s);
-    case 7: return launch_fused_rvn<R, VEC, 7>(p, mean, grid, s);
-    case 8: return launch_fused_rvn<R, VEC, 8>(p, mean, grid, s);
+    case 0: return launch_fused_rvn<R, VEC, 0>(p, mode, grid, s);
+    case 1: return launch_fused_rvn<R, VEC, 1>(p, mode, grid, s);
+    case 2: return launch_fused_rvn<R, VEC, 2>(p, mode, grid, s);
+    case 3: return launch_fused_rvn<R, VEC, 3>(p, mode, grid, s);
+    case 4: return launch_fused_rvn<R, VEC, 4>(p, mode, grid, s);
+    case 5: return launch_fused_rvn<R, VEC, 5>(p, mode, grid, s);
+    case 6: return launch_fused_rvn<R, VEC, 6>(p, mode, grid, s);
+    case 7: return launch_fused_rvn<R, VEC, 7>(p, mode, grid, s);
+    case 8: return launch_fused_rvn<R, VEC, 8>(p, mode, grid, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -456,13 +428,13 @@ hipError_t launch_general_rv(const FilterParams &p, bool mean, hipStream_t s)
 }
 
 template <int R>
-hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int nb, int grid, int vec,
+hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int mode, int nb, int grid, int vec,
                     hipStream_t s)
 {
     if (fused) {
-        if (vec == 4) return launch_fused_rv<R, 4>(p, mean, nb, grid, s);
-        if (vec == 2) return launch_fused_rv<R, 2>(p, mean, nb, grid, s);
-        return launch_fused_rv<R, 1>(p, mean, nb, grid, s);
+        if (vec == 4) return launch_fused_rv<R, 4>(p, mode, nb, grid, s);
+        if (vec == 2) return launch_fused_rv<R, 2>(p, mode, nb, grid, s);
+        return launch_fused_rv<R, 1>(p, mode, nb, grid, s);
     }
     if (vec == 4) return launch_general_rv<R, 4>(p, mean, s);
     if (vec == 2) return launch_general_rv<R, 2>(p, mean, s);
@@ -502,26 +474,35 @@ FilterWs carve_filter_ws(void *ws, int64_t n_votes)
     return w;
 }
 
-hipError_t launch_filter(FilterParams p, bool mean, bool want_gram, int *fused_blocks,
-                         hipStream_t s)
+hipError_t launch_filter(FilterParams p, FilterWant want, FilterDone *done, hipStream_t s)
 {
+    const bool mean = want != FilterWant::kVotes;
     int vec = row_vec_width(p.G, p.ld);
-    if (mean) {
+    if (p.Zhat) {
         const int vo = row_vec_width(p.Zhat, p.ldo);
         vec = vo < vec ? vo : vec;
     }
-    if (const char *e = getenv("DETOX_DEV_FLAGS")) p.dev = atoi(e);
+    if (want == FilterWant::kMedian) {
+        const int vo = row_vec_width(p.out, 4);
+        vec = vo < vec ? vo : vec;
+    }
     const int64_t chunks = (p.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     // The persistent kernel serves the paper's regime: up to kFusedMaxVotes node groups cut into
     // few vote groups.  A pure filter is the same kernel with every group its own block.
-    const bool fused = p.n_votes <= kFusedMaxVotes && (!mean || p.B <= 64);
-    const int nb = (fused && mean && want_gram && p.B <= 8) ? (int)p.B : 0;
-    if (fused_blocks) *fused_blocks = 0;
+    const bool fused = p.n_votes <= kFusedMaxVotes;
+    int mode = kFilterOnly, nb = 0;
+    if (mean) {
+        mode = kMeans;
+        if (fused && p.B <= 8 && want == FilterWant::kGram) mode = kGram, nb = (int)p.B;
+        if (fused && p.B <= 8 && want == FilterWant::kMedian) mode = kMedian, nb = (int)p.B;
+    }
+    // without a register mode the means must go to memory
+    if (mode == kMeans && p.Zhat == nullptr) return hipErrorInvalidValue;
+    if (done) *done = FilterDone{};
     hipError_t e;
     int grid = 0;
     if (fused) {
         grid = num_compute_units() * (p.n_votes <= 128 ? 4 : 2);
-        if (const char *e = getenv("DETOX_DEV_GRID_MULT")) grid = num_compute_units() * atoi(e);
         if (grid > kFusedMaxGrid) grid = kFusedMaxGrid;
         if (grid > chunks) grid = (int)chunks;
     } else {
@@ -534,17 +515,17 @@ hipError_t launch_filter(FilterParams p, bool mean, bool want_gram, int *fused_b
         if (e != hipSuccess) return e;
     }
     switch (p.r) {
-    case 1: e = launch_r<1>(p, mean, fused, nb, grid, vec, s); break;
-    case 2: e = launch_r<2>(p, mean, fused, nb, grid, vec, s); break;
-    case 3: e = launch_r<3>(p, mean, fused, nb, grid, vec, s); break;
-    case 4: e = launch_r<4>(p, mean, fused, nb, grid, vec, s); break;
-    case 5: e = launch_r<5>(p, mean, fused, nb, grid, vec, s); break;
-    case 6: e = launch_r<6>(p, mean, fused, nb, grid, vec, s); break;
-    case 7: e = launch_r<7>(p, mean, fused, nb, grid, vec, s); break;
-    case 8: e = launch_r<8>(p, mean, fused, nb, grid, vec, s); break;
-    case 9: e = launch_r<9>(p, mean, fused, nb, grid, vec, s); break;
-    case 10: e = launch_r<10>(p, mean, fused, nb, grid, vec, s); break;
-    case 11: e = launch_r<11>(p, mean, fused, nb, grid, vec, s); break;
+    case 1: e = launch_r<1>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 2: e = launch_r<2>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 3: e = launch_r<3>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 4: e = launch_r<4>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 5: e = launch_r<5>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 6: e = launch_r<6>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 7: e = launch_r<7>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 8: e = launch_r<8>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 9: e = launch_r<9>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 10: e = launch_r<10>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 11: e = launch_r<11>(p, mean, fused, mode, nb, grid, vec, s); break;
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
@@ -552,7 +533,10 @@ hipError_t launch_filter(FilterParams p, bool mean, bool want_gram, int *fused_b
     if (fused) {
         finalize_partials_kernel<<<1, 1024, 0, s>>>(p.flag_partials, grid, p.group_rows, p.r,
                                                     (int)p.n_votes, p.winner, p.redo);
-        if (fused_blocks && nb > 0) *fused_blocks = grid;
+        if (done) {
+            done->gram_blocks = mode == kGram ? grid : 0;
+            done->median_written = mode == kMedian;
+        }
     } else {
         filter_finalize_kernel<<<(unsigned)((p.n_votes + 255) / 256), 256, 0, s>>>(
             p.flags, p.group_rows, p.r, p.n_votes, p.winner, p.redo);

@@ -8,7 +8,7 @@
 // Either way every workgroup / wavefront writes its partial sums to the workspace and a second
 // kernel adds them in a fixed order in fp64.  No atomics: results repeat bit for bit, and rows
 // that are bit-identical produce bit-identical Gram entries (same products, same order).
-#include "detox_internal.h"
+#include "rows.cuh"
 
 namespace detox {
 namespace {
@@ -22,42 +22,16 @@ __host__ __device__ constexpr int tiles_for(int T) { return T * (T + 1) / 2; }
 // ---------------------------------------------------------------------------------------
 // count <= 8: fp64 on the vector ALUs
 // ---------------------------------------------------------------------------------------
-template <int VEC>
-__device__ inline void load_row_guarded(const float *p, int valid, float (&w)[VEC])
-{
-    if (valid == VEC) {
-        if constexpr (VEC == 4) {
-            const float4 t = *reinterpret_cast<const float4 *>(p);
-            w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
-        } else if constexpr (VEC == 2) {
-            const float2 t = *reinterpret_cast<const float2 *>(p);
-            w[0] = t.x, w[1] = t.y;
-        } else {
-            w[0] = p[0];
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) w[i] = i < valid ? p[i] : 0.0f;
-    }
-}
-
-__device__ inline double wave_sum_fixed(double v)
-{
-    // fixed butterfly: the same tree for every call, so equal inputs give equal sums
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
-    return v;
-}
-
-template <int C, int VEC>
-__global__ __launch_bounds__(kBlock) void gram_small_kernel(const float *X, int64_t d, int64_t ld,
-                                                            double *partials, const int *run_if)
+template <int C, int VEC, bool MEANS>
+__global__ __launch_bounds__(kBlock) void gram_small_kernel(RowSet rs, double *partials,
+                                                            const int *run_if)
 {
     constexpr int NP = C * (C + 1) / 2;
     if (run_if && *run_if == 0) return;   // uniform: the caller's partials are valid already
     double acc[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) acc[i] = 0.0;
+    const int64_t d = rs.d;
     const int64_t chunks = (d + (int64_t)kBlock * VEC - 1) / ((int64_t)kBlock * VEC);
     for (int64_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
         const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
@@ -66,7 +40,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(const float *X, int6
         const int valid = left >= VEC ? VEC : (int)left;
         float x[C][VEC];
 #pragma unroll
-        for (int a = 0; a < C; ++a) load_row_guarded<VEC>(X + a * ld + col, valid, x[a]);
+        for (int a = 0; a < C; ++a) row_load<MEANS, VEC>(rs, a, col, valid, x[a]);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
             double xd[C];
@@ -140,9 +114,13 @@ __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double 
 // 16-byte load and the four components serve four successive MFMA steps.  The accumulator of
 // tile (ti, tj) holds C[4*(l/16)+v][l%16] in component v of lane l.
 // ---------------------------------------------------------------------------------------
+// rowp[t]: this lane's row of row tile t; zero[t]: that logical row is the zero vector (a vote
+// without majority), in which case the loaded values are discarded.  Plain (temporal) loads:
+// the four lanes of a row and the two halves of a step share 128-byte lines through the caches.
 template <int T, bool ALIGNED>
-__device__ inline void gram_load_step(const float *const (&rowp)[T], int64_t c0, int kk,
-                                      int64_t d, bool guarded, float4 (&buf)[T][2])
+__device__ inline void gram_load_step(const float *const (&rowp)[T], const bool (&zero)[T],
+                                      int64_t c0, int kk, int64_t d, bool guarded,
+                                      float4 (&buf)[T][2])
 {
 #pragma unroll
     for (int t = 0; t < T; ++t)
@@ -150,16 +128,18 @@ __device__ inline void gram_load_step(const float *const (&rowp)[T], int64_t c0,
         for (int u = 0; u < 2; ++u) {
             const int64_t c = c0 + 16 * u + 4 * kk;
             const float *q = rowp[t] + c;
+            float4 v;
             if (!guarded) {
                 if constexpr (ALIGNED) {
-                    buf[t][u] = *reinterpret_cast<const float4 *>(q);
+                    v = *reinterpret_cast<const float4 *>(q);
                 } else {
-                    buf[t][u] = make_float4(q[0], q[1], q[2], q[3]);
+                    v = make_float4(q[0], q[1], q[2], q[3]);
                 }
             } else {
-                buf[t][u] = make_float4(c + 0 < d ? q[0] : 0.0f, c + 1 < d ? q[1] : 0.0f,
-                                        c + 2 < d ? q[2] : 0.0f, c + 3 < d ? q[3] : 0.0f);
+                v = make_float4(c + 0 < d ? q[0] : 0.0f, c + 1 < d ? q[1] : 0.0f,
+                                c + 2 < d ? q[2] : 0.0f, c + 3 < d ? q[3] : 0.0f);
             }
+            buf[t][u] = zero[t] ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : v;
         }
 }
 
@@ -186,9 +166,10 @@ __device__ inline void gram_mfma_step(const float4 (&buf)[T][2], f32x4 (&acc)[ti
 }
 
 template <int T, bool ALIGNED>
-__global__ __launch_bounds__(kBlock) void gram_mfma_kernel(const float *X, int count, int64_t d,
-                                                           int64_t ld, float *partials)
+__global__ __launch_bounds__(kBlock) void gram_mfma_kernel(RowSet rs, float *partials)
 {
+    const int count = rs.count;
+    const int64_t d = rs.d;
     constexpr int NT = tiles_for(T);
     const int lane = threadIdx.x & (kWave - 1);
     const int i = lane & 15, kk = lane >> 4;
@@ -196,11 +177,14 @@ __global__ __launch_bounds__(kBlock) void gram_mfma_kernel(const float *X, int c
     const int64_t waves = (int64_t)gridDim.x * (kBlock / kWave);
 
     const float *rowp[T];
+    bool zero[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         int row = 16 * t + i;
         row = row < count ? row : count - 1;   // padded rows re-read the last row; never reported
-        rowp[t] = X + (int64_t)row * ld;
+        const int64_t phys = rs.index ? (int64_t)rs.index[row] : (int64_t)row;
+        zero[t] = phys < 0;
+        rowp[t] = rs.base + (phys < 0 ? 0 : phys) * rs.ld;
     }
     f32x4 acc[NT];
 #pragma unroll
@@ -209,10 +193,10 @@ __global__ __launch_bounds__(kBlock) void gram_mfma_kernel(const float *X, int c
     const int64_t full_steps = d / 32;   // 32 columns per step
     float4 cur[T][2], nxt[T][2];
     int64_t step = wave;
-    if (step < full_steps) gram_load_step<T, ALIGNED>(rowp, step * 32, kk, d, false, cur);
+    if (step < full_steps) gram_load_step<T, ALIGNED>(rowp, zero, step * 32, kk, d, false, cur);
     while (step < full_steps) {
         const int64_t next = step + waves;
-        if (next < full_steps) gram_load_step<T, ALIGNED>(rowp, next * 32, kk, d, false, nxt);
+        if (next < full_steps) gram_load_step<T, ALIGNED>(rowp, zero, next * 32, kk, d, false, nxt);
         gram_mfma_step<T>(cur, acc);
 #pragma unroll
         for (int t = 0; t < T; ++t)
@@ -222,7 +206,7 @@ __global__ __launch_bounds__(kBlock) void gram_mfma_kernel(const float *X, int c
     }
     // the ragged last step (d % 32 columns) goes to one wavefront
     if ((d % 32) != 0 && wave == full_steps % waves) {
-        gram_load_step<T, ALIGNED>(rowp, full_steps * 32, kk, d, true, cur);
+        gram_load_step<T, ALIGNED>(rowp, zero, full_steps * 32, kk, d, true, cur);
         gram_mfma_step<T>(cur, acc);
     }
     float *out = partials + wave * (int64_t)(NT * 256);
@@ -273,50 +257,57 @@ __global__ void gram_mfma_reduce2_kernel(const double *slices, int T, int count,
 }
 
 template <int C>
-hipError_t launch_small(const float *X, int64_t d, int64_t ld, double *partials, int grid, int vec,
-                        const int *run_if, hipStream_t s)
+hipError_t launch_small(const RowSet &rs, double *partials, int grid, int vec, const int *run_if,
+                        hipStream_t s)
 {
     TraceScope t(run_if ? "gram_f64_if_redo" : "gram_f64", s);
+#define DETOX_GS(V)                                                                               \
+    do {                                                                                          \
+        if (rs.means())                                                                           \
+            gram_small_kernel<C, V, true><<<grid, kBlock, 0, s>>>(rs, partials, run_if);          \
+        else                                                                                      \
+            gram_small_kernel<C, V, false><<<grid, kBlock, 0, s>>>(rs, partials, run_if);         \
+    } while (0)
     if (vec == 4)
-        gram_small_kernel<C, 4><<<grid, kBlock, 0, s>>>(X, d, ld, partials, run_if);
+        DETOX_GS(4);
     else if (vec == 2)
-        gram_small_kernel<C, 2><<<grid, kBlock, 0, s>>>(X, d, ld, partials, run_if);
+        DETOX_GS(2);
     else
-        gram_small_kernel<C, 1><<<grid, kBlock, 0, s>>>(X, d, ld, partials, run_if);
+        DETOX_GS(1);
+#undef DETOX_GS
     return hipGetLastError();
 }
 
-hipError_t launch_small_any(const float *X, int64_t count, int64_t d, int64_t ld, double *pp,
-                            const int *run_if, int *grid_out, hipStream_t s)
+hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int *grid_out,
+                            hipStream_t s)
 {
-    const int vec = row_vec_width(X, ld);
-    const int64_t chunks = (d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
+    const int vec = row_vec_width(rs.base, rs.ld);
+    const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     int grid = num_compute_units() * 8;
     if (grid > kMaxGramWaves) grid = kMaxGramWaves;
     if (grid > chunks) grid = (int)chunks;
     *grid_out = grid;
-    switch (count) {
-    case 1: return launch_small<1>(X, d, ld, pp, grid, vec, run_if, s);
-    case 2: return launch_small<2>(X, d, ld, pp, grid, vec, run_if, s);
-    case 3: return launch_small<3>(X, d, ld, pp, grid, vec, run_if, s);
-    case 4: return launch_small<4>(X, d, ld, pp, grid, vec, run_if, s);
-    case 5: return launch_small<5>(X, d, ld, pp, grid, vec, run_if, s);
-    case 6: return launch_small<6>(X, d, ld, pp, grid, vec, run_if, s);
-    case 7: return launch_small<7>(X, d, ld, pp, grid, vec, run_if, s);
-    case 8: return launch_small<8>(X, d, ld, pp, grid, vec, run_if, s);
+    switch (rs.count) {
+    case 1: return launch_small<1>(rs, pp, grid, vec, run_if, s);
+    case 2: return launch_small<2>(rs, pp, grid, vec, run_if, s);
+    case 3: return launch_small<3>(rs, pp, grid, vec, run_if, s);
+    case 4: return launch_small<4>(rs, pp, grid, vec, run_if, s);
+    case 5: return launch_small<5>(rs, pp, grid, vec, run_if, s);
+    case 6: return launch_small<6>(rs, pp, grid, vec, run_if, s);
+    case 7: return launch_small<7>(rs, pp, grid, vec, run_if, s);
+    case 8: return launch_small<8>(rs, pp, grid, vec, run_if, s);
     default: return hipErrorInvalidValue;
     }
 }
 
 template <int T>
-hipError_t launch_mfma(const float *X, int count, int64_t d, int64_t ld, float *partials, int grid,
-                       bool aligned, hipStream_t s)
+hipError_t launch_mfma(const RowSet &rs, float *partials, int grid, bool aligned, hipStream_t s)
 {
     TraceScope t("gram_mfma_f32", s);
     if (aligned)
-        gram_mfma_kernel<T, true><<<grid, kBlock, 0, s>>>(X, count, d, ld, partials);
+        gram_mfma_kernel<T, true><<<grid, kBlock, 0, s>>>(rs, partials);
     else
-        gram_mfma_kernel<T, false><<<grid, kBlock, 0, s>>>(X, count, d, ld, partials);
+        gram_mfma_kernel<T, false><<<grid, kBlock, 0, s>>>(rs, partials);
     return hipGetLastError();
 }
 
@@ -330,16 +321,17 @@ size_t gram_partial_bytes(int64_t count)
            (size_t)kReduceSlices * (size_t)tiles_for(T) * 256 * sizeof(double);
 }
 
-hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, void *partials,
-                       double *Gm, bool /*high_precision*/, hipStream_t s)
+hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s)
 {
+    if (rs.means() && rs.count > 8) return hipErrorInvalidValue;   // MFMA path reads rows only
     const int cus = num_compute_units();
-    const int vec = row_vec_width(X, ld);
+    const int vec = row_vec_width(rs.base, rs.ld);
+    const int64_t count = rs.count, d = rs.d;
     hipError_t e;
     if (count <= 8) {
         double *pp = static_cast<double *>(partials);
         int grid = 0;
-        e = launch_small_any(X, count, d, ld, pp, nullptr, &grid, s);
+        e = launch_small_any(rs, pp, nullptr, &grid, s);
         if (e != hipSuccess) return e;
         const int np = (int)(count * (count + 1) / 2);
         TraceScope t("gram_reduce", s);
@@ -355,14 +347,14 @@ hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, voi
     float *pp = static_cast<float *>(partials);
     const bool aligned = vec == 4;
     switch (T) {
-    case 1: e = launch_mfma<1>(X, (int)count, d, ld, pp, grid, aligned, s); break;
-    case 2: e = launch_mfma<2>(X, (int)count, d, ld, pp, grid, aligned, s); break;
-    case 3: e = launch_mfma<3>(X, (int)count, d, ld, pp, grid, aligned, s); break;
-    case 4: e = launch_mfma<4>(X, (int)count, d, ld, pp, grid, aligned, s); break;
-    case 5: e = launch_mfma<5>(X, (int)count, d, ld, pp, grid, aligned, s); break;
-    case 6: e = launch_mfma<6>(X, (int)count, d, ld, pp, grid, aligned, s); break;
-    case 7: e = launch_mfma<7>(X, (int)count, d, ld, pp, grid, aligned, s); break;
-    case 8: e = launch_mfma<8>(X, (int)count, d, ld, pp, grid, aligned, s); break;
+    case 1: e = launch_mfma<1>(rs, pp, grid, aligned, s); break;
+    case 2: e = launch_mfma<2>(rs, pp, grid, aligned, s); break;
+    case 3: e = launch_mfma<3>(rs, pp, grid, aligned, s); break;
+    case 4: e = launch_mfma<4>(rs, pp, grid, aligned, s); break;
+    case 5: e = launch_mfma<5>(rs, pp, grid, aligned, s); break;
+    case 6: e = launch_mfma<6>(rs, pp, grid, aligned, s); break;
+    case 7: e = launch_mfma<7>(rs, pp, grid, aligned, s); break;
+    case 8: e = launch_mfma<8>(rs, pp, grid, aligned, s); break;
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
@@ -381,14 +373,14 @@ hipError_t launch_gram(const float *X, int64_t count, int64_t d, int64_t ld, voi
     return hipGetLastError();
 }
 
-hipError_t launch_gram_after_filter(const float *X, int64_t count, int64_t d, int64_t ld,
-                                    void *partials, const double *fused_partials,
+hipError_t launch_gram_after_filter(const RowSet &rs, void *partials, const double *fused_partials,
                                     int fused_blocks, const int *redo, double *Gm, hipStream_t s)
 {
+    const int64_t count = rs.count;
     if (count < 1 || count > 8) return hipErrorInvalidValue;
     double *pp = static_cast<double *>(partials);
     int grid = 0;
-    hipError_t e = launch_small_any(X, count, d, ld, pp, redo, &grid, s);   // runs only if *redo
+    hipError_t e = launch_small_any(rs, pp, redo, &grid, s);   // runs only if *redo
     if (e != hipSuccess) return e;
     const int np = (int)(count * (count + 1) / 2);
     TraceScope t("gram_reduce", s);

@@ -1,0 +1,120 @@
+// Device-side access to the logical rows an aggregator works on, and the small load / store
+// helpers shared by the streaming kernels.
+//
+// A RowSet is one of
+//   rows        : logical row b is row index[b] of `base` (index == nullptr: row b; an index of
+//                 -1 stands for the zero vector, which is what a vote without majority is), or
+//   block means : (winner != nullptr) logical row b is the mean of the votes of vote group b,
+//                 formed on the fly from the winners of the filtering step (Algorithm 2 with
+//                 A0 = mean) with exactly the arithmetic of the block-mean kernel: fp32 adds in
+//                 vote order, one fp32 division, a vote without majority counting as zero.
+// Both let the aggregators run after the filter without votes or block means ever being written
+// to memory: on this chip a write stream mixed into a read stream costs far more than its
+// bytes, while re-reading the few winner rows a second pass needs is cheap.  Kernels take the
+// kind as a template parameter (MEANS), so the common case carries no extra branches.
+#pragma once
+
+#include "detox_internal.h"
+
+namespace detox {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+// Loads `valid` (<= VEC) fp32 words starting at p as raw bits (non-temporal: every input byte is
+// used once); the rest read as zero.  Never touches memory beyond p + valid.
+// NT: non-temporal (every input byte is used once); kernels that rely on the caches to merge
+// their partial-line accesses pass NT = false.
+template <int VEC, bool NT = true>
+__device__ inline void load_words(const float *p, int valid, uint32_t (&w)[VEC])
+{
+    if (valid == VEC) {
+        if constexpr (VEC == 4) {
+            const u32x4_t *q = reinterpret_cast<const u32x4_t *>(p);
+            const u32x4_t t = NT ? __builtin_nontemporal_load(q) : *q;
+            w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
+        } else if constexpr (VEC == 2) {
+            const u32x2_t *q = reinterpret_cast<const u32x2_t *>(p);
+            const u32x2_t t = NT ? __builtin_nontemporal_load(q) : *q;
+            w[0] = t.x, w[1] = t.y;
+        } else {
+            const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+            w[0] = NT ? __builtin_nontemporal_load(q) : *q;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            w[i] = i < valid ? reinterpret_cast<const uint32_t *>(p)[i] : 0u;
+    }
+}
+
+template <int VEC, bool NT = true>
+__device__ inline void load_floats(const float *p, int valid, float (&v)[VEC])
+{
+    uint32_t w[VEC];
+    load_words<VEC, NT>(p, valid, w);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = __uint_as_float(w[i]);
+}
+
+template <int VEC>
+__device__ inline void store_floats(float *p, int valid, const float (&v)[VEC])
+{
+    if (valid == VEC) {
+        if constexpr (VEC == 4)
+            *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        else if constexpr (VEC == 2)
+            *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+        else
+            p[0] = v[0];
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            if (i < valid) p[i] = v[i];
+    }
+}
+
+// Logical row b of rs at columns [col, col+valid); `valid` >= 1.
+template <bool MEANS, int VEC, bool NT = true>
+__device__ inline void row_load(const RowSet &rs, int b, int64_t col, int valid, float (&out)[VEC])
+{
+    if constexpr (!MEANS) {
+        const int64_t row = rs.index ? (int64_t)rs.index[b] : (int64_t)b;
+        if (row >= 0) {
+            load_floats<VEC, NT>(rs.base + row * rs.ld + col, valid, out);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) out[i] = 0.0f;
+        }
+    } else {
+        const int64_t lo = ((int64_t)b * rs.n_votes) / rs.count;
+        const int64_t hi = ((int64_t)(b + 1) * rs.n_votes) / rs.count;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) out[i] = 0.0f;
+        for (int64_t pos = lo; pos < hi; ++pos) {
+            const int32_t w = rs.winner[rs.vote_perm ? rs.vote_perm[pos] : pos];
+            float x[VEC];
+            if (w >= 0) {
+                load_floats<VEC, NT>(rs.base + (int64_t)w * rs.ld + col, valid, x);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) x[i] = 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) out[i] = (pos == lo) ? x[i] : __fadd_rn(out[i], x[i]);
+        }
+        const float size = (float)(hi - lo);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) out[i] = __fdiv_rn(out[i], size);
+    }
+}
+
+__device__ inline double wave_sum_fixed(double v)
+{
+    // fixed butterfly: the same tree for every call, so equal inputs give equal sums
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    return v;
+}
+
+}  // namespace detox

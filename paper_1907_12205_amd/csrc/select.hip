@@ -1,7 +1,7 @@
 // The count x count part of the robust aggregators (scores, selections, Weiszfeld weights), run
 // by a single workgroup in fp64 so that no host round trip interrupts the stream, and the two
 // streaming kernels that turn a selection / a weight vector into the output d-vector.
-#include "detox_internal.h"
+#include "rows.cuh"
 
 namespace detox {
 namespace {
@@ -174,65 +174,28 @@ __global__ __launch_bounds__(kMaxCount) void weiszfeld_kernel(const double *Gm, 
     if (j < count) weights[j] = w[j];
 }
 
-template <int VEC>
-__device__ inline void load_guarded(const float *p, int valid, float (&w)[VEC])
-{
-    if (valid == VEC) {
-        if constexpr (VEC == 4) {
-            const float4 t = *reinterpret_cast<const float4 *>(p);
-            w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
-        } else if constexpr (VEC == 2) {
-            const float2 t = *reinterpret_cast<const float2 *>(p);
-            w[0] = t.x, w[1] = t.y;
-        } else {
-            w[0] = p[0];
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) w[i] = i < valid ? p[i] : 0.0f;
-    }
-}
-
-template <int VEC>
-__device__ inline void store_guarded(float *p, int valid, const float (&v)[VEC])
-{
-    if (valid == VEC) {
-        if constexpr (VEC == 4)
-            *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-        else if constexpr (VEC == 2)
-            *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
-        else
-            p[0] = v[0];
-    } else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i)
-            if (i < valid) p[i] = v[i];
-    }
-}
-
-// WEIGHTED = false: out = fp32( (sum_i (double) X[rows[i]]) / m ), rows in list order.
-// WEIGHTED = true : out = fp32( sum_j weights[j] * (double) X[j] ).
-template <int VEC, bool WEIGHTED>
-__global__ __launch_bounds__(kBlock) void combine_rows_kernel(const float *X, int64_t d, int64_t ld,
-                                                              const int32_t *rows,
+// WEIGHTED = false: out = fp32( (sum_i (double) row[rows[i]]) / m ), logical rows in list order.
+// WEIGHTED = true : out = fp32( sum_j weights[j] * (double) row[j] ) over all logical rows.
+template <int VEC, bool WEIGHTED, bool MEANS>
+__global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const int32_t *rows,
                                                               const double *weights, int m,
-                                                              int count, float *out)
+                                                              float *out)
 {
     const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
-    const int64_t left = d - col;
+    const int64_t left = rs.d - col;
     if (left <= 0) return;
     const int valid = left >= VEC ? VEC : (int)left;
     double acc[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.0;
     for (int k = 0; k < m; ++k) {
-        int64_t row = k;
+        int b = k;
         if constexpr (!WEIGHTED) {
-            row = rows[k];   // written by the selection kernel; clamped so a bad index cannot fault
-            row = row < 0 ? 0 : (row >= count ? count - 1 : row);
+            b = rows[k];   // written by the selection kernel; clamped so a bad index cannot fault
+            b = b < 0 ? 0 : (b >= rs.count ? rs.count - 1 : b);
         }
         float x[VEC];
-        load_guarded<VEC>(X + row * ld + col, valid, x);
+        row_load<MEANS, VEC>(rs, b, col, valid, x);
         if constexpr (WEIGHTED) {
             const double wk = weights[k];
 #pragma unroll
@@ -245,28 +208,51 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(const float *X, in
     float o[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) o[i] = WEIGHTED ? (float)acc[i] : (float)(acc[i] / (double)m);
-    store_guarded<VEC>(out + col, valid, o);
+    store_floats<VEC>(out + col, valid, o);
 }
 
 template <bool WEIGHTED>
-hipError_t launch_combine(const float *X, int64_t d, int64_t ld, const int32_t *rows,
-                          const double *weights, int m, int count, float *out, hipStream_t s)
+hipError_t launch_combine(const RowSet &rs, const int32_t *rows, const double *weights, int m,
+                          float *out, hipStream_t s)
 {
-    int vec = row_vec_width(X, ld);
+    int vec = row_vec_width(rs.base, rs.ld);
     const int vo = row_vec_width(out, 4);
     vec = vo < vec ? vo : vec;
-    const int64_t chunks = (d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
+    const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     TraceScope t(WEIGHTED ? "weighted_sum" : "rows_mean", s);
+#define DETOX_CR(V)                                                                               \
+    do {                                                                                          \
+        if (rs.means())                                                                           \
+            combine_rows_kernel<V, WEIGHTED, true><<<(unsigned)chunks, kBlock, 0, s>>>(rs, rows, weights, m, out); \
+        else                                                                                      \
+            combine_rows_kernel<V, WEIGHTED, false><<<(unsigned)chunks, kBlock, 0, s>>>(rs, rows, weights, m, out); \
+    } while (0)
     if (vec == 4)
-        combine_rows_kernel<4, WEIGHTED><<<(unsigned)chunks, kBlock, 0, s>>>(X, d, ld, rows, weights, m, count, out);
+        DETOX_CR(4);
     else if (vec == 2)
-        combine_rows_kernel<2, WEIGHTED><<<(unsigned)chunks, kBlock, 0, s>>>(X, d, ld, rows, weights, m, count, out);
+        DETOX_CR(2);
     else
-        combine_rows_kernel<1, WEIGHTED><<<(unsigned)chunks, kBlock, 0, s>>>(X, d, ld, rows, weights, m, count, out);
+        DETOX_CR(1);
+#undef DETOX_CR
     return hipGetLastError();
 }
 
+__global__ void compose_index_kernel(const int32_t *winner, const int32_t *vote_perm, int n,
+                                     int32_t *index)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < n) index[b] = winner[vote_perm[b]];
+}
+
 }  // namespace
+
+hipError_t launch_compose_index(const int32_t *winner, const int32_t *vote_perm, int n,
+                                int32_t *index, hipStream_t s)
+{
+    TraceScope t("compose_index", s);
+    compose_index_kernel<<<(n + 255) / 256, 256, 0, s>>>(winner, vote_perm, n, index);
+    return hipGetLastError();
+}
 
 hipError_t launch_sqdist_from_gram(const double *Gm, int64_t count, double *D, hipStream_t s)
 {
@@ -301,16 +287,14 @@ hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double e
     return hipGetLastError();
 }
 
-hipError_t launch_rows_mean(const float *X, int64_t count, int64_t d, int64_t ld,
-                            const int32_t *rows, int m, float *out, hipStream_t s)
+hipError_t launch_rows_mean(const RowSet &rs, const int32_t *rows, int m, float *out, hipStream_t s)
 {
-    return launch_combine<false>(X, d, ld, rows, nullptr, m, (int)count, out, s);
+    return launch_combine<false>(rs, rows, nullptr, m, out, s);
 }
 
-hipError_t launch_weighted_sum(const float *X, int64_t count, int64_t d, int64_t ld,
-                               const double *weights, float *out, hipStream_t s)
+hipError_t launch_weighted_sum(const RowSet &rs, const double *weights, float *out, hipStream_t s)
 {
-    return launch_combine<true>(X, d, ld, nullptr, weights, (int)count, (int)count, out, s);
+    return launch_combine<true>(rs, nullptr, weights, rs.count, out, s);
 }
 
 }  // namespace detox

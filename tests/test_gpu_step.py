@@ -19,14 +19,19 @@ def dx():
     return dx
 
 
-def _run(dx, w, spec, ld=None):
-    G = w.matrix()
+def _run(dx, w, spec, ld=None, materialise=True, G=None, group_rows=None, vote_perm=None):
+    G = w.matrix() if G is None else G
     kw = {k: v for k, v in spec.items() if k not in ("B", "aggregator")}
-    ref_out, ref_w, ref_Zh = oracle.detox_step(G, w.r, spec["B"], spec["aggregator"], **kw)
+    ref_out, ref_w, ref_Zh = oracle.detox_step(G, w.r, spec["B"], spec["aggregator"], group_rows=group_rows,
+                                               vote_perm=vote_perm, **kw)
     b = dx.detox_step(dev_matrix(G, ld), w.r, w.q, spec["B"], spec["aggregator"], f=spec.get("f", -1),
-                      m=spec.get("m", -1), iters=spec.get("iters", 50), eps=spec.get("eps", 1e-8))
+                      m=spec.get("m", -1), iters=spec.get("iters", 50), eps=spec.get("eps", 1e-8),
+                      group_rows=group_rows, vote_perm=vote_perm, materialise=materialise)
     assert host(b.winner).tolist() == ref_w.tolist()
-    assert host(b.Zhat).tobytes() == ref_Zh.tobytes()
+    if materialise:
+        assert host(b.Zhat).tobytes() == ref_Zh.tobytes()
+    else:
+        assert b.Zhat is None
     got = host(b.out)
     if spec["aggregator"] == "coord_median":
         assert got.tobytes() == ref_out.tobytes()
@@ -44,8 +49,36 @@ def _run(dx, w, spec, ld=None):
 def test_step_on_each_workload(dx, idx, d):
     w = workloads.config(idx, d=d)
     for spec in w.detox:
-        _run(dx, w, spec)
-        _run(dx, w, spec, ld=(d + 63) // 64 * 64)
+        for materialise in (True, False):
+            _run(dx, w, spec, materialise=materialise)
+            _run(dx, w, spec, ld=(d + 63) // 64 * 64, materialise=materialise)
+
+
+AGGS = [dict(B=5, aggregator="multikrum", f=1, m=3), dict(B=15, aggregator="multikrum", f=2, m=9),
+        dict(B=5, aggregator="coord_median"), dict(B=3, aggregator="coord_median"),
+        dict(B=15, aggregator="coord_median"), dict(B=4, aggregator="coord_median"),
+        dict(B=7, aggregator="bulyan", f=1), dict(B=15, aggregator="bulyan", f=2),
+        dict(B=5, aggregator="geomedian"), dict(B=15, aggregator="geomedian", iters=20)]
+
+
+@pytest.mark.parametrize("spec", AGGS, ids=lambda s: f"{s['aggregator']}-B{s['B']}")
+@pytest.mark.parametrize("materialise", [True, False])
+def test_step_with_votes_without_majority_and_permutations(dx, spec, materialise):
+    """Groups without a majority (zero votes), a Byzantine-majority group, scattered node groups
+    and a vote permutation: the one-pass results must be redone exactly where needed."""
+    w = workloads.config(3, d=30011)
+    G = w.matrix()
+    d = w.d
+    G[3, d // 2:] += 1; G[5, : d // 2] += 2          # group 1: piecewise agreement only
+    G[12] = 7; G[13] = 8; G[14] = 9                  # group 4: three different rows
+    G[18] = -3; G[20] = -3                           # group 6: two colluding Byzantine rows
+    rng = np.random.default_rng(11)
+    _run(dx, w, spec, G=G, materialise=materialise)
+    order = rng.permutation(15)
+    group_rows = np.concatenate([3 * g + rng.permutation(3) for g in order]).astype(np.int32)
+    vote_perm = rng.permutation(15).astype(np.int32)
+    _run(dx, w, spec, G=G, materialise=materialise, group_rows=group_rows, vote_perm=vote_perm)
+    _run(dx, w, spec, G=G, ld=d + 1, materialise=materialise, vote_perm=vote_perm)
 
 
 def test_step_derives_f_and_m(dx):
@@ -93,6 +126,8 @@ def test_full_size_resnet18_shape(dx):
     assert host(b.winner).tolist() == ref_w.tolist()
     assert host(b.Zhat).tobytes() == ref_Zh.tobytes()
     assert rel_l2(host(b.out), ref_out) <= TOL
+    b2 = dx.detox_step(Gd, 3, 5, spec["B"], "multikrum", f=spec["f"], m=spec["m"], materialise=False)
+    assert host(b2.out).tobytes() == host(b.out).tobytes()      # the launch configuration bench.py times
     v = w.vanilla[0]
     ref_out, ref_sel, ref_scores = oracle.multikrum(G, v["f"], v["m"])
     out, sel, scores = dx.robust_multikrum(Gd, v["f"], v["m"])
