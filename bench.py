@@ -24,6 +24,18 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
 
+def measured_traffic(agg, n, d):
+    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE for this workload (the committed summary under profiles/), or None."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"detox_step_{agg}__n{n}_d{d}.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\[.*\]: (\d+)", open(path).read(), re.M)
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -109,7 +121,7 @@ def main():
     achieved = alg_bytes / (kernel_ms[dominant] * 1e-3) / 1e9
     log("[bench] per-kernel ms: " + ", ".join(f"{k}={v:.4f}" for k, v in kernel_ms.items()))
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(agg, n, d),
                 "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": round(kernel_ms[dominant], 5)}
     # compulsory traffic of the whole step: n rows in, B block means, m of them out again, 1 result
     step_alg_bytes = (n + B + spec.get("m", 0) + 1) * d * 4 if agg == "multikrum" else None
