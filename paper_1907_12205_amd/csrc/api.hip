@@ -5,6 +5,7 @@
 
 #include "../../include/detox.h"
 #include "detox_internal.h"
+#include "small_select.cuh"
 
 namespace detox {
 namespace {
@@ -93,12 +94,13 @@ struct FusedGram {
     const double *partials = nullptr;
     int blocks = 0;
     const int *redo = nullptr;
+    bool reduced = false;   // Gm (and the Multi-Krum selection) already produced unless *redo
 };
 
 hipError_t gram_for(const RowSet &rs, const AggWs &a, const FusedGram &fg, hipStream_t s)
 {
-    if (fg.blocks > 0)
-        return launch_gram_after_filter(rs, a.partials, fg.partials, fg.blocks, fg.redo, a.Gm, s);
+    if (fg.reduced)
+        return launch_small_redo(rs, a.partials, fg.redo, a.Gm, 0, 0, a.sc.scores, nullptr, s);
     return launch_gram(rs, a.partials, a.Gm, s);
 }
 
@@ -106,8 +108,15 @@ int multikrum_impl(const RowSet &rs, int f, int m, float *out, int32_t *selected
                    void *ws, const FusedGram &fg, hipStream_t s)
 {
     AggWs a = carve_aggregator(ws, rs.count);
-    hipError_t e = gram_for(rs, a, fg, s);
-    if (e == hipSuccess) e = launch_multikrum_select(a.Gm, rs.count, f, m, a.sc, selected, scores, s);
+    hipError_t e;
+    if (fg.reduced) {
+        // scores and selection came with the finalize kernel; repeat them only if *redo
+        e = launch_small_redo(rs, a.partials, fg.redo, a.Gm, f, m, a.sc.scores, selected, s);
+    } else {
+        e = gram_for(rs, a, fg, s);
+        if (e == hipSuccess)
+            e = launch_multikrum_select(a.Gm, rs.count, f, m, a.sc, selected, scores, s);
+    }
     if (e == hipSuccess) e = launch_rows_mean(rs, selected, m, out, s);
     return status_of(e);
 }
@@ -226,7 +235,7 @@ int detox_majority_filter(const float *G, int64_t n, int64_t d, int64_t ld, int 
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
                    fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
-    hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, s);
+    hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, nullptr, s);
     if (e == hipSuccess && Z)
         e = launch_block_mean(G, d, ld, winner, groups, groups, nullptr, Z, ldz, true, false, s);
     return status_of(e);
@@ -257,7 +266,7 @@ int detox_filter_block_mean(const float *G, int64_t n, int64_t d, int64_t ld, in
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
                    fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
-    hipError_t e = launch_filter(p, FilterWant::kMeans, nullptr, s);
+    hipError_t e = launch_filter(p, FilterWant::kMeans, nullptr, nullptr, s);
     if (e == hipSuccess)
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     return status_of(e);
@@ -360,21 +369,24 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     FilterWant want = agg == DETOX_AGG_COORD_MEDIAN ? FilterWant::kMedian : FilterWant::kGram;
     if (Zhat == nullptr && (B > 8 || groups > kFusedMaxVotes)) want = FilterWant::kVotes;   // B = n/r
     FilterDone done;
-    hipError_t e = launch_filter(p, want, &done, s);
+    void *aws = static_cast<char *>(ws) + fbytes;
+    const AggWs aw = carve_aggregator(aws, B);
+    // what the finalize kernel can do on the side when the Gram matrix comes with the pass
+    SmallSelect tail{nullptr, 0, 0, 0, (int)B, aw.Gm, f, agg == DETOX_AGG_MULTIKRUM ? m : 0, aw.sc.scores, selected};
+    hipError_t e = launch_filter(p, want, &tail, &done, s);
     if (e == hipSuccess && Zhat != nullptr)   // redo the blocks that hold a vote without majority
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     if (e != hipSuccess) return status_of(e);
 
     // The rows the aggregator works on: the stored block means, or the same values formed on
     // the fly from the winners.
-    void *aws = static_cast<char *>(ws) + fbytes;
     RowSet rs = direct_rows(Zhat, B, d, ldo);
     if (!Zhat) {
         if (B == groups) {
             // every vote its own block: the rows are the winner rows themselves
             const int32_t *index = winner;
             if (vote_perm) {
-                int32_t *table = carve_aggregator(aws, B).row_index;
+                int32_t *table = aw.row_index;
                 e = launch_compose_index(winner, vote_perm, (int)B, table, s);
                 if (e != hipSuccess) return status_of(e);
                 index = table;
@@ -388,6 +400,7 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     fg.partials = fw.gram_partials;
     fg.blocks = done.gram_blocks;
     fg.redo = fw.redo;
+    fg.reduced = done.gram_reduced;
     switch (agg) {
     case DETOX_AGG_MULTIKRUM: return multikrum_impl(rs, f, m, out, selected, nullptr, aws, fg, s);
     case DETOX_AGG_BULYAN: return bulyan_impl(rs, f, out, selected, aws, fg, s);

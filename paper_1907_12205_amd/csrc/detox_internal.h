@@ -93,11 +93,18 @@ enum class FilterWant {
 };
 struct FilterDone {
     int gram_blocks = 0;          // > 0: Gram partial slots written (kGram honoured)
+    bool gram_reduced = false;    // the finalize kernel already produced Gm (and, if asked, the
+                                  //   Multi-Krum selection) unless *redo
     bool median_written = false;  // kMedian honoured: `out` holds the median unless *redo
 };
+struct SmallSelect;               // small_select.cuh: what the finalize kernel should go on to do
 // kGram / kMedian with B > 8 (or more than kFusedMaxVotes groups) degrade to kMeans; then Zhat
 // must be non-null (hipErrorInvalidValue otherwise).
-hipError_t launch_filter(FilterParams p, FilterWant want, FilterDone *done, hipStream_t s);
+//   tail (may be null): with kGram honoured, the finalize kernel also reduces the Gram partials
+//   into tail->Gm and, if tail->krum_m > 0, runs Multi-Krum's scoring and selection, all skipped
+//   when *redo gets set.
+hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tail, FilterDone *done,
+                         hipStream_t s);
 // Zhat_b = mean of the votes of block b, read through `winner`.
 //   copy: blocks of one vote copied bit for bit; only_bad: touch only blocks holding winner = -1.
 hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_t *winner,
@@ -108,11 +115,11 @@ hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_
 size_t gram_partial_bytes(int64_t count);
 // Gram matrix Gm[a][b] = <x_a, x_b> of the logical rows (count x count doubles, full, symmetric).
 hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s);
-// count <= 8 only: Gm from the partials the persistent filter kernel accumulated
-// (fused_partials, fused_blocks slots), unless *redo is set on the device, in which case the
-// Gram matrix is recomputed from the rows.  No host round trip either way.
-hipError_t launch_gram_after_filter(const RowSet &rs, void *partials, const double *fused_partials,
-                                    int fused_blocks, const int *redo, double *Gm, hipStream_t s);
+// count <= 8, the finalize kernel has produced Gm (and the Multi-Krum selection when krum_m > 0)
+// unless *redo: two kernels that do nothing unless *redo recompute the Gram matrix from the rows
+// and repeat the reduction (and the selection).
+hipError_t launch_small_redo(const RowSet &rs, void *partials, const int *redo, double *Gm, int krum_f,
+                             int krum_m, double *scores, int32_t *selected, hipStream_t s);
 
 // ---- select.hip ------------------------------------------------------------
 struct SelectScratch {   // all dev, carved from the caller's workspace

@@ -19,6 +19,7 @@
 #include <cstdlib>
 
 #include "rows.cuh"
+#include "small_select.cuh"
 #include "sortnet.cuh"
 
 namespace detox {
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
             double s = 0.0;
 #pragma unroll
             for (int w = 0; w < kBlock / kWave; ++w) s += red[w][threadIdx.x];
-            p.gram_partials[(int64_t)blockIdx.x * NP + threadIdx.x] = s;
+            p.gram_partials[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = s;   // [pair][slot]
         }
     }
 }
@@ -232,13 +233,14 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
 // One workgroup: ORs the per-workgroup pair bits, decides the winners, and reports whether any
 // group has no majority (*redo = 1) so that later kernels know the one-pass block means and
 // Gram partials of those blocks must be recomputed.
-__global__ __launch_bounds__(1024) void finalize_partials_kernel(const unsigned long long *partials,
-                                                                int blocks,
-                                                                const int32_t *group_rows, int r,
-                                                                int n_votes, int32_t *winner,
-                                                                int *redo)
+// When every group has a majority and the pass left Gram partials, the same workgroup goes on to
+// add them up and (Multi-Krum) to score and select.
+__global__ __launch_bounds__(kPostThreads) void finalize_partials_kernel(
+    const unsigned long long *partials, int blocks, const int32_t *group_rows, int r, int n_votes,
+    int32_t *winner, int *redo, SmallSelect q)
 {
     __shared__ unsigned long long sbits[kFusedMaxVotes];
+    const double gv = small_gram_load(q);   // issued first: overlaps the vote bookkeeping below
     for (int j = threadIdx.x; j < n_votes; j += blockDim.x) sbits[j] = 0ull;
     __syncthreads();
     // thread (j, slice): group j = tid % pad, every slices-th workgroup starting at tid / pad
@@ -261,6 +263,10 @@ __global__ __launch_bounds__(1024) void finalize_partials_kernel(const unsigned 
     }
     bad = __syncthreads_or(bad);
     if (threadIdx.x == 0) *redo = bad ? 1 : 0;
+    if (bad || q.gram_partials == nullptr) return;   // uniform
+    __shared__ double Gl[kSmallCount * kSmallCount];
+    small_gram_reduce(q, gv, Gl);
+    if (q.krum_m > 0) small_multikrum(q, Gl);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -474,7 +480,8 @@ FilterWs carve_filter_ws(void *ws, int64_t n_votes)
     return w;
 }
 
-hipError_t launch_filter(FilterParams p, FilterWant want, FilterDone *done, hipStream_t s)
+hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tail, FilterDone *done,
+                         hipStream_t s)
 {
     const bool mean = want != FilterWant::kVotes;
     int vec = row_vec_width(p.G, p.ld);
@@ -531,10 +538,20 @@ hipError_t launch_filter(FilterParams p, FilterWant want, FilterDone *done, hipS
     if (e != hipSuccess) return e;
     TraceScope t("filter_finalize", s);
     if (fused) {
-        finalize_partials_kernel<<<1, 1024, 0, s>>>(p.flag_partials, grid, p.group_rows, p.r,
-                                                    (int)p.n_votes, p.winner, p.redo);
+        SmallSelect q{};
+        if (mode == kGram && tail) {
+            q = *tail;
+            q.gram_partials = p.gram_partials;
+            q.gram_blocks = grid;
+            q.slot_stride = 1;        // the pass writes [pair][slot]: coalesced for the reader
+            q.pair_stride = grid;
+            q.count = (int)p.B;
+        }
+        finalize_partials_kernel<<<1, kPostThreads, 0, s>>>(p.flag_partials, grid, p.group_rows, p.r,
+                                                            (int)p.n_votes, p.winner, p.redo, q);
         if (done) {
             done->gram_blocks = mode == kGram ? grid : 0;
+            done->gram_reduced = mode == kGram && tail != nullptr;
             done->median_written = mode == kMedian;
         }
     } else {

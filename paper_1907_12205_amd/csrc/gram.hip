@@ -9,6 +9,7 @@
 // kernel adds them in a fixed order in fp64.  No atomics: results repeat bit for bit, and rows
 // that are bit-identical produce bit-identical Gram entries (same products, same order).
 #include "rows.cuh"
+#include "small_select.cuh"
 
 namespace detox {
 namespace {
@@ -73,16 +74,8 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(RowSet rs, double *p
 // then the 256 thread sums are added by a fixed tree.
 __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double *partials,
                                                                    int blocks, int count,
-                                                                   double *Gm,
-                                                                   const double *alt_partials,
-                                                                   int alt_blocks,
-                                                                   const int *use_main)
+                                                                   double *Gm)
 {
-    // alt_partials: sums accumulated by the persistent filter kernel, valid unless *use_main
-    if (alt_partials && *use_main == 0) {
-        partials = alt_partials;
-        blocks = alt_blocks;
-    }
     const int np = count * (count + 1) / 2;
     const int pair = blockIdx.x;
     double s = 0.0;
@@ -335,7 +328,7 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
         if (e != hipSuccess) return e;
         const int np = (int)(count * (count + 1) / 2);
         TraceScope t("gram_reduce", s);
-        gram_small_reduce_kernel<<<np, kBlock, 0, s>>>(pp, grid, (int)count, Gm, nullptr, 0, nullptr);
+        gram_small_reduce_kernel<<<np, kBlock, 0, s>>>(pp, grid, (int)count, Gm);
         return hipGetLastError();
     }
     const int T = (int)((count + 15) / 16);
@@ -373,19 +366,27 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
     return hipGetLastError();
 }
 
-hipError_t launch_gram_after_filter(const RowSet &rs, void *partials, const double *fused_partials,
-                                    int fused_blocks, const int *redo, double *Gm, hipStream_t s)
+namespace {
+__global__ __launch_bounds__(kPostThreads) void small_redo_kernel(SmallSelect q, const int *run_if)
 {
-    const int64_t count = rs.count;
-    if (count < 1 || count > 8) return hipErrorInvalidValue;
+    if (*run_if == 0) return;   // uniform
+    __shared__ double Gl[kSmallCount * kSmallCount];
+    small_gram_reduce(q, small_gram_load(q), Gl);
+    if (q.krum_m > 0) small_multikrum(q, Gl);
+}
+}  // namespace
+
+hipError_t launch_small_redo(const RowSet &rs, void *partials, const int *redo, double *Gm, int krum_f,
+                             int krum_m, double *scores, int32_t *selected, hipStream_t s)
+{
+    if (rs.count < 1 || rs.count > kSmallCount) return hipErrorInvalidValue;
     double *pp = static_cast<double *>(partials);
     int grid = 0;
     hipError_t e = launch_small_any(rs, pp, redo, &grid, s);   // runs only if *redo
     if (e != hipSuccess) return e;
-    const int np = (int)(count * (count + 1) / 2);
-    TraceScope t("gram_reduce", s);
-    gram_small_reduce_kernel<<<np, kBlock, 0, s>>>(pp, grid, (int)count, Gm, fused_partials,
-                                                   fused_blocks, redo);
+    SmallSelect q{pp, grid, rs.count * (rs.count + 1) / 2, 1, rs.count, Gm, krum_f, krum_m, scores, selected};
+    TraceScope t("select_if_redo", s);
+    small_redo_kernel<<<1, kPostThreads, 0, s>>>(q, redo);
     return hipGetLastError();
 }
 

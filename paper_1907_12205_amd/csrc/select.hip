@@ -6,8 +6,6 @@
 namespace detox {
 namespace {
 
-constexpr int kSelThreads = 1024;
-
 __device__ inline bool dbl_before(double x, double y)   // ascending, NaN last
 {
     if (x != x) return false;
@@ -31,32 +29,6 @@ __global__ void sqdist_kernel(const double *Gm, int count, double *D)
     D[e] = a <= b ? sq_dist(Gm, count, a, b) : sq_dist(Gm, count, b, a);
 }
 
-// D and, for every row a, its distances to the other rows in ascending order (NaN last, equal
-// values by row index) with the matching row indices.  Rank by counting: no data-dependent
-// loop, every (a,b) pair independent.
-__device__ void build_sorted_rows(const double *Gm, int count, const SelectScratch &sc)
-{
-    for (int e = threadIdx.x; e < count * count; e += blockDim.x) {
-        const int a = e / count, b = e % count;
-        sc.D[e] = a <= b ? sq_dist(Gm, count, a, b) : sq_dist(Gm, count, b, a);
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < count * count; e += blockDim.x) {
-        const int a = e / count, b = e % count;
-        if (a == b) continue;
-        const double x = sc.D[e];
-        int rank = 0;
-        for (int c = 0; c < count; ++c) {
-            if (c == a || c == b) continue;
-            const double y = sc.D[a * count + c];
-            if (dbl_before(y, x) || (!dbl_before(x, y) && c < b)) ++rank;
-        }
-        sc.sorted[a * count + rank] = x;
-        sc.sorted_idx[a * count + rank] = b;
-    }
-    __syncthreads();
-}
-
 __device__ inline bool score_before(double sa, int a, double sb, int b)
 {
     const double ka = sa != sa ? INFINITY : sa, kb = sb != sb ? INFINITY : sb;
@@ -65,110 +37,161 @@ __device__ inline bool score_before(double sa, int a, double sb, int b)
     return a < b;
 }
 
-// Multi-Krum: score(a) = sum of the count-f-2 smallest distances, ascending; the m best rows.
-__global__ __launch_bounds__(kSelThreads) void multikrum_select_kernel(
-    const double *Gm, int count, int f, int m, SelectScratch sc, int32_t *selected,
-    double *scores_out)
+constexpr int kRowThreads = 128;   // >= kMaxCount
+
+// One workgroup per row a: D[a][.] from the Gram matrix, then the distances to the other rows in
+// ascending order (NaN last, equal values by row index) with the matching row indices, ranked by
+// counting in LDS (no data-dependent loop).  nb > 0: also score(a) = sum of the nb smallest,
+// added in ascending order (the Krum score).
+__global__ __launch_bounds__(kRowThreads) void sort_rows_kernel(const double *Gm, int count, int nb,
+                                                                SelectScratch sc,
+                                                                double *scores_out)
 {
-    build_sorted_rows(Gm, count, sc);
-    const int nb = count - f - 2;
-    for (int a = threadIdx.x; a < count; a += blockDim.x) {
+    __shared__ double drow[kMaxCount];
+    __shared__ double srow[kMaxCount];
+    const int a = blockIdx.x, b = threadIdx.x;
+    if (b < count) {
+        const double x = a <= b ? sq_dist(Gm, count, a, b) : sq_dist(Gm, count, b, a);
+        drow[b] = x;
+        sc.D[a * count + b] = x;
+    }
+    __syncthreads();
+    if (b < count && b != a) {
+        const double x = drow[b];
+        int rank = 0;
+        for (int c = 0; c < count; ++c) {
+            if (c == a || c == b) continue;
+            const double y = drow[c];
+            if (dbl_before(y, x) || (!dbl_before(x, y) && c < b)) ++rank;
+        }
+        srow[rank] = x;
+        sc.sorted[a * count + rank] = x;
+        sc.sorted_idx[a * count + rank] = b;
+    }
+    __syncthreads();
+    if (nb > 0 && b == 0) {
         double s = 0.0;
-        for (int i = 0; i < nb; ++i) s += sc.sorted[a * count + i];
+        for (int i = 0; i < nb; ++i) s += srow[i];
         sc.scores[a] = s;
         if (scores_out) scores_out[a] = s;
     }
-    __syncthreads();
-    for (int a = threadIdx.x; a < count; a += blockDim.x) {
-        const double sa = sc.scores[a];
-        int rank = 0;
-        for (int c = 0; c < count; ++c)
-            if (c != a && score_before(sc.scores[c], c, sa, a)) ++rank;
-        if (rank < m) selected[rank] = a;
-    }
 }
 
-// Bulyan stage 1: count-2f rounds of Krum over the rows still in the pool.
-__global__ __launch_bounds__(kSelThreads) void bulyan_select_kernel(const double *Gm, int count,
-                                                                    int f, SelectScratch sc,
+// The m rows of smallest score in ascending (score, index) order.
+__global__ __launch_bounds__(kRowThreads) void top_m_kernel(const double *scores, int count, int m,
+                                                            int32_t *selected)
+{
+    __shared__ double s[kMaxCount];
+    const int a = threadIdx.x;
+    if (a < count) s[a] = scores[a];
+    __syncthreads();
+    if (a >= count) return;
+    int rank = 0;
+    for (int c = 0; c < count; ++c)
+        if (c != a && score_before(s[c], c, s[a], a)) ++rank;
+    if (rank < m) selected[rank] = a;
+}
+
+// Bulyan stage 1: count-2f rounds of Krum over the rows still in the pool, on the sorted
+// neighbour lists held in LDS (dynamic: count*(count-1) doubles + as many bytes).  One thread per
+// row; the pool is a 128-bit mask every thread keeps in step; the arg-min runs over wavefront
+// shuffles, so a round costs one barrier.
+__global__ __launch_bounds__(kRowThreads) void bulyan_select_kernel(int count, int f,
+                                                                    SelectScratch sc,
                                                                     int32_t *selected)
 {
-    __shared__ unsigned char in_pool[kMaxCount];
-    __shared__ double best_score[kMaxCount];
-    build_sorted_rows(Gm, count, sc);
-    for (int a = threadIdx.x; a < count; a += blockDim.x) in_pool[a] = 1;
+    extern __shared__ double lds[];
+    const int nbrs = count - 1;
+    double *sval = lds;                                                 // [count][nbrs]
+    unsigned char *sidx = reinterpret_cast<unsigned char *>(lds + (size_t)count * nbrs);
+    __shared__ double wave_key[2][kRowThreads / kWave];
+    __shared__ int wave_row[2][kRowThreads / kWave];
+    for (int e = threadIdx.x; e < count * nbrs; e += blockDim.x) {
+        const int a = e / nbrs, i = e % nbrs;
+        sval[e] = sc.sorted[a * count + i];
+        sidx[e] = (unsigned char)sc.sorted_idx[a * count + i];
+    }
     __syncthreads();
+    unsigned long long pool_lo = count >= 64 ? ~0ull : ((1ull << count) - 1ull);
+    unsigned long long pool_hi = count <= 64 ? 0ull : (count >= 128 ? ~0ull : ((1ull << (count - 64)) - 1ull));
+    auto in_pool = [&](int r) { return ((r < 64 ? pool_lo >> r : pool_hi >> (r - 64)) & 1ull) != 0ull; };
+    const int a = threadIdx.x, lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int theta = count - 2 * f;
     for (int it = 0; it < theta; ++it) {
         const int pool = count - it;
         int nb = pool - f - 2;
         if (nb < 1) nb = 1;
-        for (int a = threadIdx.x; a < count; a += blockDim.x) {
-            double s = INFINITY;
-            if (in_pool[a]) {
-                s = 0.0;
-                int taken = 0;
-                for (int i = 0; i < count - 1 && taken < nb; ++i) {
-                    if (in_pool[sc.sorted_idx[a * count + i]]) {
-                        s += sc.sorted[a * count + i];
-                        ++taken;
-                    }
+        double key = INFINITY;
+        int row = 1 << 30;
+        if (a < count && in_pool(a)) {
+            double s = 0.0;
+            int taken = 0;
+            for (int i = 0; i < nbrs; ++i) {      // full length, predicated: the loads pipeline
+                const int r = sidx[a * nbrs + i];
+                const double v = sval[a * nbrs + i];
+                if (in_pool(r) && taken < nb) {
+                    s += v;
+                    ++taken;
                 }
             }
-            best_score[a] = s;
+            key = s != s ? INFINITY : s;
+            row = a;
         }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            int best = -1;
-            for (int a = 0; a < count; ++a) {
-                if (!in_pool[a]) continue;
-                if (best < 0 || score_before(best_score[a], a, best_score[best], best)) best = a;
-            }
-            in_pool[best] = 0;
-            selected[it] = best;
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) {
+            const double k2 = __shfl_xor(key, off, kWave);
+            const int r2 = __shfl_xor(row, off, kWave);
+            if (k2 < key || (k2 == key && r2 < row)) key = k2, row = r2;
         }
+        if (lane == 0) wave_key[it & 1][wave] = key, wave_row[it & 1][wave] = row;
         __syncthreads();
+        double bk = wave_key[it & 1][0];
+        int best = wave_row[it & 1][0];
+        for (int w = 1; w < kRowThreads / kWave; ++w) {
+            const double k2 = wave_key[it & 1][w];
+            const int r2 = wave_row[it & 1][w];
+            if (k2 < bk || (k2 == bk && r2 < best)) bk = k2, best = r2;
+        }
+        if (best < 64) pool_lo &= ~(1ull << best); else pool_hi &= ~(1ull << (best - 64));
+        if (threadIdx.x == 0) selected[it] = best;
     }
 }
 
 // Weiszfeld on the Gram matrix: the iterate is x = sum_j w_j x_j with sum w = 1, so
-// ||x - x_j||^2 = w'Gw - 2 (Gw)_j + G_jj.  Exactly `iters` updates from w = 1/count.
+// ||x - x_j||^2 = w'Gw - 2 (Gw)_j + G_jj.  Exactly `iters` updates from w = 1/count.  One thread
+// per row, the Gram matrix in LDS (dynamic: count*count doubles); the two scalar sums are formed
+// by every thread in the same order, so all threads hold identical values.
 __global__ __launch_bounds__(kMaxCount) void weiszfeld_kernel(const double *Gm, int count,
                                                               int iters, double eps,
                                                               double *weights)
 {
+    extern __shared__ double G[];
     __shared__ double w[kMaxCount], gw[kMaxCount], inv[kMaxCount];
-    __shared__ double quad, inv_sum;
     const int j = threadIdx.x;
+    for (int e = threadIdx.x; e < count * count; e += blockDim.x) G[e] = Gm[e];
     if (j < count) w[j] = 1.0 / (double)count;
     __syncthreads();
     for (int t = 0; t < iters; ++t) {
         if (j < count) {
             double s = 0.0;
-            for (int k = 0; k < count; ++k) s += Gm[j * count + k] * w[k];
+            for (int k = 0; k < count; ++k) s += G[j * count + k] * w[k];
             gw[j] = s;
         }
         __syncthreads();
-        if (j == 0) {
-            double s = 0.0;
-            for (int k = 0; k < count; ++k) s += w[k] * gw[k];
-            quad = s;
-        }
-        __syncthreads();
         if (j < count) {
-            double d2 = quad - 2.0 * gw[j] + Gm[j * count + j];
+            double quad = 0.0;
+            for (int k = 0; k < count; ++k) quad += w[k] * gw[k];
+            double d2 = quad - 2.0 * gw[j] + G[j * count + j];
             if (d2 < 0.0) d2 = 0.0;
             const double dist = sqrt(d2);
             inv[j] = 1.0 / (dist > eps ? dist : eps);
         }
         __syncthreads();
-        if (j == 0) {
-            double s = 0.0;
-            for (int k = 0; k < count; ++k) s += inv[k];
-            inv_sum = s;
+        if (j < count) {
+            double inv_sum = 0.0;
+            for (int k = 0; k < count; ++k) inv_sum += inv[k];
+            w[j] = inv[j] / inv_sum;
         }
-        __syncthreads();
-        if (j < count) w[j] = inv[j] / inv_sum;
         __syncthreads();
     }
     if (j < count) weights[j] = w[j];
@@ -266,24 +289,51 @@ hipError_t launch_multikrum_select(const double *Gm, int64_t count, int f, int m
                                    const SelectScratch &sc, int32_t *selected, double *scores_out,
                                    hipStream_t s)
 {
+    {
+        TraceScope t("krum_scores", s);
+        sort_rows_kernel<<<(unsigned)count, kRowThreads, 0, s>>>(Gm, (int)count, (int)count - f - 2,
+                                                                 sc, scores_out);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     TraceScope t("multikrum_select", s);
-    multikrum_select_kernel<<<1, kSelThreads, 0, s>>>(Gm, (int)count, f, m, sc, selected, scores_out);
+    top_m_kernel<<<1, kRowThreads, 0, s>>>(sc.scores, (int)count, m, selected);
     return hipGetLastError();
 }
 
 hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const SelectScratch &sc,
                                 int32_t *selected, hipStream_t s)
 {
+    {
+        TraceScope t("sort_rows", s);
+        sort_rows_kernel<<<(unsigned)count, kRowThreads, 0, s>>>(Gm, (int)count, 0, sc, nullptr);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t lds = (size_t)count * (count - 1) * (sizeof(double) + 1) + 16;
+    if (lds > 64 * 1024) {
+        // gfx950 has 160 KB of LDS per workgroup; more than 64 KB has to be asked for
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(bulyan_select_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
     TraceScope t("bulyan_select", s);
-    bulyan_select_kernel<<<1, kSelThreads, 0, s>>>(Gm, (int)count, f, sc, selected);
+    bulyan_select_kernel<<<1, kRowThreads, lds, s>>>((int)count, f, sc, selected);
     return hipGetLastError();
 }
 
 hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double eps,
                             double *weights, hipStream_t s)
 {
+    const size_t lds = (size_t)count * count * sizeof(double);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(weiszfeld_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const int threads = count <= 64 ? 64 : kMaxCount;
     TraceScope t("weiszfeld_gram", s);
-    weiszfeld_kernel<<<1, kMaxCount, 0, s>>>(Gm, (int)count, iters, eps, weights);
+    weiszfeld_kernel<<<1, threads, lds, s>>>(Gm, (int)count, iters, eps, weights);
     return hipGetLastError();
 }
 
