@@ -26,7 +26,7 @@ namespace detox {
 namespace {
 
 // Loads the R member rows of node group j at this thread's columns (zeros where invalid) and
-// returns the pairs that differ there.
+// returns the pairs that differ anywhere in the wavefront's columns (a uniform value).
 template <int R, int VEC>
 __device__ inline unsigned long long load_group(const FilterParams &p, int64_t j, int64_t col,
                                                 int valid, uint32_t (&x)[R][VEC])
@@ -41,6 +41,8 @@ __device__ inline unsigned long long load_group(const FilterParams &p, int64_t j
             for (int i = 0; i < VEC; ++i) x[k][i] = 0u;
         }
     }
+    // per-thread pair bits first (pure vector work), then one wavefront-wide test; the
+    // per-pair ballots run only in the rare wavefront that saw a difference
     unsigned long long bits = 0ull;
     int pair = 0;
 #pragma unroll
@@ -52,41 +54,34 @@ __device__ inline unsigned long long load_group(const FilterParams &p, int64_t j
             for (int i = 0; i < VEC; ++i) diff |= x[a][i] ^ x[c][i];
             if (diff) bits |= 1ull << pair;
         }
-    return bits;
-}
-
-// OR of `bits` over the wavefront (uniform result); cheap when nothing differs.
-template <int R>
-__device__ inline unsigned long long wave_or(unsigned long long bits)
-{
     unsigned long long wave_bits = 0ull;
     if (__any(bits != 0ull)) {
 #pragma unroll
-        for (int pair = 0; pair < R * (R - 1) / 2; ++pair)
-            if (__any((bits >> pair) & 1ull)) wave_bits |= 1ull << pair;
+        for (int q = 0; q < R * (R - 1) / 2; ++q)
+            if (__any((bits >> q) & 1ull)) wave_bits |= 1ull << q;
     }
     return wave_bits;
 }
 
-// Per coordinate: the value held by more than R/2 members (it shows among the first R/2+1), or 0.
+// Per coordinate: the value held by more than R/2 members, found by the majority-vote scan
+// (keep a candidate and a counter; a different value cancels one count).  Where no value has a
+// strict majority the result is arbitrary: such a group has no vector majority either, and
+// everything derived from its block is recomputed from the winners afterwards.
 template <int R, int VEC>
 __device__ inline void majority_values(const uint32_t (&x)[R][VEC], float (&out)[VEC])
 {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
-        uint32_t v = 0u;
-        bool found = false;
+        uint32_t cand = x[0][i];
+        int cnt = 1;
 #pragma unroll
-        for (int a = 0; a <= R / 2; ++a) {
-            int votes = 0;
-#pragma unroll
-            for (int c = 0; c < R; ++c) votes += (x[a][i] == x[c][i]) ? 1 : 0;
-            if (!found && 2 * votes > R) {
-                v = x[a][i];
-                found = true;
-            }
+        for (int k = 1; k < R; ++k) {
+            const bool same = x[k][i] == cand;
+            const bool empty = cnt == 0;
+            cand = (!same && empty) ? x[k][i] : cand;
+            cnt = (same || empty) ? cnt + 1 : cnt - 1;
         }
-        out[i] = __uint_as_float(v);
+        out[i] = __uint_as_float(cand);
     }
 }
 
@@ -160,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
             for (int64_t pos = lo; pos < hi; ++pos) {
                 const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
                 uint32_t x[R][VEC];
-                const unsigned long long wave_bits = wave_or<R>(load_group<R, VEC>(p, j, col, valid, x));
+                const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, x);
                 if (wave_bits != 0ull && lane == 0) atomicOr(&sbits[j], wave_bits);   // LDS, integer
                 if constexpr (MEAN) {
                     float v[VEC];
@@ -295,7 +290,7 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(FilterParams p)
     for (int64_t pos = lo; pos < hi; ++pos) {
         const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
         uint32_t x[R][VEC];
-        const unsigned long long wave_bits = wave_or<R>(load_group<R, VEC>(p, j, col, valid, x));
+        const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, x);
         if (wave_bits != 0ull && lane == 0) {
             // one conditional atomic per wavefront; skipped once the bits are known
             const unsigned long long seen = __atomic_load_n(&p.flags[j], __ATOMIC_RELAXED);
@@ -378,42 +373,70 @@ __global__ __launch_bounds__(kBlock) void block_mean_kernel(const float *G, int6
 }
 
 // ---- dispatch -----------------------------------------------------------------------------
-template <int R, int VEC, int NB>
-hipError_t launch_fused_rvn(const FilterParams &p, int mode, int grid, hipStream_t s)
+// Resident workgroups per CU of a kernel (cached per instantiation); the persistent grid must
+// not exceed what is resident at once, or the surplus workgroups run as a tail.
+template <class K>
+int resident_blocks(K kernel)
 {
-    if constexpr (NB == 0) {
-        if (mode == kMeans) {
-            TraceScope t("filter_block_mean", s);
-            fused_all_kernel<R, VEC, 0, kMeans><<<grid, kBlock, 0, s>>>(p);
-        } else {
-            TraceScope t("filter", s);
-            fused_all_kernel<R, VEC, 0, kFilterOnly><<<grid, kBlock, 0, s>>>(p);
-        }
-    } else {
-        if (mode == kMedian) {
-            TraceScope t("filter_block_mean_median", s);
-            fused_all_kernel<R, VEC, NB, kMedian><<<grid, kBlock, 0, s>>>(p);
-        } else {
-            TraceScope t("filter_block_mean_gram", s);
-            fused_all_kernel<R, VEC, NB, kGram><<<grid, kBlock, 0, s>>>(p);
-        }
+    static int cached = 0;
+    if (cached == 0) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, kBlock, 0) != hipSuccess || nb < 1)
+            nb = 1;
+        cached = nb;
     }
+    return cached;
+}
+
+// grid: in = workgroups wanted per the caller (multiple of the CU count), capped by the number
+// of column chunks; out = workgroups launched.
+template <int R, int VEC, int NB, int MODE>
+hipError_t launch_fused_mode(const FilterParams &p, const char *name, int *grid, int64_t chunks,
+                             hipStream_t s)
+{
+    auto kernel = fused_all_kernel<R, VEC, NB, MODE>;
+    const int cus = num_compute_units();
+    int per_cu = *grid / cus;
+    const int fit = resident_blocks(kernel);
+    if (per_cu > fit) per_cu = fit;
+    if (per_cu < 1) per_cu = 1;
+    int g = per_cu * cus;
+    if (g > kFusedMaxGrid) g = kFusedMaxGrid;
+    if (g > chunks) g = (int)chunks;
+    *grid = g;
+    TraceScope t(name, s);
+    kernel<<<g, kBlock, 0, s>>>(p);
     return hipGetLastError();
 }
 
+template <int R, int VEC, int NB>
+hipError_t launch_fused_rvn(const FilterParams &p, int mode, int *grid, int64_t chunks, hipStream_t s)
+{
+    if constexpr (NB == 0) {
+        if (mode == kMeans)
+            return launch_fused_mode<R, VEC, 0, kMeans>(p, "filter_block_mean", grid, chunks, s);
+        return launch_fused_mode<R, VEC, 0, kFilterOnly>(p, "filter", grid, chunks, s);
+    } else {
+        if (mode == kMedian)
+            return launch_fused_mode<R, VEC, NB, kMedian>(p, "filter_block_mean_median", grid, chunks, s);
+        return launch_fused_mode<R, VEC, NB, kGram>(p, "filter_block_mean_gram", grid, chunks, s);
+    }
+}
+
 template <int R, int VEC>
-hipError_t launch_fused_rv(const FilterParams &p, int mode, int nb, int grid, hipStream_t s)
+hipError_t launch_fused_rv(const FilterParams &p, int mode, int nb, int *grid, int64_t chunks,
+                           hipStream_t s)
 {
     switch (nb) {
-    case 0: return launch_fused_rvn<R, VEC, 0>(p, mode, grid, s);
-    case 1: return launch_fused_rvn<R, VEC, 1>(p, mode, grid, s);
-    case 2: return launch_fused_rvn<R, VEC, 2>(p, mode, grid, s);
-    case 3: return launch_fused_rvn<R, VEC, 3>(p, mode, grid, s);
-    case 4: return launch_fused_rvn<R, VEC, 4>(p, mode, grid, s);
-    case 5: return launch_fused_rvn<R, VEC, 5>(p, mode, grid, s);
-    case 6: return launch_fused_rvn<R, VEC, 6>(p, mode, grid, s);
-    case 7: return launch_fused_rvn<R, VEC, 7>(p, mode, grid, s);
-    case 8: return launch_fused_rvn<R, VEC, 8>(p, mode, grid, s);
+    case 0: return launch_fused_rvn<R, VEC, 0>(p, mode, grid, chunks, s);
+    case 1: return launch_fused_rvn<R, VEC, 1>(p, mode, grid, chunks, s);
+    case 2: return launch_fused_rvn<R, VEC, 2>(p, mode, grid, chunks, s);
+    case 3: return launch_fused_rvn<R, VEC, 3>(p, mode, grid, chunks, s);
+    case 4: return launch_fused_rvn<R, VEC, 4>(p, mode, grid, chunks, s);
+    case 5: return launch_fused_rvn<R, VEC, 5>(p, mode, grid, chunks, s);
+    case 6: return launch_fused_rvn<R, VEC, 6>(p, mode, grid, chunks, s);
+    case 7: return launch_fused_rvn<R, VEC, 7>(p, mode, grid, chunks, s);
+    case 8: return launch_fused_rvn<R, VEC, 8>(p, mode, grid, chunks, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -434,13 +457,13 @@ hipError_t launch_general_rv(const FilterParams &p, bool mean, hipStream_t s)
 }
 
 template <int R>
-hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int mode, int nb, int grid, int vec,
-                    hipStream_t s)
+hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int mode, int nb, int *grid,
+                    int64_t chunks, int vec, hipStream_t s)
 {
     if (fused) {
-        if (vec == 4) return launch_fused_rv<R, 4>(p, mode, nb, grid, s);
-        if (vec == 2) return launch_fused_rv<R, 2>(p, mode, nb, grid, s);
-        return launch_fused_rv<R, 1>(p, mode, nb, grid, s);
+        if (vec == 4) return launch_fused_rv<R, 4>(p, mode, nb, grid, chunks, s);
+        if (vec == 2) return launch_fused_rv<R, 2>(p, mode, nb, grid, chunks, s);
+        return launch_fused_rv<R, 1>(p, mode, nb, grid, chunks, s);
     }
     if (vec == 4) return launch_general_rv<R, 4>(p, mean, s);
     if (vec == 2) return launch_general_rv<R, 2>(p, mean, s);
@@ -509,9 +532,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
     hipError_t e;
     int grid = 0;
     if (fused) {
-        grid = num_compute_units() * (p.n_votes <= 128 ? 4 : 2);
-        if (grid > kFusedMaxGrid) grid = kFusedMaxGrid;
-        if (grid > chunks) grid = (int)chunks;
+        grid = num_compute_units() * (p.n_votes <= 128 ? 4 : 2);   // wanted; trimmed to what is resident
     } else {
         // the redo word (first 256 bytes of the workspace) and the flag words that follow it
         TraceScope t("fill_flags", s);
@@ -522,17 +543,17 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         if (e != hipSuccess) return e;
     }
     switch (p.r) {
-    case 1: e = launch_r<1>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 2: e = launch_r<2>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 3: e = launch_r<3>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 4: e = launch_r<4>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 5: e = launch_r<5>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 6: e = launch_r<6>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 7: e = launch_r<7>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 8: e = launch_r<8>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 9: e = launch_r<9>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 10: e = launch_r<10>(p, mean, fused, mode, nb, grid, vec, s); break;
-    case 11: e = launch_r<11>(p, mean, fused, mode, nb, grid, vec, s); break;
+    case 1: e = launch_r<1>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 2: e = launch_r<2>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 3: e = launch_r<3>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 4: e = launch_r<4>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 5: e = launch_r<5>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 6: e = launch_r<6>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 7: e = launch_r<7>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 8: e = launch_r<8>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 9: e = launch_r<9>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 10: e = launch_r<10>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 11: e = launch_r<11>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

@@ -134,3 +134,74 @@ def test_full_size_resnet18_shape(dx):
     assert host(sel).tolist() == ref_sel.tolist()
     np.testing.assert_allclose(host(scores), ref_scores, rtol=3e-6)
     assert rel_l2(host(out), ref_out) <= TOL
+
+
+def _sample_columns(d, width=4096, pieces=6, seed=0):
+    """Column windows spread over [0, d), including both ends (the ragged tail too)."""
+    rng = np.random.default_rng(seed)
+    starts = [0, d - width] + [int(x) for x in rng.integers(0, d - width, size=pieces - 2)]
+    return [(s, s + width) for s in sorted(starts)]
+
+
+def test_full_size_heavy_tailed_shape(dx):
+    """n = 45, r = 3, q = 5, d = 25,000,000 (Student-t gradients, uniform Byzantine rows):
+    DETOX median (5 vote groups, one pass) bit-exact on sampled column windows; DETOX Bulyan over
+    the 15 votes and vanilla Bulyan over the 45 rows: selections exact (the oracle computes the
+    full-size distances), outputs on sampled windows within 1e-5."""
+    w = workloads.config(4)
+    G = w.matrix()
+    Gd = w.to_device()
+    wins = _sample_columns(w.d)
+    ref_w = oracle.majority_filter(G, 3)
+    med = dx.detox_step(Gd, 3, 5, 5, "coord_median", materialise=False)
+    assert host(med.winner).tolist() == ref_w.tolist()
+    got = host(med.out)
+    for a, b in wins:
+        sub = np.ascontiguousarray(G[:, a:b])
+        ref = oracle.detox_step(sub, 3, 5, "coord_median")[0]
+        assert got[a:b].tobytes() == ref.tobytes()
+    # Bulyan over the votes: selection from full-size distances of the 15 honest votes
+    votes = np.ascontiguousarray(G[ref_w])
+    ref_sel = oracle.bulyan_select(oracle.pairwise_sqdist(votes), 1)
+    bul = dx.detox_step(Gd, 3, 5, 15, "bulyan", f=1, materialise=False)
+    assert host(bul.selected)[:13].tolist() == ref_sel.tolist()
+    got = host(bul.out)
+    for a, b in wins:
+        ref = oracle.bulyan_trim(np.ascontiguousarray(votes[:, a:b]), ref_sel, 11)
+        assert rel_l2(got[a:b], ref) <= TOL
+    del votes
+    # vanilla Bulyan over all 45 rows
+    ref_sel = oracle.bulyan_select(oracle.pairwise_sqdist(G), 5)
+    out, sel = dx.robust_bulyan(Gd, 5)
+    assert host(sel).tolist() == ref_sel.tolist()
+    got = host(out)
+    for a, b in wins:
+        ref = oracle.bulyan_trim(np.ascontiguousarray(G[:, a:b]), ref_sel, 25)
+        assert rel_l2(got[a:b], ref) <= TOL
+
+
+def test_full_size_105_node_shape(dx):
+    """n = 105, r = 5, q = 10 (two per group), d = 25,000,000: DETOX geometric median over 7 block
+    means against the full oracle; vanilla coordinate median bit-exact on sampled windows; vanilla
+    Multi-Krum selection against full-size oracle distances."""
+    w = workloads.config(5)
+    G = w.matrix()
+    Gd = w.to_device()
+    spec = w.detox[0]
+    ref_out, ref_w, _ = oracle.detox_step(G, 5, 7, "geomedian", iters=spec["iters"], eps=spec["eps"])
+    b = dx.detox_step(Gd, 5, 10, 7, "geomedian", iters=spec["iters"], eps=spec["eps"], materialise=False)
+    assert host(b.winner).tolist() == ref_w.tolist()
+    assert rel_l2(host(b.out), ref_out) <= TOL
+    wins = _sample_columns(w.d)
+    got = host(dx.robust_coord_median(Gd))
+    for a, c in wins:
+        assert got[a:c].tobytes() == oracle.coord_median(np.ascontiguousarray(G[:, a:c])).tobytes()
+    v = w.vanilla[1]
+    ref_sel, ref_scores = oracle.multikrum_from_dist(oracle.pairwise_sqdist(G), v["f"], v["m"])
+    out, sel, scores = dx.robust_multikrum(Gd, v["f"], v["m"])
+    assert host(sel).tolist() == ref_sel.tolist()
+    np.testing.assert_allclose(host(scores), ref_scores, rtol=3e-6)
+    got = host(out)
+    for a, c in wins:
+        ref = G[ref_sel][:, a:c].astype(np.float64).sum(axis=0) / v["m"]
+        assert rel_l2(got[a:c], ref) <= TOL
