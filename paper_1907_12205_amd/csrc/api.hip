@@ -52,7 +52,7 @@ size_t aggregator_ws_bytes(int64_t count)
     const size_t c2 = (size_t)(count * count);
     return round_up(gram_partial_bytes(count)) + round_up(c2 * sizeof(double)) * 3 +
            round_up(c2 * sizeof(int32_t)) + round_up((size_t)count * sizeof(double)) * 2 +
-           round_up((size_t)count * sizeof(int32_t));
+           round_up((size_t)count * sizeof(int32_t)) * 2;
 }
 
 struct AggWs {
@@ -60,6 +60,7 @@ struct AggWs {
     double *Gm;
     SelectScratch sc;
     int32_t *row_index;   // count entries: row table of a vote row set
+    int32_t *trim_rows;   // count entries: physical rows of Bulyan's selected votes
 };
 
 AggWs carve_aggregator(void *ws, int64_t count)
@@ -75,6 +76,7 @@ AggWs carve_aggregator(void *ws, int64_t count)
     a.sc.scores = c.take<double>((size_t)count);
     a.sc.weights = c.take<double>((size_t)count);
     a.row_index = c.take<int32_t>((size_t)count);
+    a.trim_rows = c.take<int32_t>((size_t)count);
     return a;
 }
 
@@ -128,7 +130,7 @@ int bulyan_impl(const RowSet &rs, int f, float *out, int32_t *selected, void *ws
     const int theta = rs.count - 2 * f, beta = theta - 2 * f;
     hipError_t e = gram_for(rs, a, fg, s);
     if (e == hipSuccess) e = launch_bulyan_select(a.Gm, rs.count, f, a.sc, selected, s);
-    if (e == hipSuccess) e = launch_bulyan_trim(rs, selected, theta, beta, out, s);
+    if (e == hipSuccess) e = launch_bulyan_trim(rs, selected, a.trim_rows, theta, beta, out, s);
     return status_of(e);
 }
 
@@ -387,13 +389,13 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
             const int32_t *index = winner;
             if (vote_perm) {
                 int32_t *table = aw.row_index;
-                e = launch_compose_index(winner, vote_perm, (int)B, table, s);
+                e = launch_compose_index(winner, (int)groups, vote_perm, (int)B, table, s);
                 if (e != hipSuccess) return status_of(e);
                 index = table;
             }
-            rs = RowSet{G, d, ld, (int)B, index, nullptr, nullptr, 0};
+            rs = RowSet{G, d, ld, (int)n, (int)B, index, nullptr, nullptr, 0};
         } else {
-            rs = RowSet{G, d, ld, (int)B, nullptr, winner, vote_perm, (int)groups};
+            rs = RowSet{G, d, ld, (int)n, (int)B, nullptr, winner, vote_perm, (int)groups};
         }
     }
     FusedGram fg;

@@ -47,6 +47,7 @@ inline int row_vec_width(const void *base, int64_t ld)
 struct RowSet {
     const float *base;          // the matrix the rows are read from
     int64_t d, ld;
+    int base_rows;              // rows of that matrix (bound for indices read from device memory)
     int count;                  // number of logical rows
     const int32_t *index;       // dev or null: logical row b = row index[b] of base (-1: zeros)
     const int32_t *winner;      // dev or null; non-null: logical row b = mean of the votes of
@@ -56,7 +57,7 @@ struct RowSet {
 };
 inline RowSet direct_rows(const float *X, int64_t count, int64_t d, int64_t ld)
 {
-    return RowSet{X, d, ld, (int)count, nullptr, nullptr, nullptr, 0};
+    return RowSet{X, d, ld, (int)count, (int)count, nullptr, nullptr, nullptr, 0};
 }
 
 // ---- filter.hip ------------------------------------------------------------
@@ -137,9 +138,10 @@ hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const Se
                                 int32_t *selected, hipStream_t s);
 hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double eps,
                             double *weights, hipStream_t s);
-// index[b] = winner[vote_perm[b]]: the row table of the votes taken in vote order.
-hipError_t launch_compose_index(const int32_t *winner, const int32_t *vote_perm, int n,
-                                int32_t *index, hipStream_t s);
+// out[b] = table[pick[b]] for b < n (e.g. winner[vote_perm[b]]: the row table of the votes taken
+// in vote order).
+hipError_t launch_compose_index(const int32_t *table, int table_len, const int32_t *pick, int n,
+                                int32_t *out, hipStream_t s);
 // out[c] = fp32( sum_i (double) row[rows[i]][c] / m ), logical rows listed in device memory.
 hipError_t launch_rows_mean(const RowSet &rs, const int32_t *rows, int m, float *out, hipStream_t s);
 // out[c] = fp32( sum_j weights[j] * (double) row[j][c] ) over all logical rows.
@@ -149,7 +151,8 @@ hipError_t launch_weighted_sum(const RowSet &rs, const double *weights, float *o
 // Coordinate-wise median of all logical rows.  run_if (dev, may be null): skip unless *run_if.
 hipError_t launch_coord_median(const RowSet &rs, float *out, const int *run_if, hipStream_t s);
 // Per coordinate: median of the theta listed logical rows, mean of the beta values closest to it.
-hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int theta, int beta, float *out,
-                              hipStream_t s);
+//   scratch: dev, theta int32 (used when rs carries an index table).
+hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, int theta,
+                              int beta, float *out, hipStream_t s);
 
 }  // namespace detox

@@ -260,20 +260,24 @@ hipError_t launch_combine(const RowSet &rs, const int32_t *rows, const double *w
     return hipGetLastError();
 }
 
-__global__ void compose_index_kernel(const int32_t *winner, const int32_t *vote_perm, int n,
-                                     int32_t *index)
+// out[b] = table[pick[b]], pick clamped to [0, table_len) so that a bad entry cannot fault.
+__global__ void compose_index_kernel(const int32_t *table, int table_len, const int32_t *pick, int n,
+                                     int32_t *out)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < n) index[b] = winner[vote_perm[b]];
+    if (b >= n) return;
+    int i = pick[b];
+    i = i < 0 ? 0 : (i >= table_len ? table_len - 1 : i);
+    out[b] = table[i];
 }
 
 }  // namespace
 
-hipError_t launch_compose_index(const int32_t *winner, const int32_t *vote_perm, int n,
-                                int32_t *index, hipStream_t s)
+hipError_t launch_compose_index(const int32_t *table, int table_len, const int32_t *pick, int n,
+                                int32_t *out, hipStream_t s)
 {
     TraceScope t("compose_index", s);
-    compose_index_kernel<<<(n + 255) / 256, 256, 0, s>>>(winner, vote_perm, n, index);
+    compose_index_kernel<<<(n + 255) / 256, 256, 0, s>>>(table, table_len, pick, n, out);
     return hipGetLastError();
 }
 

@@ -7,15 +7,18 @@
 // Batcher's odd-even merge sorting network, generated at compile time for the exact N so that
 // every index is a constant and the values never leave the register file.  Where only the median
 // is used the compiler drops the comparators that cannot reach it.
+#include <type_traits>
+
 #include "rows.cuh"
 #include "sortnet.cuh"
 
 namespace detox {
 namespace {
 
-// The N values per coordinate are logical rows rows[0..N-1] of rs (rows == nullptr: 0..N-1).
+// The N values per coordinate come from rows phys[0..N-1] of rs.base (-1: zeros); with MEANS,
+// phys lists logical rows (block means formed on the fly).
 template <int N, int VEC, bool TRIM, bool MEANS>
-__global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int32_t *rows, int beta,
+__global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int32_t *phys, int beta,
                                                             float *out, const int *run_if)
 {
     if (run_if && *run_if == 0) return;   // uniform
@@ -24,17 +27,41 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
     if (left <= 0) return;
     const int valid = left >= VEC ? VEC : (int)left;
     uint32_t k[N][VEC];
+    // The load phase is written without branches inside the row loop (row lists and index
+    // tables are always present, a zero-vector row is a select, full and ragged vectors are two
+    // copies of the loop): any branch per row makes the compiler wait for each load in turn.
+    // phys[i] = row of rs.base holding the i-th value (-1: the zero vector), one contiguous
+    // table so that the scalar loads batch; zero rows are remembered in a uniform bit mask.
+    unsigned long long zero_lo = 0ull, zero_hi = 0ull;
+    auto load_all = [&](auto full) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            float x[VEC];
+            if constexpr (MEANS) {
+                int b = phys[i];
+                b = b < 0 ? 0 : (b >= rs.count ? rs.count - 1 : b);
+                row_load<true, VEC>(rs, b, col, valid, x);
+            } else {
+                int r = phys[i];   // may come from a selection kernel: clamped, so it cannot fault
+                if (r < 0) {
+                    if (i < 64) zero_lo |= 1ull << (i & 63); else zero_hi |= 1ull << (i & 63);
+                }
+                r = r < 0 ? 0 : (r >= rs.base_rows ? rs.base_rows - 1 : r);
+                load_floats<VEC>(rs.base + (int64_t)r * rs.ld + col, decltype(full)::value ? VEC : valid, x);
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) k[i][v] = __float_as_uint(x[v]);
+        }
+    };
+    if (valid == VEC)
+        load_all(std::true_type{});
+    else
+        load_all(std::false_type{});
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        int b = i;
-        if (rows) {   // written by the selection kernel; clamped so a bad index cannot fault
-            b = rows[i];
-            b = b < 0 ? 0 : (b >= rs.count ? rs.count - 1 : b);
-        }
-        float x[VEC];
-        row_load<MEANS, VEC>(rs, b, col, valid, x);
+        const bool zero = (((i < 64 ? zero_lo : zero_hi) >> (i & 63)) & 1ull) != 0ull;
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) k[i][v] = order_key(__float_as_uint(x[v]));
+        for (int v = 0; v < VEC; ++v) k[i][v] = order_key(zero ? 0u : k[i][v]);
     }
     sort_keys<N, VEC>(k);
     // shifted[i] = k[i + beta] (beta is uniform): log2(N) conditional shifts by powers of two
@@ -166,36 +193,79 @@ DETOX_DECL_PART(0) DETOX_DECL_PART(1) DETOX_DECL_PART(2) DETOX_DECL_PART(3)
 DETOX_DECL_PART(4) DETOX_DECL_PART(5) DETOX_DECL_PART(6) DETOX_DECL_PART(7)
 #undef DETOX_DECL_PART
 
+// 0, 1, ..., kMaxCount-1 in device memory: stands in for an absent row list / index table so that
+// the kernels never branch on their presence.  No kernel names the variable (they receive its
+// address as an argument), so it is marked used and given external linkage: otherwise the
+// device compiler drops it and the address lookup below has nothing to find.
+struct IdentityTable {
+    int32_t v[kMaxCount];
+    constexpr IdentityTable() : v()
+    {
+        for (int i = 0; i < kMaxCount; ++i) v[i] = i;
+    }
+};
+__device__ __attribute__((used)) IdentityTable g_detox_identity_table = IdentityTable();
+
 namespace {
-hipError_t order_stat(bool trim, int n, const RowSet &rs, const int32_t *rows, int beta, float *out,
-                      const int *run_if, hipStream_t s)
+const int32_t *identity_table()
+{
+    static const int32_t *cached[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    if (!cached[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_detox_identity_table)) != hipSuccess) return nullptr;
+        cached[dev] = static_cast<const int32_t *>(p);
+    }
+    return cached[dev];
+}
+
+// rows: logical rows to use (dev, n entries; null = 0..n-1).  scratch: dev, n int32, needed only
+// when both a row list and an index table are present (their composition is written there).
+hipError_t order_stat(bool trim, int n, RowSet rs, const int32_t *rows, int32_t *scratch, int beta,
+                      float *out, const int *run_if, hipStream_t s)
 {
     if (n < 1 || n > kMaxCount) return hipErrorInvalidValue;
+    const int32_t *phys = rows;
+    if (!rs.means() && rs.index) {
+        if (rows) {
+            if (!scratch) return hipErrorInvalidValue;
+            hipError_t e = launch_compose_index(rs.index, rs.count, rows, n, scratch, s);   // index[rows[i]]
+            if (e != hipSuccess) return e;
+            phys = scratch;
+        } else {
+            phys = rs.index;
+        }
+    }
+    if (!phys) {
+        phys = identity_table();
+        if (!phys) return hipErrorInvalidDeviceFunction;
+    }
     int vec = row_vec_width(rs.base, rs.ld);
     const int vo = row_vec_width(out, 4);
     vec = vo < vec ? vo : vec;
     switch ((n - 1) % kSortnetParts) {
-    case 0: return order_stat_part0(trim, n, rs, rows, beta, out, run_if, vec, s);
-    case 1: return order_stat_part1(trim, n, rs, rows, beta, out, run_if, vec, s);
-    case 2: return order_stat_part2(trim, n, rs, rows, beta, out, run_if, vec, s);
-    case 3: return order_stat_part3(trim, n, rs, rows, beta, out, run_if, vec, s);
-    case 4: return order_stat_part4(trim, n, rs, rows, beta, out, run_if, vec, s);
-    case 5: return order_stat_part5(trim, n, rs, rows, beta, out, run_if, vec, s);
-    case 6: return order_stat_part6(trim, n, rs, rows, beta, out, run_if, vec, s);
-    default: return order_stat_part7(trim, n, rs, rows, beta, out, run_if, vec, s);
+    case 0: return order_stat_part0(trim, n, rs, phys, beta, out, run_if, vec, s);
+    case 1: return order_stat_part1(trim, n, rs, phys, beta, out, run_if, vec, s);
+    case 2: return order_stat_part2(trim, n, rs, phys, beta, out, run_if, vec, s);
+    case 3: return order_stat_part3(trim, n, rs, phys, beta, out, run_if, vec, s);
+    case 4: return order_stat_part4(trim, n, rs, phys, beta, out, run_if, vec, s);
+    case 5: return order_stat_part5(trim, n, rs, phys, beta, out, run_if, vec, s);
+    case 6: return order_stat_part6(trim, n, rs, phys, beta, out, run_if, vec, s);
+    default: return order_stat_part7(trim, n, rs, phys, beta, out, run_if, vec, s);
     }
 }
 }  // namespace
 
 hipError_t launch_coord_median(const RowSet &rs, float *out, const int *run_if, hipStream_t s)
 {
-    return order_stat(false, rs.count, rs, nullptr, 0, out, run_if, s);
+    return order_stat(false, rs.count, rs, nullptr, nullptr, 0, out, run_if, s);
 }
 
-hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int theta, int beta, float *out,
-                              hipStream_t s)
+hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, int theta,
+                              int beta, float *out, hipStream_t s)
 {
-    return order_stat(true, theta, rs, rows, beta, out, nullptr, s);
+    return order_stat(true, theta, rs, rows, scratch, beta, out, nullptr, s);
 }
 
 #endif

@@ -205,3 +205,33 @@ def test_full_size_105_node_shape(dx):
     for a, c in wins:
         ref = G[ref_sel][:, a:c].astype(np.float64).sum(axis=0) / v["m"]
         assert rel_l2(got[a:c], ref) <= TOL
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 5, 63, 64, 255, 257, 1023, 1025])
+def test_tiny_dimensions(dx, d):
+    """Every entry point on dimensions smaller than one workgroup's columns, including d = 1."""
+    w = workloads.config(3, d=d)
+    G = w.matrix()
+    for materialise in (True, False):
+        for spec in (dict(B=5, aggregator="multikrum", f=1, m=3), dict(B=5, aggregator="coord_median"),
+                     dict(B=15, aggregator="bulyan", f=2), dict(B=5, aggregator="geomedian", iters=10)):
+            _run(dx, w, spec, G=G, materialise=materialise)
+    Gd = dev_matrix(G)
+    ref_out, ref_sel, _ = oracle.multikrum(G, 5, 40)
+    out, sel, _ = dx.robust_multikrum(Gd, 5, 40)
+    # at tiny d different honest groups can tie exactly or nearly; compare what is unique
+    D = oracle.pairwise_sqdist(G)
+    scores = oracle.krum_scores(D, 5)
+    assert np.allclose(np.sort(scores[host(sel)]), np.sort(scores[ref_sel]), rtol=1e-5, atol=1e-12)
+    assert host(dx.robust_coord_median(Gd)).tobytes() == oracle.coord_median(G).tobytes()
+
+
+def test_single_group_and_single_row(dx):
+    X = workloads.distinct_rows(1, 1, 300)
+    assert host(dx.robust_coord_median(dev_matrix(X))).tobytes() == X[0].tobytes()
+    assert rel_l2(host(dx.robust_geomedian(dev_matrix(X))), X[0]) <= TOL
+    G = np.repeat(X, 3, axis=0)
+    b = dx.detox_step(dev_matrix(G), 3, 0, 1, "coord_median")
+    assert host(b.winner).tolist() == [0] and host(b.out).tobytes() == X[0].tobytes()
+    b = dx.detox_step(dev_matrix(G), 3, 0, 1, "geomedian", materialise=False)
+    assert rel_l2(host(b.out), X[0]) <= TOL
