@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--d", type=int, default=None, help="override the dimension (debugging)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-vanilla", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the other aggregators' timings")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the parameter-server step on ONE GPU (the step has no "
@@ -157,6 +158,32 @@ def main():
                    "detox_speedup": round(ms_v / ms_step, 3)}
         log(f"[bench] vanilla {v['aggregator']}: {ms_v:.4f} ms/step; DETOX is {ms_v / ms_step:.2f}x faster")
 
+    # ---- the other rows of the hot path on the same resident matrix (reported, not the value) --
+    others = []
+    if not args.no_others:
+        def timed(name, fn, rows):
+            ms, _ = time_steps(fn, max(args.steps // 2, 3), 2, torch)
+            others.append({"path": name, "ms_per_step": round(ms, 5),
+                           "GBps_aggregated": round(in_bytes / (ms * 1e-3) / 1e9, 1),
+                           "hbm_frac_algorithmic": round(rows * d * 4 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+        groups = n // r
+        out_o = torch.empty(d, dtype=torch.float32, device=G.device)
+        timed("filter only (votes)", lambda: dx.detox_majority_filter(G, r), n)
+        if groups >= 5:
+            bm = StepBuffers(n, d, r, 5, G.device, materialise=False)
+            timed("DETOX coord-median, B=5 (one pass)", lambda: dx.detox_step(G, r, q, 5, "coord_median", buffers=bm), n + 1)
+            timed("DETOX geometric median, B=5, 50 iterations", lambda: dx.detox_step(G, r, q, 5, "geomedian", buffers=bm), n + groups + 1)
+        if groups >= 7:
+            bb = StepBuffers(n, d, r, groups, G.device, materialise=False)
+            timed(f"DETOX Bulyan over the {groups} votes, f=1", lambda: dx.detox_step(G, r, q, groups, "bulyan", f=1, buffers=bb),
+                  n + groups + (groups - 2) + 1)
+        timed(f"vanilla coord-median over {n} rows", lambda: dx.robust_coord_median(G, out=out_o), n + 1)
+        fb = min(q, (n - 3) // 4)
+        ws_b = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
+        timed(f"vanilla Bulyan over {n} rows, f={fb}", lambda: dx.robust_bulyan(G, fb, out=out_o, ws=ws_b), n + (n - 2 * fb) + 1)
+        for o in others:
+            log(f"[bench] {o['path']}: {o['ms_per_step']:.4f} ms/step, {o['hbm_frac_algorithmic'] * 100:.1f}% of HBM peak (algorithmic bytes)")
+
     # ---- CPU oracle on the host cores (a reported baseline, not the target) ------------------
     cpu = None
     if not args.no_cpu:
@@ -191,7 +218,7 @@ def main():
         "step_hbm_frac_algorithmic": (round(step_alg_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                                       if step_alg_bytes else None),
         "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
-        "roofline": roofline, "vanilla": vanilla, "cpu_baseline": cpu,
+        "roofline": roofline, "vanilla": vanilla, "other_paths": others, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
 
