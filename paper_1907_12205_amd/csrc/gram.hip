@@ -20,6 +20,13 @@ constexpr int kMaxGramWaves = 4096;   // upper bound used to size the workspace
 
 __host__ __device__ constexpr int tiles_for(int T) { return T * (T + 1) / 2; }
 
+// Workgroups (of 4 wavefronts) per CU for the MFMA kernel, from sweeps on MI355X: few row
+// tiles mean few loads in flight per wavefront, so more wavefronts are needed to cover the HBM
+// latency; from 5 row tiles on the kernel is MFMA-bound and one wavefront per SIMD is best.
+constexpr int mfma_blocks_per_cu(int T) { return T <= 2 ? 4 : (T <= 4 ? 3 : 1); }
+// Bound on the wavefront partials (sizes the workspace; assumes at most 256 CUs, more are clamped).
+constexpr int mfma_max_waves(int T) { return 256 * mfma_blocks_per_cu(T) * (kBlock / kWave); }
+
 // ---------------------------------------------------------------------------------------
 // count <= 8: fp64 on the vector ALUs
 // ---------------------------------------------------------------------------------------
@@ -310,7 +317,7 @@ size_t gram_partial_bytes(int64_t count)
 {
     if (count <= 8) return (size_t)kMaxGramWaves * (size_t)(count * (count + 1) / 2) * sizeof(double);
     const int T = (int)((count + 15) / 16);
-    return (size_t)kMaxGramWaves * (size_t)tiles_for(T) * 256 * sizeof(float) +
+    return (size_t)mfma_max_waves(T) * (size_t)tiles_for(T) * 256 * sizeof(float) +
            (size_t)kReduceSlices * (size_t)tiles_for(T) * 256 * sizeof(double);
 }
 
@@ -332,8 +339,8 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
         return hipGetLastError();
     }
     const int T = (int)((count + 15) / 16);
-    int grid = cus * (T <= 4 ? 4 : 2);
-    if (grid * (kBlock / kWave) > kMaxGramWaves) grid = kMaxGramWaves / (kBlock / kWave);
+    int grid = cus * mfma_blocks_per_cu(T);
+    if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
     const int64_t steps = (d + 31) / 32;
     const int64_t need = (steps + kBlock / kWave - 1) / (kBlock / kWave);
     if (grid > need) grid = (int)need;
@@ -353,7 +360,7 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
     if (e != hipSuccess) return e;
     const int elems = tiles_for(T) * 256;
     // the slice sums live behind the largest possible set of wavefront partials
-    double *slices = reinterpret_cast<double *>(pp + (size_t)kMaxGramWaves * elems);
+    double *slices = reinterpret_cast<double *>(pp + (size_t)mfma_max_waves(T) * elems);
     {
         TraceScope t("gram_reduce", s);
         gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
