@@ -177,6 +177,13 @@ def main():
             bb = StepBuffers(n, d, r, groups, G.device, materialise=False)
             timed(f"DETOX Bulyan over the {groups} votes, f=1", lambda: dx.detox_step(G, r, q, groups, "bulyan", f=1, buffers=bb),
                   n + groups + (groups - 2) + 1)
+        if groups >= 14:
+            # the hierarchy the paper deployed (Section 5.2): robust aggregator inside vote groups, mean across
+            ws_h = torch.empty(dx.workspace_bytes("step", n, d, groups) + 4 * groups + 512, dtype=torch.uint8, device=G.device)
+            timed(f"DETOX A0=Multi-Krum(f=2,m=3) on {groups // 2}+{groups - groups // 2} votes, A1=mean",
+                  lambda: dx.detox_step_robust_blocks(G, r, 2, "multikrum", 2, 3, out=out_o, ws=ws_h), n + groups + 2 * 3 + 2 + 2 + 1)
+            timed(f"DETOX A0=Bulyan(f=2) on all {groups} votes",
+                  lambda: dx.detox_step_robust_blocks(G, r, 1, "bulyan", 2, out=out_o, ws=ws_h), n + groups + (groups - 4) + 1)
         timed(f"vanilla coord-median over {n} rows", lambda: dx.robust_coord_median(G, out=out_o), n + 1)
         fb = min(q, (n - 3) // 4)
         ws_b = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)

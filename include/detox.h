@@ -200,6 +200,29 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
                int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
                int32_t *selected, float *out, void *ws, size_t ws_bytes, void *stream);
 
+/* The hierarchy the paper deployed (Section 5.2, setups 2 and 3; Appendix B.1): Algorithm 2 with
+ * A0 = a robust aggregator applied inside every vote group and A1 = mean over the B results.
+ * The votes, in the order vote_perm, are cut into B vote groups as in detox_block_mean (15 votes
+ * in 2 groups: 7 and 8); group b's votes are aggregated by Multi-Krum(f, m) or Bulyan(f) and
+ *   out = fp32( sum_b (double) block_out_b / B ),  added in group order.
+ * A vote without majority enters its group as the zero vector.
+ *   a0         DETOX_AGG_MULTIKRUM or DETOX_AGG_BULYAN
+ *   f, m       per group; every group must satisfy the aggregator's requirement
+ *              (size >= 2f+3 and 1 <= m <= size-f, or size >= 4f+3); m < 0 means size - f
+ *   winner     dev, n/r int32, out
+ *   block_out  dev, B x d (ldb), out: the per-group results; may be NULL when B = 1
+ *   selected   dev, n/r int32, out: group b's selection (positions inside the group, in
+ *              selection order) starts at its first vote position floor(b*V/B); Multi-Krum
+ *              fills m entries there, Bulyan size-2f
+ *   out        dev, d floats
+ *   ws         DETOX_OP_STEP bytes with count = n and aux = the largest group size
+ *              ceil((n/r)/B)                                                              */
+int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, int r,
+                             const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
+                             int a0, int f, int m, int32_t *winner, float *block_out,
+                             int64_t ldb, int32_t *selected, float *out, void *ws,
+                             size_t ws_bytes, void *stream);
+
 /* Per-kernel timing.  While enabled, every kernel the library launches is
  * bracketed by hipEvents on the caller's stream (this adds a few microseconds
  * per launch; leave it off when timing whole steps).  After synchronising the

@@ -208,3 +208,30 @@ def detox_step(G, r, B, aggregator, f=0, m=1, iters=50, eps=1e-8, group_rows=Non
     else:
         raise ValueError(aggregator)
     return out, winner, Zhat
+
+
+def detox_step_robust_blocks(G, r, B, a0, f, m=-1, group_rows=None, vote_perm=None):
+    """Algorithm 2 as deployed in Section 5.2 (setups 2 and 3): A0 = Multi-Krum / Bulyan inside
+    every vote group, A1 = mean of the group results (fp64 sum in group order, cast once).
+    Returns (out, winner, block_out[B x d], selections: list of per-group index arrays)."""
+    winner, Z = majority_filter(G, r, group_rows, materialise=True)
+    V = winner.size
+    order = np.arange(V) if vote_perm is None else np.asarray(vote_perm)
+    outs, sels = [], []
+    for b in range(B):
+        lo, hi = (b * V) // B, ((b + 1) * V) // B
+        X = np.ascontiguousarray(Z[order[lo:hi]])
+        if a0 == "multikrum":
+            o, sel, _ = multikrum(X, f, (hi - lo) - f if m < 0 else m)
+        elif a0 == "bulyan":
+            o, sel = bulyan(X, f)
+        else:
+            raise ValueError(a0)
+        outs.append(o)
+        sels.append(sel)
+    block_out = np.stack(outs)
+    acc = np.zeros(G.shape[1], dtype=np.float64)
+    for o in outs:
+        acc += o.astype(np.float64)
+    out = (acc / B).astype(np.float32) if B > 1 else outs[0]
+    return out, winner, block_out, sels

@@ -16,7 +16,8 @@ AGG = dict(multikrum=0, bulyan=1, coord_median=2, geomedian=3)
 EXPORTS = ["detox_strerror", "detox_last_hip_error", "detox_workspace_bytes",
            "detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
            "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan", "robust_coord_median",
-           "robust_geomedian", "detox_step", "detox_trace_enable", "detox_trace_read"]
+           "robust_geomedian", "detox_step", "detox_step_robust_blocks", "detox_trace_enable",
+           "detox_trace_read"]
 
 
 class DetoxError(RuntimeError):
@@ -60,6 +61,9 @@ def lib() -> ctypes.CDLL:
         L.robust_geomedian.argtypes = [vp, i64, i64, i64, i32, dbl, vp, vp, sz, vp]
         L.detox_step.argtypes = [vp, i64, i64, i64, i32, i32, vp, i64, vp, i32, i32, i32, i32, dbl,
                                  vp, vp, i64, vp, vp, vp, sz, vp]
+        L.detox_step_robust_blocks.argtypes = [vp, i64, i64, i64, i32, vp, i64, vp, i32, i32, i32, vp, vp, i64,
+                                               vp, vp, vp, sz, vp]
+        L.detox_step_robust_blocks.restype = i32
         L.detox_trace_enable.argtypes = [i32]
         L.detox_trace_enable.restype = None
         L.detox_trace_read.argtypes = [ctypes.POINTER(_TraceRecord), i32]
@@ -254,6 +258,27 @@ def detox_step(G, r: int, q: int, B: int, aggregator: str, f: int = -1, m: int =
                           _ptr(b.ws), b.ws.numel(), _stream())
     _check(rc, "detox_step")
     return b
+
+
+def detox_step_robust_blocks(G, r: int, B: int, a0: str, f: int, m: int = -1, group_rows=None, vote_perm=None,
+                             out=None, ws=None):
+    """Robust aggregator inside every vote group, mean over the groups.
+    Returns (out[d], winner[n/r], block_out[B x d] or None, selected[n/r])."""
+    torch = _torch()
+    p, n, d, ld = _matrix(G)
+    gr, vp = _i32(group_rows, G.device), _i32(vote_perm, G.device)
+    groups = n // max(r, 1)
+    winner = torch.empty(max(groups, 1), dtype=torch.int32, device=G.device)
+    selected = torch.full((max(groups, 1),), -1, dtype=torch.int32, device=G.device)
+    block_out = torch.empty((B, d), dtype=torch.float32, device=G.device) if B > 1 else None
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=G.device)
+    largest = -(-groups // max(B, 1))
+    ws, nb = _ws(ws, workspace_bytes("step", n, d, largest) + 4 * groups + 512, G.device)
+    rc = lib().detox_step_robust_blocks(p, n, d, ld, r, _ptr(gr), B, _ptr(vp), AGG[a0], f, m, _ptr(winner),
+                                        _ptr(block_out), d, _ptr(selected), _ptr(out), _ptr(ws), nb, _stream())
+    _check(rc, "detox_step_robust_blocks")
+    return out, winner, block_out, selected
 
 
 @contextlib.contextmanager

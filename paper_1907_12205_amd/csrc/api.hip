@@ -413,6 +413,59 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     }
 }
 
+int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, int r,
+                             const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
+                             int a0, int f, int m, int32_t *winner, float *block_out,
+                             int64_t ldb, int32_t *selected, float *out, void *ws,
+                             size_t ws_bytes, void *stream)
+{
+    int rc = check_filter_args(G, n, d, ld, r);
+    if (rc) return rc;
+    const int64_t groups = n / r;
+    if (!winner || !out || !selected || B < 1 || B > groups || f < 0) return DETOX_EINVAL;
+    if (a0 != DETOX_AGG_MULTIKRUM && a0 != DETOX_AGG_BULYAN) return DETOX_EINVAL;
+    if (B > 1 && (!block_out || ldb < d)) return DETOX_EINVAL;
+    const int64_t smallest = groups / B, largest = (groups + B - 1) / B;
+    if (largest > kMaxCount) return DETOX_EINVAL;
+    if (a0 == DETOX_AGG_MULTIKRUM) {
+        if (smallest < 2 * (int64_t)f + 3 || m == 0 || m > smallest - f) return DETOX_EPRECOND;
+    } else if (smallest < 4 * (int64_t)f + 3) {
+        return DETOX_EPRECOND;
+    }
+    const size_t fbytes = filter_bytes(groups);
+    const size_t tbytes = round_up((size_t)groups * sizeof(int32_t));
+    if (!ws_ok(ws, ws_bytes, fbytes + tbytes + aggregator_ws_bytes(largest))) return DETOX_EWORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const FilterWs fw = carve_filter_ws(ws, groups);
+    FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
+    hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, nullptr, s);
+    if (e != hipSuccess) return status_of(e);
+    // row table of the votes in vote order: winner itself, or winner o vote_perm
+    const int32_t *table = winner;
+    if (vote_perm) {
+        int32_t *t = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + fbytes);
+        e = launch_compose_index(winner, (int)groups, vote_perm, (int)groups, t, s);
+        if (e != hipSuccess) return status_of(e);
+        table = t;
+    }
+    void *aws = static_cast<char *>(ws) + fbytes + tbytes;
+    for (int64_t b = 0; b < B; ++b) {
+        const int64_t lo = (b * groups) / B, hi = ((b + 1) * groups) / B;
+        const RowSet rs{G, d, ld, (int)n, (int)(hi - lo), table + lo, nullptr, nullptr, 0};
+        float *target = B == 1 ? out : block_out + b * ldb;
+        if (a0 == DETOX_AGG_MULTIKRUM)
+            rc = multikrum_impl(rs, f, m < 0 ? (int)(hi - lo) - f : m, target, selected + lo, nullptr,
+                                aws, FusedGram{}, s);
+        else
+            rc = bulyan_impl(rs, f, target, selected + lo, aws, FusedGram{}, s);
+        if (rc) return rc;
+    }
+    if (B > 1) e = launch_rows_mean(direct_rows(block_out, B, d, ldb), nullptr, (int)B, out, s);
+    return status_of(e);
+}
+
 void detox_trace_enable(int on)
 {
     g_trace_on = on != 0;

@@ -214,8 +214,10 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const i
     for (int k = 0; k < m; ++k) {
         int b = k;
         if constexpr (!WEIGHTED) {
-            b = rows[k];   // written by the selection kernel; clamped so a bad index cannot fault
-            b = b < 0 ? 0 : (b >= rs.count ? rs.count - 1 : b);
+            if (rows) {   // written by the selection kernel; clamped so a bad index cannot fault
+                b = rows[k];
+                b = b < 0 ? 0 : (b >= rs.count ? rs.count - 1 : b);
+            }
         }
         float x[VEC];
         row_load<MEANS, VEC>(rs, b, col, valid, x);

@@ -235,3 +235,29 @@ def test_single_group_and_single_row(dx):
     assert host(b.winner).tolist() == [0] and host(b.out).tobytes() == X[0].tobytes()
     b = dx.detox_step(dev_matrix(G), 3, 0, 1, "geomedian", materialise=False)
     assert rel_l2(host(b.out), X[0]) <= TOL
+
+
+ROBUST_BLOCKS = [("multikrum", 2, 2, 3), ("multikrum", 2, 1, -1), ("multikrum", 1, 5, 8), ("multikrum", 3, 1, 2),
+                 ("bulyan", 1, 2, -1), ("bulyan", 1, 3, -1), ("bulyan", 2, 1, -1), ("bulyan", 3, 0, -1)]
+
+
+@pytest.mark.parametrize("a0,B,f,m", ROBUST_BLOCKS)
+def test_robust_aggregator_inside_vote_groups(dx, a0, B, f, m):
+    """The hierarchy of Section 5.2 (A0 robust, A1 mean), e.g. Multi-Krum on 7 + 8 votes and Bulyan
+    on all 15 (Appendix B.1), with a group without majority and a vote permutation."""
+    w = workloads.config(3, d=40009)
+    G = w.matrix()
+    G[12] = 7; G[13] = 8; G[14] = 9          # group 4 has no majority: its vote is the zero vector
+    rng = np.random.default_rng(B * 10 + f)
+    for vote_perm in (None, rng.permutation(15).astype(np.int32)):
+        ref_out, ref_w, ref_blocks, ref_sels = oracle.detox_step_robust_blocks(G, 3, B, a0, f, m, vote_perm=vote_perm)
+        for ld in (None, 40064):
+            out, winner, blocks, selected = dx.detox_step_robust_blocks(dev_matrix(G, ld), 3, B, a0, f, m, vote_perm=vote_perm)
+            assert host(winner).tolist() == ref_w.tolist()
+            sel = host(selected)
+            for b, rs in enumerate(ref_sels):
+                lo = (b * 15) // B
+                assert sel[lo: lo + len(rs)].tolist() == rs.tolist()
+            if B > 1:
+                assert rel_l2(host(blocks), ref_blocks) <= TOL
+            assert rel_l2(host(out), ref_out) <= TOL
