@@ -172,6 +172,7 @@ def main():
         if groups >= 5:
             bm = StepBuffers(n, d, r, 5, G.device, materialise=False)
             timed("DETOX coord-median, B=5 (one pass)", lambda: dx.detox_step(G, r, q, 5, "coord_median", buffers=bm), n + 1)
+            timed("DETOX trimmed mean (alpha=1/4), B=5 (one pass)", lambda: dx.detox_step(G, r, q, 5, "trimmed_mean", buffers=bm), n + 1)
             timed("DETOX geometric median, B=5, 50 iterations", lambda: dx.detox_step(G, r, q, 5, "geomedian", buffers=bm), n + groups + 1)
         if groups >= 7:
             bb = StepBuffers(n, d, r, groups, G.device, materialise=False)
@@ -185,6 +186,8 @@ def main():
             timed(f"DETOX A0=Bulyan(f=2) on all {groups} votes",
                   lambda: dx.detox_step_robust_blocks(G, r, 1, "bulyan", 2, out=out_o, ws=ws_h), n + groups + (groups - 4) + 1)
         timed(f"vanilla coord-median over {n} rows", lambda: dx.robust_coord_median(G, out=out_o), n + 1)
+        timed(f"vanilla trimmed mean over {n} rows, {n // 4} off each end",
+              lambda: dx.robust_trimmed_mean(G, n // 4, out=out_o), n + 1)
         fb = min(q, (n - 3) // 4)
         ws_b = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
         timed(f"vanilla Bulyan over {n} rows, f={fb}", lambda: dx.robust_bulyan(G, fb, out=out_o, ws=ws_b), n + (n - 2 * fb) + 1)

@@ -57,7 +57,8 @@ typedef enum {
     DETOX_AGG_MULTIKRUM = 0,
     DETOX_AGG_BULYAN = 1,
     DETOX_AGG_COORD_MEDIAN = 2,
-    DETOX_AGG_GEOMEDIAN = 3
+    DETOX_AGG_GEOMEDIAN = 3,
+    DETOX_AGG_TRIMMED_MEAN = 4
 } detox_agg;
 
 /* Operation selector of detox_workspace_bytes. */
@@ -167,6 +168,13 @@ int robust_bulyan(const float *X, int64_t count, int64_t d, int64_t ld, int f, f
 int robust_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, float *out,
                         void *stream);
 
+/* Coordinate-wise trimmed mean (Section 4, the third aggregator analysed, with alpha = 1/4): per
+ * coordinate the g smallest and the g largest of the `count` values (total order as for the
+ * median) are dropped and the rest averaged: fp32( ascending fp64 sum / (count-2g) ).
+ * g = floor(alpha*count); 2g < count or DETOX_EPRECOND.  1 <= count <= DETOX_MAX_COUNT.     */
+int robust_trimmed_mean(const float *X, int64_t count, int64_t d, int64_t ld, int g, float *out,
+                        void *stream);
+
 /* Geometric median argmin_x sum_j ||x - x_j|| (appendix, proof of the
  * robustness theorem) by Weiszfeld's iteration started at the mean:
  * x <- sum_j w_j x_j / sum_j w_j, w_j = 1/max(||x - x_j||, eps), exactly
@@ -187,7 +195,8 @@ int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
  *   q          number of Byzantine nodes; used only when f < 0 to derive
  *              f = min(q / ((r+1)/2), largest f the aggregator admits for B rows)
  *   f, m       aggregator parameters; f < 0 and m < 0 mean "derive"
- *              (m = B - f)
+ *              (m = B - f).  DETOX_AGG_TRIMMED_MEAN: f = values dropped at each end
+ *              (f < 0: floor(B/4), i.e. alpha = 1/4)
  *   iters, eps Weiszfeld parameters (DETOX_AGG_GEOMEDIAN only)
  *   winner     dev, n/r int32, out
  *   Zhat       dev, B x d (ldo), out: the block means; or NULL (ldo ignored)

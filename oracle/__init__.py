@@ -116,6 +116,15 @@ def coord_median(X):
     return out
 
 
+def trimmed_mean(X, g):
+    """Coordinate-wise trimmed mean dropping the g smallest and g largest values."""
+    X, count, d, ld = _rows(X)
+    out = np.empty(d, dtype=np.float32)
+    _check(lib().oracle_trimmed_mean(_p(X), _i64(count), _i64(d), _i64(ld), _i64(g), _p(out)),
+           "trimmed_mean")
+    return out
+
+
 def pairwise_sqdist(X):
     X, count, d, ld = _rows(X)
     D = np.empty((count, count), dtype=np.float64)
@@ -205,6 +214,8 @@ def detox_step(G, r, B, aggregator, f=0, m=1, iters=50, eps=1e-8, group_rows=Non
         out = coord_median(Zhat)
     elif aggregator == "geomedian":
         out = geomedian(Zhat, iters, eps)
+    elif aggregator == "trimmed_mean":
+        out = trimmed_mean(Zhat, f if f >= 0 else B // 4)
     else:
         raise ValueError(aggregator)
     return out, winner, Zhat

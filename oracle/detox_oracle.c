@@ -255,6 +255,37 @@ int oracle_pairwise_sqdist(const float *X, int64_t count, int64_t d, int64_t ld,
     return ORACLE_OK;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Coordinate-wise trimmed mean (Section 4, the third aggregator analysed,   */
+/* alpha = 1/4): per coordinate, drop the g smallest and the g largest of    */
+/* the `count` values (g = floor(alpha*count)) and average the rest; the sum */
+/* runs in ascending order in fp64.                                          */
+/* ------------------------------------------------------------------------ */
+int oracle_trimmed_mean(const float *X, int64_t count, int64_t d, int64_t ld, int64_t g, float *out)
+{
+    if (!X || !out || count <= 0 || d <= 0 || ld < d || g < 0 || 2 * g >= count) return ORACLE_EINVAL;
+    int failed = 0;
+#pragma omp parallel
+    {
+        uint32_t *k = (uint32_t *)malloc((size_t)count * sizeof(uint32_t));
+        if (!k) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(static)
+        for (int64_t c = 0; c < d; ++c) {
+            if (!k) continue;
+            for (int64_t i = 0; i < count; ++i) k[i] = order_key(X[i * ld + c]);
+            sort_keys(k, count);
+            double s = 0.0;
+            for (int64_t i = g; i < count - g; ++i) s += (double)key_value(k[i]);
+            out[c] = (float)(s / (double)(count - 2 * g));
+        }
+        free(k);
+    }
+    return failed ? ORACLE_ENOMEM : ORACLE_OK;
+}
+
 /* Ascending order on doubles with NaN placed last. */
 static inline int dbl_before(double x, double y)
 {

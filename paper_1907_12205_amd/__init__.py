@@ -8,4 +8,4 @@ library's exports can be checked), calling anything needs one.
 from .binding import (  # noqa: F401
     AGG, DetoxError, OP, detox_block_mean, detox_filter_block_mean, detox_majority_filter,
     detox_step, detox_step_robust_blocks, lib, library_path, robust_bulyan, robust_coord_median, robust_geomedian,
-    robust_multikrum, robust_pairwise_sqdist, strerror, trace, workspace_bytes)
+    robust_multikrum, robust_pairwise_sqdist, robust_trimmed_mean, strerror, trace, workspace_bytes)

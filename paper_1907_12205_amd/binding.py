@@ -11,12 +11,12 @@ _LIB_PATH = os.path.join(_HERE, "libdetox.so")
 
 OP = dict(filter=0, block_mean=1, pairwise_sqdist=2, multikrum=3, bulyan=4, coord_median=5,
           geomedian=6, step=7)
-AGG = dict(multikrum=0, bulyan=1, coord_median=2, geomedian=3)
+AGG = dict(multikrum=0, bulyan=1, coord_median=2, geomedian=3, trimmed_mean=4)
 
 EXPORTS = ["detox_strerror", "detox_last_hip_error", "detox_workspace_bytes",
            "detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
            "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan", "robust_coord_median",
-           "robust_geomedian", "detox_step", "detox_step_robust_blocks", "detox_trace_enable",
+           "robust_geomedian", "robust_trimmed_mean", "detox_step", "detox_step_robust_blocks", "detox_trace_enable",
            "detox_trace_read"]
 
 
@@ -58,6 +58,8 @@ def lib() -> ctypes.CDLL:
         L.robust_multikrum.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.robust_bulyan.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
         L.robust_coord_median.argtypes = [vp, i64, i64, i64, vp, vp]
+        L.robust_trimmed_mean.argtypes = [vp, i64, i64, i64, i32, vp, vp]
+        L.robust_trimmed_mean.restype = i32
         L.robust_geomedian.argtypes = [vp, i64, i64, i64, i32, dbl, vp, vp, sz, vp]
         L.detox_step.argtypes = [vp, i64, i64, i64, i32, i32, vp, i64, vp, i32, i32, i32, i32, dbl,
                                  vp, vp, i64, vp, vp, vp, sz, vp]
@@ -69,7 +71,7 @@ def lib() -> ctypes.CDLL:
         L.detox_trace_read.argtypes = [ctypes.POINTER(_TraceRecord), i32]
         for name in ("detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
                      "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan",
-                     "robust_coord_median", "robust_geomedian", "detox_step", "detox_trace_read"):
+                     "robust_coord_median", "robust_geomedian", "robust_trimmed_mean", "detox_step", "detox_trace_read"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -212,6 +214,15 @@ def robust_coord_median(X, out=None):
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=X.device)
     _check(lib().robust_coord_median(p, count, d, ld, _ptr(out), _stream()), "robust_coord_median")
+    return out
+
+
+def robust_trimmed_mean(X, g: int, out=None):
+    torch = _torch()
+    p, count, d, ld = _matrix(X)
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=X.device)
+    _check(lib().robust_trimmed_mean(p, count, d, ld, g, _ptr(out), _stream()), "robust_trimmed_mean")
     return out
 
 

@@ -23,6 +23,7 @@ def sources():
 
 
 SORTNET_PARTS = 8      # must equal kSortnetParts in csrc/sortnet.hip
+MAX_R = 11             # must equal kMaxR in csrc/detox_internal.h
 
 
 def units():
@@ -33,8 +34,11 @@ def units():
         if src == "sortnet.hip":
             for k in range(SORTNET_PARTS):
                 out.append((src, f"sortnet_part{k}.o", [f"-DDETOX_SORTNET_PART={k}"]))
+        if src == "filter.hip":
+            for r in range(1, MAX_R + 1):
+                out.append((src, f"filter_r{r}.o", [f"-DDETOX_FILTER_R={r}"]))
     # longest first
-    out.sort(key=lambda u: 0 if "part" in u[1] else 1)
+    out.sort(key=lambda u: 0 if ("part" in u[1] or "filter_r" in u[1]) else 1)
     return out
 
 

@@ -236,7 +236,7 @@ int detox_majority_filter(const float *G, int64_t n, int64_t d, int64_t ld, int 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0};
     hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, nullptr, s);
     if (e == hipSuccess && Z)
         e = launch_block_mean(G, d, ld, winner, groups, groups, nullptr, Z, ldz, true, false, s);
@@ -267,7 +267,7 @@ int detox_filter_block_mean(const float *G, int64_t n, int64_t d, int64_t ld, in
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0};
     hipError_t e = launch_filter(p, FilterWant::kMeans, nullptr, nullptr, s);
     if (e == hipSuccess)
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
@@ -317,6 +317,15 @@ int robust_coord_median(const float *X, int64_t count, int64_t d, int64_t ld, fl
                                          static_cast<hipStream_t>(stream)));
 }
 
+int robust_trimmed_mean(const float *X, int64_t count, int64_t d, int64_t ld, int g, float *out,
+                        void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount || g < 0) return DETOX_EINVAL;
+    if (2 * (int64_t)g >= count) return DETOX_EPRECOND;
+    return status_of(launch_trimmed_mean(direct_rows(X, count, d, ld), g, out, nullptr,
+                                         static_cast<hipStream_t>(stream)));
+}
+
 int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
                      float *out, void *ws, size_t ws_bytes, void *stream)
 {
@@ -339,7 +348,11 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
         return DETOX_EINVAL;
     // without Zhat the aggregator reads votes (B = n/r) or re-forms the means of few vote groups
     if (!Zhat && B != groups && (B > 8 || groups > kFusedMaxVotes)) return DETOX_EINVAL;
-    if (agg < DETOX_AGG_MULTIKRUM || agg > DETOX_AGG_GEOMEDIAN) return DETOX_EINVAL;
+    if (agg < DETOX_AGG_MULTIKRUM || agg > DETOX_AGG_TRIMMED_MEAN) return DETOX_EINVAL;
+    if (agg == DETOX_AGG_TRIMMED_MEAN) {
+        if (f < 0) f = (int)(B / 4);   // alpha = 1/4 (Theorem 3, part 3)
+        if (2 * (int64_t)f >= B) return DETOX_EPRECOND;
+    }
     if (agg == DETOX_AGG_MULTIKRUM || agg == DETOX_AGG_BULYAN) {
         if (!selected) return DETOX_EINVAL;
         if (f < 0) {
@@ -364,11 +377,12 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, out};
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, out, agg == DETOX_AGG_TRIMMED_MEAN ? f : 0};
     // One pass over G.  With Zhat the block means are also written out; without it they exist
     // only in registers during this pass and are re-formed from the winners where a later
     // kernel needs them (that is the faster way on this chip).
-    FilterWant want = agg == DETOX_AGG_COORD_MEDIAN ? FilterWant::kMedian : FilterWant::kGram;
+    FilterWant want = agg == DETOX_AGG_COORD_MEDIAN ? FilterWant::kMedian
+                      : (agg == DETOX_AGG_TRIMMED_MEAN ? FilterWant::kTrimmed : FilterWant::kGram);
     if (Zhat == nullptr && (B > 8 || groups > kFusedMaxVotes)) want = FilterWant::kVotes;   // B = n/r
     FilterDone done;
     void *aws = static_cast<char *>(ws) + fbytes;
@@ -409,6 +423,8 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     case DETOX_AGG_COORD_MEDIAN:
         // already written by the filter pass unless some group had no majority
         return status_of(launch_coord_median(rs, out, done.median_written ? fw.redo : nullptr, s));
+    case DETOX_AGG_TRIMMED_MEAN:
+        return status_of(launch_trimmed_mean(rs, f, out, done.median_written ? fw.redo : nullptr, s));
     default: return geomedian_impl(rs, iters, eps, out, aws, fg, s);
     }
 }
@@ -439,7 +455,7 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr};
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0};
     hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, nullptr, s);
     if (e != hipSuccess) return status_of(e);
     // row table of the votes in vote order: winner itself, or winner o vote_perm

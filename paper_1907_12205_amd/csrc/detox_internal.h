@@ -76,7 +76,8 @@ struct FilterParams {
     double *gram_partials;              // dev, kFusedMaxGrid x B(B+1)/2 (persistent kernel, B <= 8)
     int *redo;                          // dev, 1 word: set when some group has no majority
     int32_t *winner;                    // dev, n_votes
-    float *out;                         // dev, d: the coordinate-wise median (median mode only)
+    float *out;                         // dev, d: coordinate-wise median / trimmed mean (those modes)
+    int trim_g;                         // trimmed-mean mode: values dropped at each end
 };
 struct FilterWs {
     int *redo;
@@ -90,13 +91,14 @@ enum class FilterWant {
     kVotes,    // nothing else
     kMeans,    // block means in Zhat (must be non-null)
     kGram,     // block means (in Zhat if non-null) and, when B <= 8, the Gram matrix of the means
-    kMedian    // block means (in Zhat if non-null) and, when B <= 8, their coordinate-wise median
+    kMedian,   // block means (in Zhat if non-null) and, when B <= 8, their coordinate-wise median
+    kTrimmed   // the same with the coordinate-wise trimmed mean (FilterParams::trim_g per end)
 };
 struct FilterDone {
     int gram_blocks = 0;          // > 0: Gram partial slots written (kGram honoured)
     bool gram_reduced = false;    // the finalize kernel already produced Gm (and, if asked, the
                                   //   Multi-Krum selection) unless *redo
-    bool median_written = false;  // kMedian honoured: `out` holds the median unless *redo
+    bool median_written = false;  // kMedian / kTrimmed honoured: `out` holds the result unless *redo
 };
 struct SmallSelect;               // small_select.cuh: what the finalize kernel should go on to do
 // kGram / kMedian with B > 8 (or more than kFusedMaxVotes groups) degrade to kMeans; then Zhat
@@ -150,6 +152,8 @@ hipError_t launch_weighted_sum(const RowSet &rs, const double *weights, float *o
 // ---- sortnet.hip -----------------------------------------------------------
 // Coordinate-wise median of all logical rows.  run_if (dev, may be null): skip unless *run_if.
 hipError_t launch_coord_median(const RowSet &rs, float *out, const int *run_if, hipStream_t s);
+// Coordinate-wise trimmed mean of all logical rows: the g smallest and g largest values dropped.
+hipError_t launch_trimmed_mean(const RowSet &rs, int g, float *out, const int *run_if, hipStream_t s);
 // Per coordinate: median of the theta listed logical rows, mean of the beta values closest to it.
 //   scratch: dev, theta int32 (used when rs carries an index table).
 hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, int theta,

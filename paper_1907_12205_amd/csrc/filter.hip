@@ -118,17 +118,18 @@ __device__ inline int32_t winner_from_bits(unsigned long long bits, const int32_
 //   kMeans      : + block means written to Zhat (any B, read from the parameters; NB = 0).
 //   kGram       : + block means kept in registers (NB = B <= 8, compile time), their Gram matrix
 //                 accumulated in fp64 into per-workgroup partials; Zhat written only if non-null.
+//   kTrimmedMean: as kMedian with the coordinate-wise trimmed mean (trim_g values off each end).
 //   kMedian     : + block means kept in registers (NB = B <= 8), their coordinate-wise median
 //                 written to `out` (the whole DETOX-median step in one pass over G); Zhat
 //                 written only if non-null.
 // ---------------------------------------------------------------------------------------
-enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3 };
+enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3, kTrimmedMean = 4 };
 
 template <int R, int VEC, int NB, int MODE>
 __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
 {
     constexpr bool MEAN = MODE != kFilterOnly;
-    constexpr bool REGS = MODE == kGram || MODE == kMedian;   // means of all blocks in registers
+    constexpr bool REGS = MODE == kGram || MODE == kMedian || MODE == kTrimmedMean;   // means of all blocks in registers
     constexpr int NP = MODE == kGram ? NB * (NB + 1) / 2 : 1;
     static_assert(!REGS || NB > 0, "register modes need the block count at compile time");
     __shared__ unsigned long long sbits[kFusedMaxVotes];
@@ -191,6 +192,24 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
 #pragma unroll
                     for (int c = a; c < NB; ++c, ++pair) gacc[pair] = fma(zd[a], zd[c], gacc[pair]);
             }
+        }
+        if constexpr (MODE == kTrimmedMean) {
+            uint32_t k[NB][VEC];
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) k[a][i] = order_key(__float_as_uint(z[a][i]));
+            sort_keys<NB, VEC>(k);
+            float tm[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                double s = 0.0;
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+                    if (a >= p.trim_g && a < NB - p.trim_g) s += (double)key_value(k[a][i]);
+                tm[i] = (float)(s / (double)(NB - 2 * p.trim_g));
+            }
+            if (valid > 0) store_floats<VEC>(p.out + col, valid, tm);
         }
         if constexpr (MODE == kMedian) {
             uint32_t k[NB][VEC];
@@ -419,6 +438,8 @@ hipError_t launch_fused_rvn(const FilterParams &p, int mode, int *grid, int64_t 
     } else {
         if (mode == kMedian)
             return launch_fused_mode<R, VEC, NB, kMedian>(p, "filter_block_mean_median", grid, chunks, s);
+        if (mode == kTrimmedMean)
+            return launch_fused_mode<R, VEC, NB, kTrimmedMean>(p, "filter_block_mean_trimmed", grid, chunks, s);
         return launch_fused_mode<R, VEC, NB, kGram>(p, "filter_block_mean_gram", grid, chunks, s);
     }
 }
@@ -472,6 +493,30 @@ hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int mode, int 
 
 }  // namespace
 
+// This file is compiled once per node-group size (-DDETOX_FILTER_R=r holds the kernels for that r
+// only) so that the instantiations build in parallel, and once without the macro for everything
+// that does not depend on r.
+#ifdef DETOX_FILTER_R
+
+#define DETOX_FR_FN2(r) filter_launch_r##r
+#define DETOX_FR_FN(r) DETOX_FR_FN2(r)
+hipError_t DETOX_FR_FN(DETOX_FILTER_R)(const FilterParams &p, bool mean, bool fused, int mode, int nb,
+                                       int *grid, int64_t chunks, int vec, hipStream_t s)
+{
+    return launch_r<DETOX_FILTER_R>(p, mean, fused, mode, nb, grid, chunks, vec, s);
+}
+
+}  // namespace detox
+
+#else
+
+#define DETOX_DECL_FR(r)                                                                           \
+    hipError_t filter_launch_r##r(const FilterParams &p, bool mean, bool fused, int mode, int nb,   \
+                                  int *grid, int64_t chunks, int vec, hipStream_t s);
+DETOX_DECL_FR(1) DETOX_DECL_FR(2) DETOX_DECL_FR(3) DETOX_DECL_FR(4) DETOX_DECL_FR(5) DETOX_DECL_FR(6)
+DETOX_DECL_FR(7) DETOX_DECL_FR(8) DETOX_DECL_FR(9) DETOX_DECL_FR(10) DETOX_DECL_FR(11)
+#undef DETOX_DECL_FR
+
 // Workspace of the filter kernels: [redo word | n_votes flag words | per-workgroup flag slots |
 // per-workgroup Gram partials], each piece rounded up to 256 bytes.  Monotone in n_votes.
 namespace {
@@ -512,7 +557,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         const int vo = row_vec_width(p.Zhat, p.ldo);
         vec = vo < vec ? vo : vec;
     }
-    if (want == FilterWant::kMedian) {
+    if (want == FilterWant::kMedian || want == FilterWant::kTrimmed) {
         const int vo = row_vec_width(p.out, 4);
         vec = vo < vec ? vo : vec;
     }
@@ -525,6 +570,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         mode = kMeans;
         if (fused && p.B <= 8 && want == FilterWant::kGram) mode = kGram, nb = (int)p.B;
         if (fused && p.B <= 8 && want == FilterWant::kMedian) mode = kMedian, nb = (int)p.B;
+        if (fused && p.B <= 8 && want == FilterWant::kTrimmed) mode = kTrimmedMean, nb = (int)p.B;
     }
     // without a register mode the means must go to memory
     if (mode == kMeans && p.Zhat == nullptr) return hipErrorInvalidValue;
@@ -543,17 +589,17 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         if (e != hipSuccess) return e;
     }
     switch (p.r) {
-    case 1: e = launch_r<1>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 2: e = launch_r<2>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 3: e = launch_r<3>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 4: e = launch_r<4>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 5: e = launch_r<5>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 6: e = launch_r<6>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 7: e = launch_r<7>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 8: e = launch_r<8>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 9: e = launch_r<9>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 10: e = launch_r<10>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 11: e = launch_r<11>(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 1: e = filter_launch_r1(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 2: e = filter_launch_r2(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 3: e = filter_launch_r3(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 4: e = filter_launch_r4(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 5: e = filter_launch_r5(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 6: e = filter_launch_r6(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 7: e = filter_launch_r7(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 8: e = filter_launch_r8(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 9: e = filter_launch_r9(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 10: e = filter_launch_r10(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 11: e = filter_launch_r11(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
@@ -573,7 +619,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         if (done) {
             done->gram_blocks = mode == kGram ? grid : 0;
             done->gram_reduced = mode == kGram && tail != nullptr;
-            done->median_written = mode == kMedian;
+            done->median_written = mode == kMedian || mode == kTrimmedMean;
         }
     } else {
         filter_finalize_kernel<<<(unsigned)((p.n_votes + 255) / 256), 256, 0, s>>>(
@@ -614,3 +660,5 @@ hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_
 }
 
 }  // namespace detox
+
+#endif  // DETOX_FILTER_R

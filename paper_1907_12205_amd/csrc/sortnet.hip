@@ -17,7 +17,11 @@ namespace {
 
 // The N values per coordinate come from rows phys[0..N-1] of rs.base (-1: zeros); with MEANS,
 // phys lists logical rows (block means formed on the fly).
-template <int N, int VEC, bool TRIM, bool MEANS>
+// MODE: kStatMedian, kStatBulyanTrim (beta = values kept around the median), kStatTrimmedMean
+// (beta = values dropped at each end).
+enum StatMode { kStatMedian = 0, kStatBulyanTrim = 1, kStatTrimmedMean = 2 };
+
+template <int N, int VEC, int MODE, bool MEANS>
 __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int32_t *phys, int beta,
                                                             float *out, const int *run_if)
 {
@@ -65,6 +69,7 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
     }
     sort_keys<N, VEC>(k);
     // shifted[i] = k[i + beta] (beta is uniform): log2(N) conditional shifts by powers of two
+    constexpr bool TRIM = MODE == kStatBulyanTrim;
     uint32_t shifted[TRIM ? N : 1][VEC];
     if constexpr (TRIM) {
 #pragma unroll
@@ -84,6 +89,15 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
     float o[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
+        if constexpr (MODE == kStatTrimmedMean) {
+            // drop the beta smallest and the beta largest, average the rest (ascending fp64 sum)
+            double s = 0.0;
+#pragma unroll
+            for (int c = 0; c < N; ++c)
+                if (c >= beta && c < N - beta) s += (double)key_value(k[c][v]);
+            o[v] = (float)(s / (double)(N - 2 * beta));
+            continue;
+        }
         const float med = median_of_sorted<N, VEC>(k, v);
         if constexpr (!TRIM) {
             o[v] = med;
@@ -112,23 +126,23 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
     store_floats<VEC>(out + col, valid, o);
 }
 
-template <int N, int VEC, bool TRIM>
+template <int N, int VEC, int MODE>
 hipError_t launch_nv(const RowSet &rs, const int32_t *rows, int beta, float *out, const int *run_if,
                      unsigned chunks, hipStream_t s)
 {
     if (rs.means()) {
         // block means formed on the fly: only offered for the few rows of a hierarchical step
         if constexpr (N <= 8)
-            order_stat_kernel<N, VEC, TRIM, true><<<chunks, kBlock, 0, s>>>(rs, rows, beta, out, run_if);
+            order_stat_kernel<N, VEC, MODE, true><<<chunks, kBlock, 0, s>>>(rs, rows, beta, out, run_if);
         else
             return hipErrorInvalidValue;
     } else {
-        order_stat_kernel<N, VEC, TRIM, false><<<chunks, kBlock, 0, s>>>(rs, rows, beta, out, run_if);
+        order_stat_kernel<N, VEC, MODE, false><<<chunks, kBlock, 0, s>>>(rs, rows, beta, out, run_if);
     }
     return hipGetLastError();
 }
 
-template <int N, bool TRIM>
+template <int N, int MODE>
 hipError_t launch_n(const RowSet &rs, const int32_t *rows, int beta, float *out, const int *run_if,
                     int vec, hipStream_t s)
 {
@@ -136,14 +150,14 @@ hipError_t launch_n(const RowSet &rs, const int32_t *rows, int beta, float *out,
     constexpr int kMaxVec = N <= 24 ? 4 : (N <= 56 ? 2 : 1);
     if (vec > kMaxVec) vec = kMaxVec;
     const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
-    TraceScope t(TRIM ? "bulyan_trim" : (run_if ? "coord_median_if_redo" : "coord_median"), s);
+    TraceScope t(MODE == kStatBulyanTrim ? "bulyan_trim" : (MODE == kStatTrimmedMean ? (run_if ? "trimmed_mean_if_redo" : "trimmed_mean") : (run_if ? "coord_median_if_redo" : "coord_median")), s);
     if constexpr (kMaxVec >= 4) {
-        if (vec == 4) return launch_nv<N, 4, TRIM>(rs, rows, beta, out, run_if, (unsigned)chunks, s);
+        if (vec == 4) return launch_nv<N, 4, MODE>(rs, rows, beta, out, run_if, (unsigned)chunks, s);
     }
     if constexpr (kMaxVec >= 2) {
-        if (vec == 2) return launch_nv<N, 2, TRIM>(rs, rows, beta, out, run_if, (unsigned)chunks, s);
+        if (vec == 2) return launch_nv<N, 2, MODE>(rs, rows, beta, out, run_if, (unsigned)chunks, s);
     }
-    return launch_nv<N, 1, TRIM>(rs, rows, beta, out, run_if, (unsigned)chunks, s);
+    return launch_nv<N, 1, MODE>(rs, rows, beta, out, run_if, (unsigned)chunks, s);
 }
 
 // The instantiations are spread over kSortnetParts translation units (this file compiled with
@@ -156,14 +170,14 @@ constexpr int kSortnetParts = 8;
 #ifdef DETOX_SORTNET_PART
 
 namespace {
-template <bool TRIM, int... Js>
+template <int MODE, int... Js>
 hipError_t dispatch_part(int n, const RowSet &rs, const int32_t *rows, int beta, float *out,
                          const int *run_if, int vec, hipStream_t s,
                          std::integer_sequence<int, Js...>)
 {
     hipError_t e = hipErrorInvalidValue;
     (void)((n == Js * kSortnetParts + DETOX_SORTNET_PART + 1
-                ? (e = launch_n<Js * kSortnetParts + DETOX_SORTNET_PART + 1, TRIM>(rs, rows, beta, out, run_if, vec, s), true)
+                ? (e = launch_n<Js * kSortnetParts + DETOX_SORTNET_PART + 1, MODE>(rs, rows, beta, out, run_if, vec, s), true)
                 : false) || ...);
     return e;
 }
@@ -171,23 +185,26 @@ hipError_t dispatch_part(int n, const RowSet &rs, const int32_t *rows, int beta,
 
 #define DETOX_PART_FN2(k) order_stat_part##k
 #define DETOX_PART_FN(k) DETOX_PART_FN2(k)
-hipError_t DETOX_PART_FN(DETOX_SORTNET_PART)(bool trim, int n, const RowSet &rs, const int32_t *rows,
+hipError_t DETOX_PART_FN(DETOX_SORTNET_PART)(int mode, int n, const RowSet &rs, const int32_t *rows,
                                              int beta, float *out, const int *run_if, int vec,
                                              hipStream_t s)
 {
     constexpr int per_part = kMaxCount / kSortnetParts;
     static_assert(kMaxCount % kSortnetParts == 0, "parts must tile the supported counts");
-    if (trim)
-        return dispatch_part<true>(n, rs, rows, beta, out, run_if, vec, s,
-                                   std::make_integer_sequence<int, per_part>{});
-    return dispatch_part<false>(n, rs, rows, beta, out, run_if, vec, s,
-                                std::make_integer_sequence<int, per_part>{});
+    if (mode == kStatBulyanTrim)
+        return dispatch_part<kStatBulyanTrim>(n, rs, rows, beta, out, run_if, vec, s,
+                                              std::make_integer_sequence<int, per_part>{});
+    if (mode == kStatTrimmedMean)
+        return dispatch_part<kStatTrimmedMean>(n, rs, rows, beta, out, run_if, vec, s,
+                                               std::make_integer_sequence<int, per_part>{});
+    return dispatch_part<kStatMedian>(n, rs, rows, beta, out, run_if, vec, s,
+                                      std::make_integer_sequence<int, per_part>{});
 }
 
 #else  // dispatcher
 
 #define DETOX_DECL_PART(k)                                                                        \
-    hipError_t order_stat_part##k(bool trim, int n, const RowSet &rs, const int32_t *rows, int beta, \
+    hipError_t order_stat_part##k(int mode, int n, const RowSet &rs, const int32_t *rows, int beta, \
                                   float *out, const int *run_if, int vec, hipStream_t s);
 DETOX_DECL_PART(0) DETOX_DECL_PART(1) DETOX_DECL_PART(2) DETOX_DECL_PART(3)
 DETOX_DECL_PART(4) DETOX_DECL_PART(5) DETOX_DECL_PART(6) DETOX_DECL_PART(7)
@@ -222,7 +239,7 @@ const int32_t *identity_table()
 
 // rows: logical rows to use (dev, n entries; null = 0..n-1).  scratch: dev, n int32, needed only
 // when both a row list and an index table are present (their composition is written there).
-hipError_t order_stat(bool trim, int n, RowSet rs, const int32_t *rows, int32_t *scratch, int beta,
+hipError_t order_stat(int mode, int n, RowSet rs, const int32_t *rows, int32_t *scratch, int beta,
                       float *out, const int *run_if, hipStream_t s)
 {
     if (n < 1 || n > kMaxCount) return hipErrorInvalidValue;
@@ -245,27 +262,32 @@ hipError_t order_stat(bool trim, int n, RowSet rs, const int32_t *rows, int32_t 
     const int vo = row_vec_width(out, 4);
     vec = vo < vec ? vo : vec;
     switch ((n - 1) % kSortnetParts) {
-    case 0: return order_stat_part0(trim, n, rs, phys, beta, out, run_if, vec, s);
-    case 1: return order_stat_part1(trim, n, rs, phys, beta, out, run_if, vec, s);
-    case 2: return order_stat_part2(trim, n, rs, phys, beta, out, run_if, vec, s);
-    case 3: return order_stat_part3(trim, n, rs, phys, beta, out, run_if, vec, s);
-    case 4: return order_stat_part4(trim, n, rs, phys, beta, out, run_if, vec, s);
-    case 5: return order_stat_part5(trim, n, rs, phys, beta, out, run_if, vec, s);
-    case 6: return order_stat_part6(trim, n, rs, phys, beta, out, run_if, vec, s);
-    default: return order_stat_part7(trim, n, rs, phys, beta, out, run_if, vec, s);
+    case 0: return order_stat_part0(mode, n, rs, phys, beta, out, run_if, vec, s);
+    case 1: return order_stat_part1(mode, n, rs, phys, beta, out, run_if, vec, s);
+    case 2: return order_stat_part2(mode, n, rs, phys, beta, out, run_if, vec, s);
+    case 3: return order_stat_part3(mode, n, rs, phys, beta, out, run_if, vec, s);
+    case 4: return order_stat_part4(mode, n, rs, phys, beta, out, run_if, vec, s);
+    case 5: return order_stat_part5(mode, n, rs, phys, beta, out, run_if, vec, s);
+    case 6: return order_stat_part6(mode, n, rs, phys, beta, out, run_if, vec, s);
+    default: return order_stat_part7(mode, n, rs, phys, beta, out, run_if, vec, s);
     }
 }
 }  // namespace
 
 hipError_t launch_coord_median(const RowSet &rs, float *out, const int *run_if, hipStream_t s)
 {
-    return order_stat(false, rs.count, rs, nullptr, nullptr, 0, out, run_if, s);
+    return order_stat(kStatMedian, rs.count, rs, nullptr, nullptr, 0, out, run_if, s);
 }
 
 hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, int theta,
                               int beta, float *out, hipStream_t s)
 {
-    return order_stat(true, theta, rs, rows, scratch, beta, out, nullptr, s);
+    return order_stat(kStatBulyanTrim, theta, rs, rows, scratch, beta, out, nullptr, s);
+}
+
+hipError_t launch_trimmed_mean(const RowSet &rs, int g, float *out, const int *run_if, hipStream_t s)
+{
+    return order_stat(kStatTrimmedMean, rs.count, rs, nullptr, nullptr, g, out, run_if, s);
 }
 
 #endif

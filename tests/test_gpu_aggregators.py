@@ -153,3 +153,18 @@ def test_aggregators_accept_unaligned_rows(dx):
         out, sel = dx.robust_bulyan(Xd, 1)
         assert host(sel).tolist() == ref_bsel.tolist() and rel_l2(host(out), ref_b) <= TOL
         assert rel_l2(host(dx.robust_geomedian(Xd)), ref_g) <= TOL
+
+
+@pytest.mark.parametrize("count,g", [(1, 0), (3, 1), (5, 1), (5, 0), (8, 2), (8, 3), (15, 3), (16, 4), (25, 6),
+                                     (45, 11), (57, 14), (105, 26), (128, 32), (128, 63)])
+def test_trimmed_mean(dx, count, g):
+    d = 3001 if count > 32 else 10007
+    X = workloads.distinct_rows(count + 77, count, d)
+    X[:, 5] = 0.0; X[: count // 2, 5] = -0.0
+    X[:, 17] = X[0, 17]
+    ref = oracle.trimmed_mean(X, g)
+    for ld, off in ((None, 0), ((d + 63) // 64 * 64, 0), (None, 1)):
+        got = host(dx.robust_trimmed_mean(dev_matrix(X, ld, off), g))
+        assert rel_l2(got, ref) <= TOL
+        if 2 * g == count - 1:          # a single value survives: the median, bit for bit
+            assert got.tobytes() == oracle.coord_median(X).tobytes()

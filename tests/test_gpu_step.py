@@ -35,6 +35,8 @@ def _run(dx, w, spec, ld=None, materialise=True, G=None, group_rows=None, vote_p
     got = host(b.out)
     if spec["aggregator"] == "coord_median":
         assert got.tobytes() == ref_out.tobytes()
+    elif spec["aggregator"] == "trimmed_mean":
+        assert rel_l2(got, ref_out) <= TOL
     else:
         assert rel_l2(got, ref_out) <= TOL
     if spec["aggregator"] == "multikrum":
@@ -58,7 +60,9 @@ AGGS = [dict(B=5, aggregator="multikrum", f=1, m=3), dict(B=15, aggregator="mult
         dict(B=5, aggregator="coord_median"), dict(B=3, aggregator="coord_median"),
         dict(B=15, aggregator="coord_median"), dict(B=4, aggregator="coord_median"),
         dict(B=7, aggregator="bulyan", f=1), dict(B=15, aggregator="bulyan", f=2),
-        dict(B=5, aggregator="geomedian"), dict(B=15, aggregator="geomedian", iters=20)]
+        dict(B=5, aggregator="geomedian"), dict(B=15, aggregator="geomedian", iters=20),
+        dict(B=5, aggregator="trimmed_mean", f=1), dict(B=15, aggregator="trimmed_mean", f=3),
+        dict(B=7, aggregator="trimmed_mean", f=-1)]
 
 
 @pytest.mark.parametrize("spec", AGGS, ids=lambda s: f"{s['aggregator']}-B{s['B']}")
