@@ -137,3 +137,35 @@ def test_repeated_calls_are_bit_identical(dx):
     a = dx.detox_filter_block_mean(Gd, 3, 5)
     b = dx.detox_filter_block_mean(Gd, 3, 5)
     assert host(a[1]).tobytes() == host(b[1]).tobytes() and host(a[0]).tolist() == host(b[0]).tolist()
+
+
+def test_many_groups_take_the_general_kernel(dx):
+    """More than 1024 node groups: the per-group flag words with integer atomics (grid.y = vote
+    group) instead of the persistent kernel; also exercised with block means and the whole step."""
+    rng = np.random.default_rng(77)
+    groups, r, d = 1500, 3, 301
+    base = rng.standard_normal((groups, d)).astype(np.float32)
+    G = np.repeat(base, r, axis=0)
+    for g in rng.choice(groups, size=200, replace=False):
+        kind = g % 3
+        if kind == 0:
+            G[g * r + int(rng.integers(r))] = rng.standard_normal(d).astype(np.float32)     # one Byzantine member
+        elif kind == 1:
+            bad = rng.standard_normal(d).astype(np.float32)                                 # two colluding
+            G[g * r] = bad; G[g * r + 2] = bad
+        else:
+            G[g * r + 1, d // 2:] += 1; G[g * r + 2, : d // 2] -= 1                        # no majority
+    ref_w = _check_filter(dx, G, r)
+    assert (ref_w < 0).sum() > 10
+    Gd = dev_matrix(G)
+    for B in (10, 1500, 7):
+        ref = oracle.block_mean(G, ref_w, B)
+        w2, fused = dx.detox_filter_block_mean(Gd, r, B)
+        assert host(w2).tolist() == ref_w.tolist()
+        assert host(fused).tobytes() == ref.tobytes()
+    ref_out, _, _ = oracle.detox_step(G, r, 10, "coord_median")
+    b = dx.detox_step(Gd, r, 100, 10, "coord_median")
+    assert host(b.out).tobytes() == ref_out.tobytes()
+    ref_out, _, _ = oracle.detox_step(G, r, 20, "multikrum", f=2, m=10)
+    b = dx.detox_step(Gd, r, 100, 20, "multikrum", f=2, m=10)
+    assert np.linalg.norm(host(b.out) - ref_out) <= 1e-5 * np.linalg.norm(ref_out)
