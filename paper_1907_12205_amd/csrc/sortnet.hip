@@ -70,56 +70,75 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
     sort_keys<N, VEC>(k);
     // shifted[i] = k[i + beta] (beta is uniform): log2(N) conditional shifts by powers of two
     constexpr bool TRIM = MODE == kStatBulyanTrim;
-    uint32_t shifted[TRIM ? N : 1][VEC];
-    if constexpr (TRIM) {
-#pragma unroll
-        for (int i = 0; i < N; ++i)
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) shifted[i][v] = k[i][v];
-#pragma unroll
-        for (int bit = 1; bit < N; bit *= 2)
-            if (beta & bit) {
-#pragma unroll
-                for (int i = 0; i < N; ++i)
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v)
-                        shifted[i][v] = i + bit < N ? shifted[i + bit][v] : 0u;
-            }
-    }
     float o[VEC];
+    if constexpr (MODE == kStatTrimmedMean) {
+        // drop the beta smallest and the beta largest, average the rest (ascending fp64 sum)
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-        if constexpr (MODE == kStatTrimmedMean) {
-            // drop the beta smallest and the beta largest, average the rest (ascending fp64 sum)
+        for (int v = 0; v < VEC; ++v) {
             double s = 0.0;
 #pragma unroll
             for (int c = 0; c < N; ++c)
                 if (c >= beta && c < N - beta) s += (double)key_value(k[c][v]);
             o[v] = (float)(s / (double)(N - 2 * beta));
-            continue;
         }
-        const float med = median_of_sorted<N, VEC>(k, v);
-        if constexpr (!TRIM) {
-            o[v] = med;
-        } else {
-            // The beta values closest to the median form a window [lo, lo+beta) of the sorted
-            // values that contains the (lower) middle index h.  Starting from the leftmost such
-            // window, sliding right pays as long as the value entering on the right is strictly
-            // closer to the median than the one leaving on the left (equal closeness keeps the
-            // lower value); both distances move monotonically, so the first refusal is final.
-            constexpr int h = (N - 1) / 2;
-            const int lo_min = h - beta + 1 > 0 ? h - beta + 1 : 0;
-            int lo = lo_min;
+    } else if constexpr (!TRIM) {
 #pragma unroll
-            for (int c = 0; c <= h; ++c) {
-                const float dl = fabsf(key_value(k[c][v]) - med);
-                const float dr = fabsf(key_value(shifted[c][v]) - med);
-                if (c >= lo_min && c + beta < N && dr < dl && lo == c) lo = c + 1;
+        for (int v = 0; v < VEC; ++v) o[v] = median_of_sorted<N, VEC>(k, v);
+    } else {
+        // Bulyan's second stage.  The beta values closest to the median form a window
+        // [lo, lo+beta) of the sorted values that contains the (lower) middle index h.  Starting
+        // from the leftmost such window, sliding right pays as long as the value entering on the
+        // right (index c+beta) is strictly closer to the median than the one leaving on the left
+        // (index c; equal closeness keeps the lower value); both distances move monotonically,
+        // so the first refusal is final.  c is a compile-time index, c+beta is not (beta is a
+        // uniform run-time value): the upper half of the sorted values is parked in LDS, each
+        // thread in its own slots, and read back with that run-time index.
+        constexpr int h = (N - 1) / 2;
+        constexpr int kTop = N - h - 1;                       // values above the middle index
+        __shared__ float top[(kTop > 0 ? kTop : 1) * kBlock * VEC];
+        float val[N][VEC];
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) val[i][v] = key_value(k[i][v]);
+#pragma unroll
+        for (int i = h + 1; i < N; ++i)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                top[((i - h - 1) * kBlock + threadIdx.x) * VEC + v] = val[i][v];
+        const int lo_min = h - beta + 1 > 0 ? h - beta + 1 : 0;
+        const int dropped = N - beta;                         // values outside the window
+        float med[VEC];
+        int lo[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            med[v] = N % 2 == 1 ? val[N / 2][v] : (val[N / 2 - 1][v] + val[N / 2][v]) * 0.5f;
+            lo[v] = lo_min;
+        }
+#pragma unroll
+        for (int c = 0; c <= h; ++c) {
+            if (c >= lo_min && c + beta < N) {                // uniform: a real candidate
+                const int e = c + beta - (h + 1);             // in [0, kTop)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const float enter = top[(e * kBlock + threadIdx.x) * VEC + v];
+                    const float dl = fabsf(val[c][v] - med[v]);
+                    const float dr = fabsf(enter - med[v]);
+                    if (dr < dl && lo[v] == c) lo[v] = c + 1;
+                }
             }
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
             double s = 0.0;
 #pragma unroll
-            for (int c = 0; c < N; ++c)
-                if (c >= lo && c < lo + beta) s += (double)key_value(k[c][v]);
+            for (int c = 0; c < N; ++c) {
+                if (c >= dropped && c < beta) {               // uniform: inside every window
+                    s += (double)val[c][v];
+                } else if (c >= lo[v] && c < lo[v] + beta) {
+                    s += (double)val[c][v];
+                }
+            }
             o[v] = (float)(s / (double)beta);
         }
     }
