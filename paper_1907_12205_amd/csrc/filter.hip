@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
 // Gram partials of those blocks must be recomputed.
 // When every group has a majority and the pass left Gram partials, the same workgroup goes on to
 // add them up and (Multi-Krum) to score and select.
-__global__ __launch_bounds__(kPostThreads) void finalize_partials_kernel(
+[[maybe_unused]] __global__ __launch_bounds__(kPostThreads) void finalize_partials_kernel(
     const unsigned long long *partials, int blocks, const int32_t *group_rows, int r, int n_votes,
     int32_t *winner, int *redo, SmallSelect q)
 {
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(kPostThreads) void finalize_partials_kernel(
 // ---------------------------------------------------------------------------------------
 // General kernel: one workgroup = 256*VEC columns of one vote group b (grid.y = B).
 // ---------------------------------------------------------------------------------------
-__global__ void fill_u64_kernel(unsigned long long *p, int64_t count)
+[[maybe_unused]] __global__ void fill_u64_kernel(unsigned long long *p, int64_t count)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0ull;
@@ -332,7 +332,7 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(FilterParams p)
     }
 }
 
-__global__ void filter_finalize_kernel(const unsigned long long *flags, const int32_t *group_rows,
+[[maybe_unused]] __global__ void filter_finalize_kernel(const unsigned long long *flags, const int32_t *group_rows,
                                        int r, int64_t groups, int32_t *winner, int *redo)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
