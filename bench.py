@@ -191,6 +191,13 @@ def main():
         fb = min(q, (n - 3) // 4)
         ws_b = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
         timed(f"vanilla Bulyan over {n} rows, f={fb}", lambda: dx.robust_bulyan(G, fb, out=out_o, ws=ws_b), n + (n - 2 * fb) + 1)
+        if groups >= 5:
+            # signSGD pairing: one sign bit per coordinate, two levels of coordinate-wise majority vote
+            S = torch.from_numpy(workloads.pack_signs(w.matrix()).view(np.int32)).to(G.device)
+            ws_s = torch.empty(dx.workspace_bytes("filter", groups, S.shape[1]), dtype=torch.uint8, device=G.device)
+            out_s = torch.empty((2, S.shape[1]), dtype=torch.int32, device=G.device)
+            timed("DETOX + signSGD majority vote, bit-packed signs, B=5",
+                  lambda: dx.detox_sign_majority(S, d, r, 5, ws=ws_s, out=out_s), (n + groups + 2) / 32)
         for o in others:
             log(f"[bench] {o['path']}: {o['ms_per_step']:.4f} ms/step, {o['hbm_frac_algorithmic'] * 100:.1f}% of HBM peak (algorithmic bytes)")
 

@@ -232,6 +232,25 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
                              int64_t ldb, int32_t *selected, float *out, void *ws,
                              size_t ws_bytes, void *stream);
 
+/* DETOX paired with signSGD (Section 5.2, setup 4; the signSGD comparison of Section 5.3): every
+ * node sends only the signs of its gradient and both A0 and A1 are the coordinate-wise majority
+ * vote.
+ *   S          dev, n x words uint32 (ldw words between rows), words = ceil(d/32): bit (c % 32)
+ *              of word (c / 32) set <=> sign +1, clear <=> sign -1; the unused bits of the last
+ *              word must be zero (they take part in the bytewise comparison of the filter)
+ *   filter     bytewise majority inside each node group, exactly as detox_majority_filter
+ *   vote group a_b[c] = sign( sum over its votes with a majority of +-1 ), groups cut as in
+ *              detox_block_mean; a vote without majority contributes nothing
+ *   result     sign( sum_b a_b[c] ) in {-1, 0, +1}, returned as two bit masks of `words` words:
+ *              out_pos has bit c set where the result is +1, out_neg where it is -1
+ *   limits     r <= DETOX_MAX_R, at most 255 votes per vote group, B <= 255
+ *   winner     dev, n/r int32, out
+ *   ws         DETOX_OP_FILTER bytes                                                      */
+int detox_sign_majority(const uint32_t *S, int64_t n, int64_t d, int64_t ldw, int r,
+                        const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
+                        int32_t *winner, uint32_t *out_pos, uint32_t *out_neg, void *ws,
+                        size_t ws_bytes, void *stream);
+
 /* Per-kernel timing.  While enabled, every kernel the library launches is
  * bracketed by hipEvents on the caller's stream (this adds a few microseconds
  * per launch; leave it off when timing whole steps).  After synchronising the

@@ -221,6 +221,22 @@ def detox_step(G, r, B, aggregator, f=0, m=1, iters=50, eps=1e-8, group_rows=Non
     return out, winner, Zhat
 
 
+def sign_majority(S, d, r, B, group_rows=None, vote_perm=None):
+    """DETOX paired with signSGD: returns (out[d] int8 in {-1,0,+1}, winner[n/r])."""
+    if S.dtype != np.uint32 or S.ndim != 2 or S.strides[1] != 4:
+        raise ValueError("expected a 2-D uint32 array with unit column stride")
+    n, ldw = S.shape[0], S.strides[0] // 4
+    if r < 1 or n % r:
+        raise OracleError(EINVAL, "sign_majority")
+    winner = np.empty(n // r, dtype=np.int32)
+    out = np.empty(d, dtype=np.int8)
+    gr, vp = _i32(group_rows, n), _i32(vote_perm, n // r)
+    rc = lib().oracle_sign_majority(_p(S), _i64(n), _i64(d), _i64(ldw), _int(r), _p(gr), _i64(B), _p(vp),
+                                    _p(winner), _p(out))
+    _check(rc, "sign_majority")
+    return out, winner
+
+
 def detox_step_robust_blocks(G, r, B, a0, f, m=-1, group_rows=None, vote_perm=None):
     """Algorithm 2 as deployed in Section 5.2 (setups 2 and 3): A0 = Multi-Krum / Bulyan inside
     every vote group, A1 = mean of the group results (fp64 sum in group order, cast once).

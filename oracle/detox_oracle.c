@@ -586,6 +586,46 @@ int oracle_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
     return ORACLE_OK;
 }
 
+/* ------------------------------------------------------------------------ */
+/* DETOX paired with signSGD (Section 5.2, setup 4, and the signSGD           */
+/* comparison of Section 5.3): every node sends only the signs of its         */
+/* gradient; A0 and A1 are both the coordinate-wise majority vote.            */
+/* S: n x words uint32, bit (c % 32) of word (c / 32) set <=> sign +1, clear  */
+/* <=> sign -1; unused bits of the last word must be zero.                    */
+/* Filter: bytewise majority inside each node group, as for fp32 gradients.   */
+/* Vote group b: a_b[c] = sign( sum over its votes with a majority of +-1 ).  */
+/* Result: out[c] = sign( sum_b a_b[c] ) in {-1, 0, +1}.                      */
+/* ------------------------------------------------------------------------ */
+int oracle_sign_majority(const uint32_t *S, int64_t n, int64_t d, int64_t ldw, int r,
+                         const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
+                         int32_t *winner, int8_t *out)
+{
+    const int64_t words = (d + 31) / 32;
+    if (!S || !winner || !out || n <= 0 || d <= 0 || ldw < words || r < 1 || n % r != 0)
+        return ORACLE_EINVAL;
+    const int64_t V = n / r;
+    if (B < 1 || B > V) return ORACLE_EINVAL;
+    int rc = oracle_majority_filter((const float *)S, n, words, ldw, r, group_rows, winner, NULL, 0);
+    if (rc) return rc;
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < d; ++c) {
+        int total = 0;
+        for (int64_t b = 0; b < B; ++b) {
+            const int64_t lo = (b * V) / B, hi = ((b + 1) * V) / B;
+            int sum = 0;
+            for (int64_t p = lo; p < hi; ++p) {
+                const int32_t w = winner[vote_perm ? vote_perm[p] : p];
+                if (w < 0) continue;   /* a vote without majority is the zero vector */
+                const uint32_t word = S[(int64_t)w * ldw + c / 32];
+                sum += ((word >> (c % 32)) & 1u) ? 1 : -1;
+            }
+            total += (sum > 0) - (sum < 0);
+        }
+        out[c] = (int8_t)((total > 0) - (total < 0));
+    }
+    return ORACLE_OK;
+}
+
 int oracle_num_threads(void)
 {
     int t = 1;

@@ -7,5 +7,5 @@ library's exports can be checked), calling anything needs one.
 """
 from .binding import (  # noqa: F401
     AGG, DetoxError, OP, detox_block_mean, detox_filter_block_mean, detox_majority_filter,
-    detox_step, detox_step_robust_blocks, lib, library_path, robust_bulyan, robust_coord_median, robust_geomedian,
+    detox_sign_majority, detox_step, detox_step_robust_blocks, lib, library_path, robust_bulyan, robust_coord_median, robust_geomedian,
     robust_multikrum, robust_pairwise_sqdist, robust_trimmed_mean, strerror, trace, workspace_bytes)

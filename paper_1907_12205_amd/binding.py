@@ -16,7 +16,7 @@ AGG = dict(multikrum=0, bulyan=1, coord_median=2, geomedian=3, trimmed_mean=4)
 EXPORTS = ["detox_strerror", "detox_last_hip_error", "detox_workspace_bytes",
            "detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
            "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan", "robust_coord_median",
-           "robust_geomedian", "robust_trimmed_mean", "detox_step", "detox_step_robust_blocks", "detox_trace_enable",
+           "robust_geomedian", "robust_trimmed_mean", "detox_step", "detox_step_robust_blocks", "detox_sign_majority", "detox_trace_enable",
            "detox_trace_read"]
 
 
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.detox_step_robust_blocks.argtypes = [vp, i64, i64, i64, i32, vp, i64, vp, i32, i32, i32, vp, vp, i64,
                                                vp, vp, vp, sz, vp]
         L.detox_step_robust_blocks.restype = i32
+        L.detox_sign_majority.argtypes = [vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.detox_sign_majority.restype = i32
         L.detox_trace_enable.argtypes = [i32]
         L.detox_trace_enable.restype = None
         L.detox_trace_read.argtypes = [ctypes.POINTER(_TraceRecord), i32]
@@ -290,6 +292,26 @@ def detox_step_robust_blocks(G, r: int, B: int, a0: str, f: int, m: int = -1, gr
                                         _ptr(block_out), d, _ptr(selected), _ptr(out), _ptr(ws), nb, _stream())
     _check(rc, "detox_step_robust_blocks")
     return out, winner, block_out, selected
+
+
+def detox_sign_majority(S, d: int, r: int, B: int, group_rows=None, vote_perm=None, ws=None, out=None):
+    """signSGD pairing: S is an n x words int32/uint32 device tensor of bit-packed signs.
+    Returns (out_pos[words], out_neg[words], winner[n/r]) as int32 tensors holding the bit masks."""
+    torch = _torch()
+    if S.dim() != 2 or S.stride(1) != 1 or S.element_size() != 4 or not S.is_cuda:
+        raise ValueError("expected a 2-D device tensor of 32-bit words with unit column stride")
+    n, ldw = S.shape[0], S.stride(0)
+    words = (d + 31) // 32
+    gr, vp = _i32(group_rows, S.device), _i32(vote_perm, S.device)
+    groups = n // max(r, 1)
+    winner = torch.empty(max(groups, 1), dtype=torch.int32, device=S.device)
+    if out is None:
+        out = torch.empty((2, words), dtype=torch.int32, device=S.device)
+    ws, nb = _ws(ws, workspace_bytes("filter", max(groups, 1), words), S.device)
+    rc = lib().detox_sign_majority(S.data_ptr(), n, d, ldw, r, _ptr(gr), B, _ptr(vp), _ptr(winner),
+                                   out[0].data_ptr(), out[1].data_ptr(), _ptr(ws), nb, _stream())
+    _check(rc, "detox_sign_majority")
+    return out[0], out[1], winner
 
 
 @contextlib.contextmanager

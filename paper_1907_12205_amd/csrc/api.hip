@@ -482,6 +482,32 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
     return status_of(e);
 }
 
+int detox_sign_majority(const uint32_t *S, int64_t n, int64_t d, int64_t ldw, int r,
+                        const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
+                        int32_t *winner, uint32_t *out_pos, uint32_t *out_neg, void *ws,
+                        size_t ws_bytes, void *stream)
+{
+    const int64_t words = (d + 31) / 32;
+    if (!S || !winner || !out_pos || !out_neg || n <= 0 || d <= 0 || ldw < words || r < 1 ||
+        r > kMaxR || n % r != 0)
+        return DETOX_EINVAL;
+    const int64_t groups = n / r;
+    if (groups > 65535 || n > INT32_MAX || B < 1 || B > groups || B > 255 ||
+        (groups + B - 1) / B > 255)
+        return DETOX_EINVAL;
+    if (!ws_ok(ws, ws_bytes, filter_bytes(groups))) return DETOX_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const FilterWs fw = carve_filter_ws(ws, groups);
+    // the filter compares bit patterns, so the packed words go through it as they are
+    FilterParams p{reinterpret_cast<const float *>(S), words, ldw, r, group_rows, nullptr, groups,
+                   groups, nullptr, 0, fw.flags, fw.flag_partials, fw.gram_partials, fw.redo,
+                   winner, nullptr, 0};
+    hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, nullptr, s);
+    if (e == hipSuccess)
+        e = launch_sign_vote(S, d, ldw, winner, vote_perm, (int)groups, (int)B, out_pos, out_neg, s);
+    return status_of(e);
+}
+
 void detox_trace_enable(int on)
 {
     g_trace_on = on != 0;

@@ -159,4 +159,10 @@ hipError_t launch_trimmed_mean(const RowSet &rs, int g, float *out, const int *r
 hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, int theta,
                               int beta, float *out, hipStream_t s);
 
+// ---- signvote.hip ----------------------------------------------------------
+// Two levels of coordinate-wise majority vote over bit-packed sign rows read through winner[].
+hipError_t launch_sign_vote(const uint32_t *S, int64_t d, int64_t ldw, const int32_t *winner,
+                            const int32_t *vote_perm, int n_votes, int B, uint32_t *out_pos,
+                            uint32_t *out_neg, hipStream_t s);
+
 }  // namespace detox

@@ -197,3 +197,16 @@ def distinct_rows(seed: int, count: int, d: int, sigma: float = 1.0, mean: float
 def integer_rows(seed: int, count: int, d: int, lo: int = -8, hi: int = 8):
     """Rows of small integers: every sum and product is exact in fp32 and fp64."""
     return _rng(seed, _S_BASE).integers(lo, hi + 1, size=(count, d)).astype(np.float32)
+
+
+def pack_signs(X):
+    """Bit-pack the signs of a float matrix for the signSGD pairing (input preparation only):
+    bit (c % 32) of word (c // 32) set <=> X[i, c] >= 0; unused bits of the last word are zero."""
+    n, d = X.shape
+    words = (d + 31) // 32
+    out = np.empty((n, words), dtype=np.uint32)
+    for i in range(n):
+        bits = np.zeros(words * 32, dtype=np.uint8)
+        bits[:d] = X[i] >= 0
+        out[i] = np.packbits(bits.reshape(words, 32), axis=-1, bitorder="little").view(np.uint32).reshape(words)
+    return out
