@@ -70,12 +70,15 @@ typedef enum {
     DETOX_OP_BULYAN = 4,
     DETOX_OP_COORD_MEDIAN = 5,      /* no workspace                                                 */
     DETOX_OP_GEOMEDIAN = 6,
-    DETOX_OP_STEP = 7               /* detox_step: count = n, aux = B                               */
+    DETOX_OP_STEP = 7,              /* detox_step: count = n, aux = B                               */
+    DETOX_OP_COORD_MEDIAN_MANY = 8, /* robust_coord_median_many (depends on count and d)            */
+    DETOX_OP_GEOMEDIAN_MANY = 9     /* robust_geomedian_many                                        */
 } detox_op;
 
 /* Limits of this build. */
 #define DETOX_MAX_R 11         /* redundancy ratio (node-group size)                    */
 #define DETOX_MAX_COUNT 128    /* rows handed to a robust aggregator                    */
+#define DETOX_MANY_MAX_D 128   /* dimension limit of robust_geomedian_many              */
 
 /* Static, human-readable text for a detox_status. */
 const char *detox_strerror(int status);
@@ -184,6 +187,22 @@ int robust_trimmed_mean(const float *X, int64_t count, int64_t d, int64_t ld, in
  *   out        dev, d floats                                                  */
 int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int iters, double eps,
                      float *out, void *ws, size_t ws_bytes, void *stream);
+
+/* The two aggregators of the synthetic mean-estimation experiment (Section 5.3: 220000 nodes,
+ * d = 20..100) applied to ALL rows, i.e. with no limit on `count`; the results are defined
+ * exactly as for robust_coord_median and robust_geomedian.
+ *
+ * robust_coord_median_many: bit-exact coordinate-wise median of `count` rows (1 <= count < 2^31).
+ * The matrix is transposed once into sortable integer keys (the workspace holds them:
+ * DETOX_OP_COORD_MEDIAN_MANY bytes = 4 * d * count rounded up to 64); the middle key(s) of every
+ * coordinate are then found by radix selection.
+ *
+ * robust_geomedian_many: Weiszfeld's iteration streamed over the rows, one pass per iteration,
+ * all sums in fp64 in a fixed order; d <= DETOX_MANY_MAX_D or DETOX_EINVAL.                  */
+int robust_coord_median_many(const float *X, int64_t count, int64_t d, int64_t ld, float *out,
+                             void *ws, size_t ws_bytes, void *stream);
+int robust_geomedian_many(const float *X, int64_t count, int64_t d, int64_t ld, int iters,
+                          double eps, float *out, void *ws, size_t ws_bytes, void *stream);
 
 /* The whole parameter-server step: filter -> B block means -> aggregator, with one pass over
  * G.  The pass that votes also forms the block means; for B <= 8 it accumulates their Gram

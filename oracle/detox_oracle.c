@@ -163,8 +163,21 @@ static inline float key_value(uint32_t k)
     return v;
 }
 
+static int compare_keys(const void *a, const void *b)
+{
+    const uint32_t x = *(const uint32_t *)a, y = *(const uint32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Ascending order of m keys: insertion sort for the short lists of the parameter-server
+ * workloads, the C library's qsort for long ones (keys are plain integers, so the sorted
+ * sequence is unique whichever routine produces it). */
 static void sort_keys(uint32_t *k, int64_t m)
 {
+    if (m > 256) {
+        qsort(k, (size_t)m, sizeof(uint32_t), compare_keys);
+        return;
+    }
     for (int64_t i = 1; i < m; ++i) {
         const uint32_t x = k[i];
         int64_t j = i - 1;
@@ -545,7 +558,7 @@ int oracle_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
         /* distances of the current iterate to every row */
         for (int64_t j = 0; j < count; ++j) {
             const float *xj = X + j * ld;
-#pragma omp parallel for schedule(static)
+#pragma omp parallel for schedule(static) if (chunks > 1)
             for (int64_t ch = 0; ch < chunks; ++ch) {
                 const int64_t c0 = ch * DIST_CHUNK;
                 const int64_t c1 = c0 + DIST_CHUNK < d ? c0 + DIST_CHUNK : d;

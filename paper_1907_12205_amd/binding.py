@@ -10,13 +10,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdetox.so")
 
 OP = dict(filter=0, block_mean=1, pairwise_sqdist=2, multikrum=3, bulyan=4, coord_median=5,
-          geomedian=6, step=7)
+          geomedian=6, step=7, coord_median_many=8, geomedian_many=9)
 AGG = dict(multikrum=0, bulyan=1, coord_median=2, geomedian=3, trimmed_mean=4)
 
 EXPORTS = ["detox_strerror", "detox_last_hip_error", "detox_workspace_bytes",
            "detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
            "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan", "robust_coord_median",
-           "robust_geomedian", "robust_trimmed_mean", "detox_step", "detox_step_robust_blocks", "detox_sign_majority", "detox_trace_enable",
+           "robust_geomedian", "robust_trimmed_mean", "robust_coord_median_many",
+           "robust_geomedian_many", "detox_step", "detox_step_robust_blocks", "detox_sign_majority", "detox_trace_enable",
            "detox_trace_read"]
 
 
@@ -61,6 +62,10 @@ def lib() -> ctypes.CDLL:
         L.robust_trimmed_mean.argtypes = [vp, i64, i64, i64, i32, vp, vp]
         L.robust_trimmed_mean.restype = i32
         L.robust_geomedian.argtypes = [vp, i64, i64, i64, i32, dbl, vp, vp, sz, vp]
+        L.robust_coord_median_many.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
+        L.robust_coord_median_many.restype = i32
+        L.robust_geomedian_many.argtypes = [vp, i64, i64, i64, i32, dbl, vp, vp, sz, vp]
+        L.robust_geomedian_many.restype = i32
         L.detox_step.argtypes = [vp, i64, i64, i64, i32, i32, vp, i64, vp, i32, i32, i32, i32, dbl,
                                  vp, vp, i64, vp, vp, vp, sz, vp]
         L.detox_step_robust_blocks.argtypes = [vp, i64, i64, i64, i32, vp, i64, vp, i32, i32, i32, vp, vp, i64,
@@ -73,7 +78,8 @@ def lib() -> ctypes.CDLL:
         L.detox_trace_read.argtypes = [ctypes.POINTER(_TraceRecord), i32]
         for name in ("detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
                      "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan",
-                     "robust_coord_median", "robust_geomedian", "robust_trimmed_mean", "detox_step", "detox_trace_read"):
+                     "robust_coord_median", "robust_geomedian", "robust_trimmed_mean", "robust_coord_median_many",
+           "robust_geomedian_many", "detox_step", "detox_trace_read"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -236,6 +242,31 @@ def robust_geomedian(X, iters: int = 50, eps: float = 1e-8, out=None, ws=None):
     ws, nb = _ws(ws, workspace_bytes("geomedian", count, d), X.device)
     rc = lib().robust_geomedian(p, count, d, ld, iters, float(eps), _ptr(out), _ptr(ws), nb, _stream())
     _check(rc, "robust_geomedian")
+    return out
+
+
+def robust_coord_median_many(X, out=None, ws=None):
+    """Coordinate-wise median of any number of rows (radix selection on transposed keys)."""
+    torch = _torch()
+    p, count, d, ld = _matrix(X)
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=X.device)
+    ws, nb = _ws(ws, workspace_bytes("coord_median_many", count, d), X.device)
+    rc = lib().robust_coord_median_many(p, count, d, ld, _ptr(out), _ptr(ws), nb, _stream())
+    _check(rc, "robust_coord_median_many")
+    return out
+
+
+def robust_geomedian_many(X, iters: int = 50, eps: float = 1e-8, out=None, ws=None):
+    """Geometric median of any number of short rows (streamed Weiszfeld iterations)."""
+    torch = _torch()
+    p, count, d, ld = _matrix(X)
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=X.device)
+    ws, nb = _ws(ws, workspace_bytes("geomedian_many", count, d), X.device)
+    rc = lib().robust_geomedian_many(p, count, d, ld, iters, float(eps), _ptr(out), _ptr(ws), nb,
+                                     _stream())
+    _check(rc, "robust_geomedian_many")
     return out
 
 

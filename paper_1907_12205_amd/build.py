@@ -42,18 +42,21 @@ def units():
     return out
 
 
-def _stale(obj: str) -> bool:
+def _stale(obj: str, src: str) -> bool:
+    """An object is stale when its source, any header beside it, the public header or this file
+    is newer."""
     if not os.path.exists(obj):
         return True
     t = os.path.getmtime(obj)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "detox.h"), __file__]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if not f.endswith(".hip")]
+    deps += [os.path.join(CSRC, src), os.path.join(HERE, "..", "include", "detox.h"), __file__]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
 def _compile(unit, force=True) -> str:
     src, objname, extra = unit
     obj = os.path.join(OBJ, objname)
-    if not force and not _stale(obj):
+    if not force and not _stale(obj, src):
         return obj
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)

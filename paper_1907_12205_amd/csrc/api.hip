@@ -1,6 +1,6 @@
 // C ABI of libdetox (declared in include/detox.h): argument validation, workspace carving and
 // the order in which the kernels of one call are enqueued.  No arithmetic of the method lives
-// here; every step runs in the kernels of filter.hip, gram.hip, select.hip and sortnet.hip.
+// here; every step runs in the kernels of the other translation units.
 #include <vector>
 
 #include "../../include/detox.h"
@@ -206,9 +206,11 @@ int detox_last_hip_error(void) { return g_last_hip_error; }
 
 size_t detox_workspace_bytes(int op, int64_t count, int64_t d, int64_t aux)
 {
-    (void)d;
     if (count < 1) return 0;
     switch (op) {
+    case DETOX_OP_COORD_MEDIAN_MANY:
+        return d < 1 || count > INT32_MAX - 64 ? 0 : round_up(many_median_ws_bytes(count, d));
+    case DETOX_OP_GEOMEDIAN_MANY: return round_up(many_geomedian_ws_bytes(count));
     case DETOX_OP_FILTER: return filter_bytes(count);
     case DETOX_OP_PAIRWISE_SQDIST:
     case DETOX_OP_MULTIKRUM:
@@ -268,8 +270,9 @@ int detox_filter_block_mean(const float *G, int64_t n, int64_t d, int64_t ld, in
     const FilterWs fw = carve_filter_ws(ws, groups);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
                    fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0};
-    hipError_t e = launch_filter(p, FilterWant::kMeans, nullptr, nullptr, s);
-    if (e == hipSuccess)
+    FilterDone done;
+    hipError_t e = launch_filter(p, FilterWant::kMeans, nullptr, &done, s);
+    if (e == hipSuccess && !done.means_exact)
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     return status_of(e);
 }
@@ -336,6 +339,25 @@ int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
                           static_cast<hipStream_t>(stream));
 }
 
+int robust_coord_median_many(const float *X, int64_t count, int64_t d, int64_t ld, float *out,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !out || count > INT32_MAX - 64 || d > INT32_MAX)
+        return DETOX_EINVAL;
+    if (!ws_ok(ws, ws_bytes, round_up(many_median_ws_bytes(count, d)))) return DETOX_EWORKSPACE;
+    return status_of(launch_many_median(X, count, d, ld, ws, out, static_cast<hipStream_t>(stream)));
+}
+
+int robust_geomedian_many(const float *X, int64_t count, int64_t d, int64_t ld, int iters,
+                          double eps, float *out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!matrix_ok(X, count, d, ld) || !out || d > kManyGeomedianMaxD || iters < 0 || !(eps > 0.0))
+        return DETOX_EINVAL;
+    if (!ws_ok(ws, ws_bytes, round_up(many_geomedian_ws_bytes(count)))) return DETOX_EWORKSPACE;
+    return status_of(launch_many_geomedian(X, count, d, ld, iters, eps, ws, out,
+                                           static_cast<hipStream_t>(stream)));
+}
+
 int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
                const int32_t *group_rows, int64_t B, const int32_t *vote_perm, int agg, int f,
                int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
@@ -390,7 +412,7 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     // what the finalize kernel can do on the side when the Gram matrix comes with the pass
     SmallSelect tail{nullptr, 0, 0, 0, (int)B, aw.Gm, f, agg == DETOX_AGG_MULTIKRUM ? m : 0, aw.sc.scores, selected};
     hipError_t e = launch_filter(p, want, &tail, &done, s);
-    if (e == hipSuccess && Zhat != nullptr)   // redo the blocks that hold a vote without majority
+    if (e == hipSuccess && Zhat != nullptr && !done.means_exact)   // redo the blocks that hold a vote without majority
         e = launch_block_mean(G, d, ld, winner, groups, B, vote_perm, Zhat, ldo, false, true, s);
     if (e != hipSuccess) return status_of(e);
 

@@ -13,6 +13,13 @@ constexpr int kMaxR = 11;              // node-group size limit (pair flags fit 
 constexpr int kMaxCount = 128;         // rows per robust aggregation
 constexpr int kFusedMaxVotes = 1024;   // node groups the persistent filter kernel handles
 constexpr int kFusedMaxGrid = 2048;    // its largest grid (sizes the per-workgroup slots)
+constexpr int kRowParMaxD = 2048;      // widest rows the row-parallel filter / block mean take
+constexpr int kManyGeomedianMaxD = 128;       // widest rows of the streaming Weiszfeld kernels
+constexpr int kManyGeomedianMaxParts = 1024;  // most workgroups (partial sums) of one of its launches
+
+// Very many node groups of short rows (the mean-estimation setting of Section 5.3): filter and
+// block means are mapped by rows (rowpar.hip) instead of by columns (filter.hip).
+inline bool row_parallel(int64_t d, int64_t n_votes) { return d <= kRowParMaxD && n_votes > kFusedMaxVotes; }
 
 // ---- tracing -------------------------------------------------------------
 // While tracing is on, TraceScope brackets a launch with two events on its stream.
@@ -95,6 +102,8 @@ enum class FilterWant {
     kTrimmed   // the same with the coordinate-wise trimmed mean (FilterParams::trim_g per end)
 };
 struct FilterDone {
+    bool means_exact = false;     // Zhat already holds the exact block means (no fix-up of blocks
+                                  //   with a vote without majority is needed)
     int gram_blocks = 0;          // > 0: Gram partial slots written (kGram honoured)
     bool gram_reduced = false;    // the finalize kernel already produced Gm (and, if asked, the
                                   //   Multi-Krum selection) unless *redo
@@ -113,6 +122,23 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
 hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_t *winner,
                              int64_t n_votes, int64_t B, const int32_t *vote_perm, float *Zhat,
                              int64_t ldo, bool copy, bool only_bad, hipStream_t s);
+
+// ---- rowpar.hip -----------------------------------------------------------
+// winner[] of every node group, one wavefront per group; with `means` also Zhat (exact).
+hipError_t launch_filter_rows(const FilterParams &p, bool means, hipStream_t s);
+hipError_t launch_block_mean_rows(const float *G, int64_t d, int64_t ld, const int32_t *winner,
+                                  int64_t n_votes, int64_t B, const int32_t *vote_perm, float *Zhat,
+                                  int64_t ldo, hipStream_t s);
+
+// ---- manyrows.hip ----------------------------------------------------------
+// Coordinate-wise median of `count` rows, any count: ws holds the transposed keys.
+size_t many_median_ws_bytes(int64_t count, int64_t d);
+hipError_t launch_many_median(const float *X, int64_t count, int64_t d, int64_t ld, void *ws,
+                              float *out, hipStream_t s);
+// Geometric median of `count` rows of d <= kManyGeomedianMaxD by streamed Weiszfeld iterations.
+size_t many_geomedian_ws_bytes(int64_t count);
+hipError_t launch_many_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int iters,
+                                 double eps, void *ws, float *out, hipStream_t s);
 
 // ---- gram.hip --------------------------------------------------------------
 size_t gram_partial_bytes(int64_t count);

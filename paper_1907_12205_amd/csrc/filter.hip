@@ -552,6 +552,14 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
                          hipStream_t s)
 {
     const bool mean = want != FilterWant::kVotes;
+    if (row_parallel(p.d, p.n_votes)) {
+        if (mean && p.Zhat == nullptr) return hipErrorInvalidValue;
+        if (done) {
+            *done = FilterDone{};
+            done->means_exact = true;
+        }
+        return launch_filter_rows(p, mean, s);
+    }
     int vec = row_vec_width(p.G, p.ld);
     if (p.Zhat) {
         const int vo = row_vec_width(p.Zhat, p.ldo);
@@ -632,6 +640,8 @@ hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_
                              int64_t n_votes, int64_t B, const int32_t *vote_perm, float *Zhat,
                              int64_t ldo, bool copy, bool only_bad, hipStream_t s)
 {
+    if (!copy && !only_bad && row_parallel(d, n_votes))
+        return launch_block_mean_rows(G, d, ld, winner, n_votes, B, vote_perm, Zhat, ldo, s);
     int vec = row_vec_width(G, ld);
     const int vo = row_vec_width(Zhat, ldo);
     vec = vo < vec ? vo : vec;

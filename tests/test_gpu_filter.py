@@ -143,7 +143,7 @@ def test_many_groups_take_the_general_kernel(dx):
     """More than 1024 node groups: the per-group flag words with integer atomics (grid.y = vote
     group) instead of the persistent kernel; also exercised with block means and the whole step."""
     rng = np.random.default_rng(77)
-    groups, r, d = 1500, 3, 301
+    groups, r, d = 1500, 3, 2301          # wider than the rows the row-parallel kernels take
     base = rng.standard_normal((groups, d)).astype(np.float32)
     G = np.repeat(base, r, axis=0)
     for g in rng.choice(groups, size=200, replace=False):

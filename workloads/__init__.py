@@ -55,8 +55,9 @@ class Workload:
         """Dense n x d host matrix (a view of an n x ld buffer when ld is given)."""
         ld = self.d if ld is None else ld
         buf = np.zeros((self.n, ld), dtype=np.float32)
-        for i in range(self.n):
-            buf[i, : self.d] = self.row(i)
+        buf[:, : self.d] = np.repeat(self.base, self.r, axis=0)
+        for i, v in self.byz.items():
+            buf[i, : self.d] = v
         return buf[:, : self.d]
 
     def honest_mean(self) -> np.ndarray:
@@ -182,6 +183,37 @@ def config(index: int, seed: int = DEFAULT_SEED, d: Optional[int] = None) -> Wor
                         vanilla=[dict(aggregator="coord_median"),
                                  dict(aggregator="multikrum", f=10, m=95)])
     raise ValueError("config index must be 1..5")
+
+
+def mean_estimation(d: int, seed: int = DEFAULT_SEED, n: int = 220_000, r: int = 11,
+                    q: Optional[int] = None, batch: int = 20, norm: float = 100.0) -> Workload:
+    """The synthetic mean-estimation setting of Section 5.3: n = 220000 nodes in groups of
+    r = 11, q = floor(e^r / 3) Byzantine nodes placed uniformly at random; every node group
+    holds the mean of `batch` = 20 iid N(0, I_d) samples (honest members bitwise identical);
+    every Byzantine node sends the same constant vector of l2 norm 100.  The true mean is 0, so
+    the error of an estimate is its l2 norm."""
+    import math
+
+    if q is None:
+        q = int(math.floor(math.exp(r) / 3.0))
+    groups = n // r
+    base = np.empty((groups, d), dtype=np.float32)
+    rng = _rng(seed, _S_BASE)
+    step = 4096
+    for g0 in range(0, groups, step):
+        g1 = min(groups, g0 + step)
+        x = rng.standard_normal((g1 - g0, batch, d), dtype=np.float32)
+        base[g0:g1] = x.mean(axis=1, dtype=np.float64).astype(np.float32)
+    rows = np.sort(_rng(seed, _S_PLACEMENT).choice(n, size=q, replace=False))
+    v = np.full(d, norm / math.sqrt(d), dtype=np.float32)
+    byz = {int(i): v for i in rows}
+    B = 65
+    return Workload(f"mean_estimation_d{d}", n, r, q, d, base, byz,
+                    attack=f"constant vector of norm {norm:g}",
+                    detox=[dict(B=B, aggregator="coord_median"),
+                           dict(B=B, aggregator="geomedian", iters=50, eps=1e-8)],
+                    vanilla=[dict(aggregator="coord_median"),
+                             dict(aggregator="geomedian", iters=50, eps=1e-8)])
 
 
 def distinct_rows(seed: int, count: int, d: int, sigma: float = 1.0, mean: float = 0.0):
