@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kBlock) void transpose_keys_kernel(const uint32_t *
     for (int i = 0; i < kTile / 4; ++i) {
         const int64_t row = r0 + ty + 4 * i, col = c0 + tx;
         uint32_t k = kPadKey;
-        if (row < count && col < d) k = key_of_bits(__builtin_nontemporal_load(X + row * ld + col));
+        if (row < count && col < d) k = key_of_bits(X[row * ld + col]);   // tiles share cache lines
         tile[ty + 4 * i][tx] = k;
     }
     __syncthreads();
@@ -50,32 +50,71 @@ __global__ __launch_bounds__(kBlock) void transpose_keys_kernel(const uint32_t *
 }
 
 constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelBins = 2048;
+constexpr int kSelKeep = 24576;   // keys of the chosen first-digit bin that fit in LDS (96 KB)
 
 struct SelShared {
     uint32_t hist[kSelBins];
-    uint32_t wave_total[kSelThreads / kWave];
+    uint32_t wave_total[kSelWaves];
+    uint32_t wave_min[kSelWaves];
     uint32_t bin, before, inside;   // the bin holding the wanted rank, keys before it, keys in it
-    uint32_t wave_min[kSelThreads / kWave];
+    uint32_t kept;                  // keys stored in keep[]
+    uint32_t keep[kSelKeep];
+};
+
+// The keys of one column in global memory: f(key) for every key (padding included), four 16-byte
+// loads in flight per thread.  An index beyond the end re-reads the last vector and is skipped.
+struct ColumnKeys {
+    const uint4 *k4;
+    int64_t n4;
+    template <class F>
+    __device__ void for_each(F f) const
+    {
+        for (int64_t i0 = threadIdx.x; i0 < n4; i0 += 4 * kSelThreads) {
+            uint4 k[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = i0 + (int64_t)u * kSelThreads;
+                k[u] = k4[i < n4 ? i : n4 - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool on = i0 + (int64_t)u * kSelThreads < n4;
+                f(k[u].x, on), f(k[u].y, on), f(k[u].z, on), f(k[u].w, on);
+            }
+        }
+    }
+};
+
+// The keys kept in LDS.
+struct KeptKeys {
+    const uint32_t *keep;
+    uint32_t n;
+    template <class F>
+    __device__ void for_each(F f) const
+    {
+        const uint32_t trips = (n + kSelThreads - 1) / kSelThreads;
+        for (uint32_t it = 0; it < trips; ++it) {
+            const uint32_t i = it * kSelThreads + threadIdx.x;
+            f(keep[i < n ? i : n - 1], i < n);
+        }
+    }
 };
 
 // One radix pass: among the keys that agree with `prefix` on `mask`, histogram the digit at
 // `shift` and locate the bin that holds rank `rank` (0-based among those keys).
-__device__ inline void radix_pass(const uint32_t *keys, int64_t cs, uint32_t prefix, uint32_t mask,
-                                  int shift, uint32_t digit_mask, uint32_t rank, SelShared &sh)
+template <class Keys>
+__device__ inline void radix_pass(const Keys &keys, uint32_t prefix, uint32_t mask, int shift,
+                                  uint32_t digit_mask, uint32_t rank, SelShared &sh)
 {
     const int t = threadIdx.x;
     sh.hist[t] = 0u;
     sh.hist[t + kSelThreads] = 0u;
     __syncthreads();
-    const uint4 *k4 = reinterpret_cast<const uint4 *>(keys);
-    for (int64_t i = t; i < cs / 4; i += kSelThreads) {
-        const uint4 k = k4[i];
-        if ((k.x & mask) == prefix) atomicAdd(&sh.hist[(k.x >> shift) & digit_mask], 1u);
-        if ((k.y & mask) == prefix) atomicAdd(&sh.hist[(k.y >> shift) & digit_mask], 1u);
-        if ((k.z & mask) == prefix) atomicAdd(&sh.hist[(k.z >> shift) & digit_mask], 1u);
-        if ((k.w & mask) == prefix) atomicAdd(&sh.hist[(k.w >> shift) & digit_mask], 1u);
-    }
+    keys.for_each([&](uint32_t k, bool on) {
+        if (on && (k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & digit_mask], 1u);
+    });
     __syncthreads();
     // exclusive scan over the bins, two adjacent bins per thread
     const uint32_t h0 = sh.hist[2 * t], h1 = sh.hist[2 * t + 1];
@@ -99,21 +138,65 @@ __device__ inline void radix_pass(const uint32_t *keys, int64_t cs, uint32_t pre
     __syncthreads();
 }
 
-// Median of column blockIdx.x of K (count keys, padded to cs).
+// Smallest key above `floor_key` (0xffffffff if there is none); every thread returns it.
+template <class Keys>
+__device__ inline uint32_t min_above(const Keys &keys, uint32_t floor_key, SelShared &sh)
+{
+    uint32_t m = 0xffffffffu;
+    keys.for_each([&](uint32_t k, bool on) {
+        if (on && k > floor_key) m = k < m ? k : m;
+    });
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        const uint32_t o = __shfl_xor(m, off, kWave);
+        m = o < m ? o : m;
+    }
+    __syncthreads();                               // an earlier result has been read by everyone
+    if ((threadIdx.x & (kWave - 1)) == 0) sh.wave_min[threadIdx.x >> 6] = m;
+    __syncthreads();
+    uint32_t r = sh.wave_min[0];
+    for (int w = 1; w < kSelWaves; ++w) r = sh.wave_min[w] < r ? sh.wave_min[w] : r;
+    return r;
+}
+
+// Median of column blockIdx.x of K (count keys, padded to cs).  The first digit is found with one
+// pass over the column; if the keys that share it fit in LDS they are copied there by a second
+// pass and the remaining digits never touch memory again.
 __global__ __launch_bounds__(kSelThreads) void radix_median_kernel(const uint32_t *K, int64_t count,
                                                                    int64_t cs, float *out)
 {
     __shared__ SelShared sh;
-    const uint32_t *keys = K + (int64_t)blockIdx.x * cs;
+    const ColumnKeys column{reinterpret_cast<const uint4 *>(K + (int64_t)blockIdx.x * cs), cs / 4};
     uint32_t rank = (uint32_t)((count - 1) / 2);   // the lower middle (the middle when count is odd)
-    uint32_t prefix = 0u, mask = 0u;
-    radix_pass(keys, cs, prefix, mask, 21, 0x7ffu, rank, sh);
-    prefix |= sh.bin << 21, mask |= 0x7ffu << 21, rank -= sh.before;
+    radix_pass(column, 0u, 0u, 21, 0x7ffu, rank, sh);
+    uint32_t prefix = sh.bin << 21, mask = 0x7ffu << 21;
+    rank -= sh.before;
+    const bool in_lds = sh.inside <= (uint32_t)kSelKeep;   // uniform
+    if (threadIdx.x == 0) sh.kept = 0u;
     __syncthreads();
-    radix_pass(keys, cs, prefix, mask, 10, 0x7ffu, rank, sh);
+    if (in_lds) {
+        const int lane = threadIdx.x & (kWave - 1);
+        column.for_each([&](uint32_t k, bool on) {
+            // one LDS atomic per wavefront and call: the matching lanes take consecutive slots
+            const bool take = on && (k & mask) == prefix;
+            const unsigned long long who = __ballot(take);
+            if (who != 0ull) {
+                const int leader = __ffsll((long long)who) - 1;
+                uint32_t base = 0u;
+                if (lane == leader) base = atomicAdd(&sh.kept, (uint32_t)__popcll(who));
+                base = __shfl(base, leader, kWave);
+                if (take) sh.keep[base + __popcll(who & ((1ull << lane) - 1ull))] = k;
+            }
+        });
+        __syncthreads();
+    }
+    const KeptKeys kept{sh.keep, in_lds ? sh.kept : 1u};
+    if (in_lds) radix_pass(kept, prefix, mask, 10, 0x7ffu, rank, sh);
+    else radix_pass(column, prefix, mask, 10, 0x7ffu, rank, sh);
     prefix |= sh.bin << 10, mask |= 0x7ffu << 10, rank -= sh.before;
     __syncthreads();
-    radix_pass(keys, cs, prefix, mask, 0, 0x3ffu, rank, sh);
+    if (in_lds) radix_pass(kept, prefix, mask, 0, 0x3ffu, rank, sh);
+    else radix_pass(column, prefix, mask, 0, 0x3ffu, rank, sh);
     const uint32_t key_lo = prefix | sh.bin;
     rank -= sh.before;                              // position among the copies of key_lo
     const uint32_t copies = sh.inside;
@@ -123,24 +206,8 @@ __global__ __launch_bounds__(kSelThreads) void radix_median_kernel(const uint32_
     }
     uint32_t key_hi = key_lo;
     if (rank + 1 >= copies) {   // uniform: the upper middle is the smallest key above key_lo
-        uint32_t m = 0xffffffffu;
-        const uint4 *k4 = reinterpret_cast<const uint4 *>(keys);
-        for (int64_t i = threadIdx.x; i < cs / 4; i += kSelThreads) {
-            const uint4 k = k4[i];
-            if (k.x > key_lo) m = k.x < m ? k.x : m;
-            if (k.y > key_lo) m = k.y < m ? k.y : m;
-            if (k.z > key_lo) m = k.z < m ? k.z : m;
-            if (k.w > key_lo) m = k.w < m ? k.w : m;
-        }
-#pragma unroll
-        for (int off = kWave / 2; off > 0; off >>= 1) {
-            const uint32_t o = __shfl_xor(m, off, kWave);
-            m = o < m ? o : m;
-        }
-        if ((threadIdx.x & (kWave - 1)) == 0) sh.wave_min[threadIdx.x >> 6] = m;
-        __syncthreads();
-        key_hi = sh.wave_min[0];
-        for (int w = 1; w < kSelThreads / kWave; ++w) key_hi = sh.wave_min[w] < key_hi ? sh.wave_min[w] : key_hi;
+        key_hi = in_lds ? min_above(kept, key_lo, sh) : 0xffffffffu;
+        if (key_hi == 0xffffffffu) key_hi = min_above(column, key_lo, sh);   // it lies in a later bin
     }
     if (threadIdx.x == 0)
         out[blockIdx.x] = __fmul_rn(__fadd_rn(value_of_key(key_lo), value_of_key(key_hi)), 0.5f);
@@ -152,6 +219,7 @@ constexpr int kWzLanes = 16;                          // lanes that share a row
 constexpr int kWzGroups = kWzThreads / kWzLanes;      // rows a workgroup has in flight
 constexpr int kWzMaxD = kManyGeomedianMaxD;
 constexpr int kWzStride = kWzMaxD + 1;                // doubles per partial: sums, then the weight sum
+constexpr int kWzUnroll = 2;                          // rows of a row group in flight
 constexpr int kWzSlices = kWzThreads / kWzMaxD;       // 8 slices of the partial list per coordinate
 
 // Adds up the `parts` partials of the previous launch in a fixed order; on return sum[c]
@@ -163,10 +231,19 @@ __device__ inline void wz_reduce_partials(const double *partials, int parts, dou
     const int c = t % kWzMaxD, slice = t / kWzMaxD;
     const int per = (parts + kWzSlices - 1) / kWzSlices;
     const int p0 = slice * per, p1 = p0 + per < parts ? p0 + per : parts;
+    // eight loads in flight per thread; the adds keep the order of the list
     double a = 0.0, wa = 0.0;
-    for (int p = p0; p < p1; ++p) {
-        a += partials[(int64_t)p * kWzStride + c];
-        if (c == 0) wa += partials[(int64_t)p * kWzStride + kWzMaxD];
+    for (int q0 = p0; q0 < p1; q0 += 8) {
+        double z[8], zw[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int p = q0 + u < p1 ? q0 + u : p1 - 1;
+            z[u] = partials[(int64_t)p * kWzStride + c];
+            zw[u] = c == 0 ? partials[(int64_t)p * kWzStride + kWzMaxD] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (q0 + u < p1) a += z[u], wa += zw[u];
     }
     slice_sum[slice * kWzStride + c] = a;
     if (c == 0) slice_sum[slice * kWzStride + kWzMaxD] = wa;
@@ -206,32 +283,46 @@ __global__ __launch_bounds__(kWzThreads) void weiszfeld_rows_kernel(
     }
     const int64_t row0 = (count * blockIdx.x) / gridDim.x, row1 = (count * (blockIdx.x + 1)) / gridDim.x;
     double acc[KPL], wacc = 0.0;
+    const double inv_eps = 1.0 / eps;
 #pragma unroll
     for (int k = 0; k < KPL; ++k) acc[k] = 0.0;
-    for (int64_t j = row0 + g; j < row1; j += kWzGroups) {
-        double v[KPL];
+    // kWzUnroll rows of the row group are in flight at once; a slot beyond row1 re-reads the last
+    // row of the range with weight 0
+    for (int64_t j0 = row0 + g; j0 < row1; j0 += (int64_t)kWzUnroll * kWzGroups) {
+        double v[kWzUnroll][KPL];
+        bool on[kWzUnroll];
 #pragma unroll
-        for (int k = 0; k < KPL; ++k) {
-            const int c = l + kWzLanes * k;
-            const float f = X[j * ld + (c < d ? c : d - 1)];
-            v[k] = c < d ? (double)f : 0.0;
-        }
-        double w = 1.0;
-        if constexpr (!INIT) {
-            double s = 0.0;
+        for (int u = 0; u < kWzUnroll; ++u) {
+            const int64_t j = j0 + (int64_t)u * kWzGroups;
+            on[u] = j < row1;
+            const float *row = X + (on[u] ? j : row1 - 1) * ld;
 #pragma unroll
             for (int k = 0; k < KPL; ++k) {
-                const double diff = x[k] - v[k];
-                s = fma(diff, diff, s);
+                const int c = l + kWzLanes * k;
+                const float f = row[c < d ? c : d - 1];
+                v[u][k] = c < d ? (double)f : 0.0;
             }
-#pragma unroll
-            for (int off = kWzLanes / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWzLanes);
-            const double dist = sqrt(s);
-            w = 1.0 / (dist > eps ? dist : eps);
         }
 #pragma unroll
-        for (int k = 0; k < KPL; ++k) acc[k] = fma(w, v[k], acc[k]);
-        wacc += w;
+        for (int u = 0; u < kWzUnroll; ++u) {
+            double w = 1.0;
+            if constexpr (!INIT) {
+                double s = 0.0;
+#pragma unroll
+                for (int k = 0; k < KPL; ++k) {
+                    const double diff = x[k] - v[u][k];
+                    s = fma(diff, diff, s);
+                }
+#pragma unroll
+                for (int off = kWzLanes / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWzLanes);
+                // 1 / max(sqrt(s), eps) without a square root followed by a division
+                w = s > eps * eps ? rsqrt(s) : inv_eps;
+            }
+            if (!on[u]) w = 0.0;
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) acc[k] = fma(w, v[u][k], acc[k]);
+            wacc += w;
+        }
     }
     // fixed order: the four row groups of a wavefront pairwise, then the wavefronts in order
 #pragma unroll

@@ -6,10 +6,10 @@
 //                            lanes take the columns, compare the r member rows pairwise as
 //                            integers, OR the "pair differs" bits over the wavefront and pick the
 //                            winner (lowest row index of the value held by more than r/2).
-//   block_mean_rows_kernel : one wavefront per (vote group, 64 columns) (Algorithm 2, A0 = mean):
+//   block_mean_rows_kernel : one workgroup per (vote group, 64 columns) (Algorithm 2, A0 = mean):
 //                            fp32 adds in vote order, one fp32 division, as everywhere in this
-//                            library; the winner indices of the next 64 votes and the rows of
-//                            the current ones are fetched ahead of the dependent chain of adds.
+//                            library.  The chain of adds is serial, so eight wavefronts fetch the
+//                            rows of up to 512 votes into LDS at once and one walks the chain.
 #include "detox_internal.h"
 
 namespace detox {
@@ -23,104 +23,110 @@ __global__ __launch_bounds__(kBlock) void filter_rows_kernel(const uint32_t *G, 
                                                              int64_t n_votes, int32_t *winner)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t j = (int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 6);
+    // the wavefront index is uniform: say so, and the row table below lives in scalar registers
+    const int64_t j = (int64_t)blockIdx.x * kGroupsPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (j >= n_votes) return;   // whole wavefronts leave together
     int64_t row[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) row[k] = group_rows ? group_rows[j * R + k] : j * R + k;
 
+    // bits: pair (a, b) differs somewhere in the row.  Each lane compares its two columns as one
+    // 64-bit word; the per-pair test over the wavefront is a scalar compare of the lane mask, so
+    // `bits` lives in scalar registers and costs the vector unit one compare per pair.
     unsigned long long bits = 0ull;
     for (int64_t c0 = 0; c0 < d; c0 += 2 * kWave) {
         // two columns per lane and trip; a column beyond d re-reads column d-1 (always a valid
-        // address) and is masked out, so the loads carry no branch
-        uint32_t x[2][R];
+        // address; both members of a pair read the same column, so it cannot add a difference
+        // that is not there), which keeps the loads free of branches
+        unsigned long long x[R];
+        const int64_t ca = c0 + lane, cb = c0 + kWave + lane;
+        const int64_t cca = ca < d ? ca : d - 1, ccb = cb < d ? cb : d - 1;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int64_t c = c0 + u * kWave + lane;
-            const int64_t cc = c < d ? c : d - 1;
-#pragma unroll
-            for (int k = 0; k < R; ++k) x[u][k] = __builtin_nontemporal_load(G + row[k] * ld + cc);
+        for (int k = 0; k < R; ++k) {
+            const uint32_t *row_k = G + row[k] * ld;   // rows share cache lines: cached loads
+            x[k] = (unsigned long long)row_k[cca] | ((unsigned long long)row_k[ccb] << 32);
         }
         int pair = 0;
 #pragma unroll
         for (int a = 0; a < R; ++a)
 #pragma unroll
             for (int b = a + 1; b < R; ++b, ++pair)
-                if ((x[0][a] ^ x[0][b]) | (x[1][a] ^ x[1][b])) bits |= 1ull << pair;
+                if (__any(x[a] != x[b])) bits |= 1ull << pair;
     }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) bits |= __shfl_xor(bits, off, kWave);
 
-    // first member whose value is held by more than R/2 members; report the lowest row index
-    int32_t win = -1;
+    // Lane a < R looks at member a: how many members hold its value, and their lowest row index.
+    // The first member whose value is held by more than R/2 names the winner.
+    const int a = lane < R ? lane : 0;
+    int votes = 0;
+    int64_t lowest = INT64_MAX;
 #pragma unroll
-    for (int a = 0; a < R; ++a) {
-        int votes = 0;
-        int64_t lowest = row[a];
-#pragma unroll
-        for (int b = 0; b < R; ++b) {
-            bool same = true;
-            if (a != b) {
-                const int lo = a < b ? a : b, hi = a < b ? b : a;
-                const int pair = lo * R - lo * (lo + 1) / 2 + (hi - lo - 1);
-                same = ((bits >> pair) & 1ull) == 0ull;
-            }
-            if (same) {
-                ++votes;
-                lowest = row[b] < lowest ? row[b] : lowest;
-            }
+    for (int b = 0; b < R; ++b) {
+        const int lo = a < b ? a : b, hi = a < b ? b : a;
+        const int pair = lo * R - lo * (lo + 1) / 2 + (hi - lo - 1);
+        const bool same = a == b || ((bits >> pair) & 1ull) == 0ull;
+        if (same) {
+            ++votes;
+            lowest = row[b] < lowest ? row[b] : lowest;
         }
-        if (win < 0 && 2 * votes > R) win = (int32_t)lowest;
     }
+    const unsigned long long has = __ballot(lane < R && 2 * votes > R);
+    int32_t win = -1;
+    if (has != 0ull) win = (int32_t)__shfl(lowest, __ffsll((long long)has) - 1, kWave);
     if (lane == 0) winner[j] = win;
 }
 
-constexpr int kMeanBatch = 64;   // votes whose winner indices one wavefront load brings in
-constexpr int kMeanAhead = 32;   // rows in flight ahead of the chain of adds
+constexpr int kBmThreads = 512;                 // 8 wavefronts fetch, the first one adds
+constexpr int kBmWaves = kBmThreads / kWave;
+constexpr int kBmVotes = 512;                   // votes staged per trip (128 KB of LDS)
+constexpr int kBmSlots = kBmVotes / kBmWaves;   // votes per wavefront and trip
 
-__global__ __launch_bounds__(kWave) void block_mean_rows_kernel(const float *G, int64_t d, int64_t ld,
-                                                                const int32_t *winner,
-                                                                int64_t n_votes, int64_t B,
-                                                                const int32_t *vote_perm,
-                                                                float *Zhat, int64_t ldo)
+__global__ __launch_bounds__(kBmThreads) void block_mean_rows_kernel(const float *G, int64_t d,
+                                                                     int64_t ld, const int32_t *winner,
+                                                                     int64_t n_votes, int64_t B,
+                                                                     const int32_t *vote_perm,
+                                                                     float *Zhat, int64_t ldo)
 {
-    const int lane = threadIdx.x;
+    __shared__ float tile[kBmVotes][kWave];
+    __shared__ int32_t wrow[kBmVotes];
+    const int t = threadIdx.x, lane = t & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int64_t b = blockIdx.y;
     const int64_t lo = (b * n_votes) / B, hi = ((b + 1) * n_votes) / B;
-    const int64_t c = (int64_t)blockIdx.x * kWave + lane;
-    const int64_t cc = c < d ? c : d - 1;
-
-    auto fetch_winner = [&](int64_t base) -> int32_t {
-        const int64_t pos = base + lane;
-        if (pos >= hi) return -1;
-        return winner[vote_perm ? vote_perm[pos] : pos];
-    };
+    const int64_t c = (int64_t)blockIdx.x * kWave + lane;   // the column of this lane
+    const int64_t cc = c < d ? c : d - 1;                    // beyond d: re-read d-1, never written
 
     float acc = 0.0f;
-    int32_t w_next = fetch_winner(lo);
-    for (int64_t base = lo; base < hi; base += kMeanBatch) {
-        const int32_t w = w_next;
-        w_next = fetch_winner(base + kMeanBatch);
-        const int cnt = hi - base < kMeanBatch ? (int)(hi - base) : kMeanBatch;
-        for (int k0 = 0; k0 < cnt; k0 += kMeanAhead) {
-            float v[kMeanAhead];
+    for (int64_t base = lo; base < hi; base += kBmVotes) {
+        const int cnt = hi - base < kBmVotes ? (int)(hi - base) : kBmVotes;
+        if (t < cnt) wrow[t] = winner[vote_perm ? vote_perm[base + t] : base + t];
+        __syncthreads();
+        // all fetches of a wavefront are issued before the first one is used; a slot beyond cnt
+        // re-reads the last vote and is never added; a vote without majority reads row 0 and
+        // stores zero
+        float x[kBmSlots];
 #pragma unroll
-            for (int u = 0; u < kMeanAhead; ++u) {
-                // lanes past the end of the block hold -1: their slot reads row 0 and is not added
-                const int32_t wk = __shfl(w, k0 + u, kWave);
-                const float x = G[(int64_t)(wk < 0 ? 0 : wk) * ld + cc];
-                v[u] = wk < 0 ? 0.0f : x;
-            }
+        for (int i = 0; i < kBmSlots; ++i) {
+            const int v = wave + kBmWaves * i;
+            const int32_t w = wrow[v < cnt ? v : cnt - 1];
+            const float g = G[(int64_t)(w < 0 ? 0 : w) * ld + cc];
+            x[i] = w < 0 ? 0.0f : g;
+        }
 #pragma unroll
-            for (int u = 0; u < kMeanAhead; ++u) {
-                if (k0 + u < cnt) {
-                    const bool first = base == lo && k0 + u == 0;
-                    acc = first ? v[u] : __fadd_rn(acc, v[u]);
-                }
+        for (int i = 0; i < kBmSlots; ++i) tile[wave + kBmWaves * i][lane] = x[i];
+        __syncthreads();
+        if (wave == 0) {
+            // the chain of adds is serial; its operands come from LDS sixteen at a time
+            for (int v0 = 0; v0 < cnt; v0 += 16) {
+                float z[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) z[u] = tile[(v0 + u) & (kBmVotes - 1)][lane];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    if (v0 + u < cnt) acc = (base == lo && v0 + u == 0) ? z[u] : __fadd_rn(acc, z[u]);
             }
         }
     }
-    if (c < d) Zhat[b * ldo + c] = __fdiv_rn(acc, (float)(hi - lo));
+    if (wave == 0 && c < d) Zhat[b * ldo + c] = __fdiv_rn(acc, (float)(hi - lo));
 }
 
 }  // namespace
@@ -163,7 +169,7 @@ hipError_t launch_block_mean_rows(const float *G, int64_t d, int64_t ld, const i
 {
     TraceScope t("block_mean_rows", s);
     const dim3 grid((unsigned)((d + kWave - 1) / kWave), (unsigned)B);
-    block_mean_rows_kernel<<<grid, kWave, 0, s>>>(G, d, ld, winner, n_votes, B, vote_perm, Zhat, ldo);
+    block_mean_rows_kernel<<<grid, kBmThreads, 0, s>>>(G, d, ld, winner, n_votes, B, vote_perm, Zhat, ldo);
     return hipGetLastError();
 }
 

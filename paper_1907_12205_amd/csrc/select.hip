@@ -157,44 +157,61 @@ __global__ __launch_bounds__(kRowThreads) void bulyan_select_kernel(int count, i
     }
 }
 
+// Sum of one value per thread over the workgroup (at most two wavefronts), formed in a fixed
+// order (pairwise inside a wavefront, then wavefront 0 + wavefront 1), so every thread returns the
+// same bits.  `slot` is two doubles of LDS; threads beyond the data pass 0.
+__device__ inline double group_sum(double v, double *slot)
+{
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    if (blockDim.x <= kWave) return v;
+    __syncthreads();                               // the previous use of slot is over
+    if ((threadIdx.x & (kWave - 1)) == 0) slot[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return slot[0] + slot[1];
+}
+
 // Weiszfeld on the Gram matrix: the iterate is x = sum_j w_j x_j with sum w = 1, so
 // ||x - x_j||^2 = w'Gw - 2 (Gw)_j + G_jj.  Exactly `iters` updates from w = 1/count.  One thread
-// per row, the Gram matrix in LDS (dynamic: count*count doubles); the two scalar sums are formed
-// by every thread in the same order, so all threads hold identical values.
+// per row, the Gram matrix in LDS (dynamic: count*count doubles, read down its columns, which by
+// symmetry are its rows, so the lanes never collide on a bank); the two scalar sums of an update
+// are formed by group_sum, so all threads hold identical values.
 __global__ __launch_bounds__(kMaxCount) void weiszfeld_kernel(const double *Gm, int count,
                                                               int iters, double eps,
                                                               double *weights)
 {
     extern __shared__ double G[];
-    __shared__ double w[kMaxCount], gw[kMaxCount], inv[kMaxCount];
+    __shared__ double w[kMaxCount], slot[2];
     const int j = threadIdx.x;
+    const bool live = j < count;
+    const int jj = live ? j : 0;
     for (int e = threadIdx.x; e < count * count; e += blockDim.x) G[e] = Gm[e];
-    if (j < count) w[j] = 1.0 / (double)count;
+    if (live) w[j] = 1.0 / (double)count;
     __syncthreads();
+    const double gjj = G[jj * count + jj];
     for (int t = 0; t < iters; ++t) {
-        if (j < count) {
-            double s = 0.0;
-            for (int k = 0; k < count; ++k) s += G[j * count + k] * w[k];
-            gw[j] = s;
+        // (Gw)_j with four partial sums added in a fixed order
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        int k = 0;
+        for (; k + 4 <= count; k += 4) {
+            s0 = fma(G[(k + 0) * count + jj], w[k + 0], s0);
+            s1 = fma(G[(k + 1) * count + jj], w[k + 1], s1);
+            s2 = fma(G[(k + 2) * count + jj], w[k + 2], s2);
+            s3 = fma(G[(k + 3) * count + jj], w[k + 3], s3);
         }
-        __syncthreads();
-        if (j < count) {
-            double quad = 0.0;
-            for (int k = 0; k < count; ++k) quad += w[k] * gw[k];
-            double d2 = quad - 2.0 * gw[j] + G[j * count + j];
-            if (d2 < 0.0) d2 = 0.0;
-            const double dist = sqrt(d2);
-            inv[j] = 1.0 / (dist > eps ? dist : eps);
-        }
-        __syncthreads();
-        if (j < count) {
-            double inv_sum = 0.0;
-            for (int k = 0; k < count; ++k) inv_sum += inv[k];
-            w[j] = inv[j] / inv_sum;
-        }
+        for (; k < count; ++k) s0 = fma(G[k * count + jj], w[k], s0);
+        const double gw = (s0 + s1) + (s2 + s3);
+        const double quad = group_sum(live ? w[jj] * gw : 0.0, slot);
+        double d2 = quad - 2.0 * gw + gjj;
+        if (d2 < 0.0) d2 = 0.0;
+        const double dist = sqrt(d2);
+        const double inv = live ? 1.0 / (dist > eps ? dist : eps) : 0.0;
+        const double inv_sum = group_sum(inv, slot);
+        __syncthreads();                           // every thread has read w
+        if (live) w[j] = inv / inv_sum;
         __syncthreads();
     }
-    if (j < count) weights[j] = w[j];
+    if (live) weights[j] = w[j];
 }
 
 // WEIGHTED = false: out = fp32( (sum_i (double) row[rows[i]]) / m ), logical rows in list order.
