@@ -4,9 +4,11 @@
 // nor a count x count Gram matrix is possible, so:
 //   coordinate-wise median : the matrix is transposed once into order-preserving integer keys,
 //                            one contiguous column per coordinate (transpose_keys_kernel); one
-//                            workgroup per coordinate then finds the middle key(s) by radix
-//                            selection, 11 + 11 + 10 bits, histograms in LDS
-//                            (radix_median_kernel).  Integer work throughout: bit-exact.
+//                            coordinate's middle key(s) are then found by radix selection,
+//                            11 + 11 + 10 bits, histograms in LDS; the first digit is counted by
+//                            several workgroups per column, the keys that share it are copied
+//                            out and the rest of the selection runs in LDS (radix_hist_kernel,
+//                            radix_gather_kernel, radix_finish_kernel).  Integer work: bit-exact.
 //   geometric median       : Weiszfeld's iteration streamed over the rows, one launch per
 //                            iteration (weiszfeld_rows_kernel).  16 lanes share a row; weights,
 //                            distances and sums are fp64; every reduction runs in a fixed order.
@@ -52,6 +54,7 @@ __global__ __launch_bounds__(kBlock) void transpose_keys_kernel(const uint32_t *
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelBins = 2048;
+constexpr int kSelAhead = 8;      // 16-byte loads in flight per thread
 constexpr int kSelKeep = 24576;   // keys of the chosen first-digit bin that fit in LDS (96 KB)
 
 struct SelShared {
@@ -59,27 +62,26 @@ struct SelShared {
     uint32_t wave_total[kSelWaves];
     uint32_t wave_min[kSelWaves];
     uint32_t bin, before, inside;   // the bin holding the wanted rank, keys before it, keys in it
-    uint32_t kept;                  // keys stored in keep[]
-    uint32_t keep[kSelKeep];
+    uint32_t kept;                  // keys copied out so far
 };
 
-// The keys of one column in global memory: f(key) for every key (padding included), four 16-byte
-// loads in flight per thread.  An index beyond the end re-reads the last vector and is skipped.
+// The keys of one column in global memory: f(key) for every key (padding included), kSelAhead
+// 16-byte loads in flight per thread.  An index beyond the end re-reads the last vector and is skipped.
 struct ColumnKeys {
     const uint4 *k4;
     int64_t n4;
     template <class F>
     __device__ void for_each(F f) const
     {
-        for (int64_t i0 = threadIdx.x; i0 < n4; i0 += 4 * kSelThreads) {
-            uint4 k[4];
+        for (int64_t i0 = threadIdx.x; i0 < n4; i0 += kSelAhead * kSelThreads) {
+            uint4 k[kSelAhead];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kSelAhead; ++u) {
                 const int64_t i = i0 + (int64_t)u * kSelThreads;
                 k[u] = k4[i < n4 ? i : n4 - 1];
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kSelAhead; ++u) {
                 const bool on = i0 + (int64_t)u * kSelThreads < n4;
                 f(k[u].x, on), f(k[u].y, on), f(k[u].z, on), f(k[u].w, on);
             }
@@ -102,20 +104,10 @@ struct KeptKeys {
     }
 };
 
-// One radix pass: among the keys that agree with `prefix` on `mask`, histogram the digit at
-// `shift` and locate the bin that holds rank `rank` (0-based among those keys).
-template <class Keys>
-__device__ inline void radix_pass(const Keys &keys, uint32_t prefix, uint32_t mask, int shift,
-                                  uint32_t digit_mask, uint32_t rank, SelShared &sh)
+// Locates the bin of sh.hist that holds rank `rank` (0-based): sh.bin, sh.before, sh.inside.
+__device__ inline void locate_rank(uint32_t rank, SelShared &sh)
 {
     const int t = threadIdx.x;
-    sh.hist[t] = 0u;
-    sh.hist[t + kSelThreads] = 0u;
-    __syncthreads();
-    keys.for_each([&](uint32_t k, bool on) {
-        if (on && (k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & digit_mask], 1u);
-    });
-    __syncthreads();
     // exclusive scan over the bins, two adjacent bins per thread
     const uint32_t h0 = sh.hist[2 * t], h1 = sh.hist[2 * t + 1];
     const uint32_t mine = h0 + h1;
@@ -136,6 +128,30 @@ __device__ inline void radix_pass(const Keys &keys, uint32_t prefix, uint32_t ma
         sh.bin = 2 * t + 1, sh.before = before + h0, sh.inside = h1;
     }
     __syncthreads();
+}
+
+// Histogram in sh.hist of the digit at `shift` over the keys that agree with `prefix` on `mask`.
+template <class Keys>
+__device__ inline void digit_histogram(const Keys &keys, uint32_t prefix, uint32_t mask, int shift,
+                                       uint32_t digit_mask, SelShared &sh)
+{
+    const int t = threadIdx.x;
+    sh.hist[t] = 0u;
+    sh.hist[t + kSelThreads] = 0u;
+    __syncthreads();
+    keys.for_each([&](uint32_t k, bool on) {
+        if (on && (k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & digit_mask], 1u);
+    });
+    __syncthreads();
+}
+
+// One radix pass: histogram, then the bin that holds rank `rank` among the matching keys.
+template <class Keys>
+__device__ inline void radix_pass(const Keys &keys, uint32_t prefix, uint32_t mask, int shift,
+                                  uint32_t digit_mask, uint32_t rank, SelShared &sh)
+{
+    digit_histogram(keys, prefix, mask, shift, digit_mask, sh);
+    locate_rank(rank, sh);
 }
 
 // Smallest key above `floor_key` (0xffffffff if there is none); every thread returns it.
@@ -159,38 +175,135 @@ __device__ inline uint32_t min_above(const Keys &keys, uint32_t floor_key, SelSh
     return r;
 }
 
-// Median of column blockIdx.x of K (count keys, padded to cs).  The first digit is found with one
-// pass over the column; if the keys that share it fit in LDS they are copied there by a second
-// pass and the remaining digits never touch memory again.
-__global__ __launch_bounds__(kSelThreads) void radix_median_kernel(const uint32_t *K, int64_t count,
-                                                                   int64_t cs, float *out)
+// The work on a column is spread over `slices` workgroups where the keys are many, in three
+// launches: (1) every slice histograms the first digit of its part of the column; (2) every slice
+// adds up the histograms, finds the bin of the middle key and copies its keys of that bin out;
+// (3) one workgroup per column gathers those few keys into LDS and finishes the selection there.
+struct SelPlan {
+    const uint32_t *K;     // d columns of cs keys
+    int64_t count, cs;
+    int slices;
+    uint32_t *H;           // d x slices x kSelBins first-digit histograms
+    uint32_t *N;           // d x slices: keys copied out by each slice
+    uint32_t *Kc;          // d x slices x cap copied keys
+    int64_t cap;
+};
+
+__device__ inline ColumnKeys slice_keys(const SelPlan &p, int64_t col, int slice)
+{
+    const int64_t n4 = p.cs / 4;
+    const int64_t lo = n4 * slice / p.slices, hi = n4 * (slice + 1) / p.slices;
+    return ColumnKeys{reinterpret_cast<const uint4 *>(p.K + col * p.cs) + lo, hi - lo};
+}
+
+__global__ __launch_bounds__(kSelThreads) void radix_hist_kernel(SelPlan p)
+{
+    __shared__ uint32_t hist[kSelBins];
+    const int t = threadIdx.x;
+    hist[t] = 0u, hist[t + kSelThreads] = 0u;
+    __syncthreads();
+    slice_keys(p, blockIdx.y, blockIdx.x).for_each([&](uint32_t k, bool on) {
+        if (on) atomicAdd(&hist[k >> 21], 1u);
+    });
+    __syncthreads();
+    uint32_t *H = p.H + ((int64_t)blockIdx.y * p.slices + blockIdx.x) * kSelBins;
+    H[t] = hist[t], H[t + kSelThreads] = hist[t + kSelThreads];
+}
+
+// The first-digit histogram of column `col` (sum over its slices) into sh.hist, then the bin of
+// the lower middle key.
+__device__ inline void first_digit(const SelPlan &p, int64_t col, uint32_t rank, SelShared &sh)
+{
+    const int t = threadIdx.x;
+    const uint32_t *H = p.H + col * p.slices * kSelBins;
+    uint32_t a = 0u, b = 0u;
+    for (int s = 0; s < p.slices; ++s) a += H[s * kSelBins + t], b += H[s * kSelBins + t + kSelThreads];
+    sh.hist[t] = a, sh.hist[t + kSelThreads] = b;
+    __syncthreads();
+    locate_rank(rank, sh);
+}
+
+__global__ __launch_bounds__(kSelThreads) void radix_gather_kernel(SelPlan p)
 {
     __shared__ SelShared sh;
-    const ColumnKeys column{reinterpret_cast<const uint4 *>(K + (int64_t)blockIdx.x * cs), cs / 4};
-    uint32_t rank = (uint32_t)((count - 1) / 2);   // the lower middle (the middle when count is odd)
-    radix_pass(column, 0u, 0u, 21, 0x7ffu, rank, sh);
-    uint32_t prefix = sh.bin << 21, mask = 0x7ffu << 21;
-    rank -= sh.before;
-    const bool in_lds = sh.inside <= (uint32_t)kSelKeep;   // uniform
+    const int64_t col = blockIdx.y;
+    const int slice = blockIdx.x;
+    first_digit(p, col, (uint32_t)((p.count - 1) / 2), sh);
+    const uint32_t bin = sh.bin;
+    const bool few = sh.inside <= (uint32_t)kSelKeep;   // uniform over the column's workgroups
     if (threadIdx.x == 0) sh.kept = 0u;
     __syncthreads();
-    if (in_lds) {
+    if (few) {
+        uint32_t *dst = p.Kc + (col * p.slices + slice) * p.cap;
         const int lane = threadIdx.x & (kWave - 1);
-        column.for_each([&](uint32_t k, bool on) {
-            // one LDS atomic per wavefront and call: the matching lanes take consecutive slots
-            const bool take = on && (k & mask) == prefix;
-            const unsigned long long who = __ballot(take);
-            if (who != 0ull) {
-                const int leader = __ffsll((long long)who) - 1;
-                uint32_t base = 0u;
-                if (lane == leader) base = atomicAdd(&sh.kept, (uint32_t)__popcll(who));
-                base = __shfl(base, leader, kWave);
-                if (take) sh.keep[base + __popcll(who & ((1ull << lane) - 1ull))] = k;
+        // per trip of the loop: every lane counts its matching keys, the wavefront reserves room
+        // for all of them with one LDS atomic, and each lane stores its keys behind those of the
+        // lanes below it (the order of the copied keys does not matter to the selection)
+        const ColumnKeys keys = slice_keys(p, col, slice);
+        for (int64_t i0 = threadIdx.x; i0 - threadIdx.x < keys.n4; i0 += kSelAhead * kSelThreads) {
+            uint4 k[kSelAhead];
+#pragma unroll
+            for (int u = 0; u < kSelAhead; ++u) {
+                const int64_t i = i0 + (int64_t)u * kSelThreads;
+                k[u] = keys.k4[i < keys.n4 ? i : keys.n4 - 1];
             }
-        });
+            uint32_t take = 0u;   // bit 4u+e: component e of vector u matches
+#pragma unroll
+            for (int u = 0; u < kSelAhead; ++u) {
+                if (i0 + (int64_t)u * kSelThreads < keys.n4) {
+                    take |= ((k[u].x >> 21) == bin ? 1u : 0u) << (4 * u);
+                    take |= ((k[u].y >> 21) == bin ? 2u : 0u) << (4 * u);
+                    take |= ((k[u].z >> 21) == bin ? 4u : 0u) << (4 * u);
+                    take |= ((k[u].w >> 21) == bin ? 8u : 0u) << (4 * u);
+                }
+            }
+            const uint32_t mine = (uint32_t)__popc(take);
+            uint32_t incl = mine;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off, kWave);
+                if (lane >= off) incl += up;
+            }
+            uint32_t base = 0u;
+            if (lane == kWave - 1 && incl != 0u) base = atomicAdd(&sh.kept, incl);
+            uint32_t at = __shfl(base, kWave - 1, kWave) + incl - mine;
+#pragma unroll
+            for (int u = 0; u < kSelAhead; ++u) {
+                if ((take >> (4 * u)) & 1u) dst[at++] = k[u].x;
+                if ((take >> (4 * u)) & 2u) dst[at++] = k[u].y;
+                if ((take >> (4 * u)) & 4u) dst[at++] = k[u].z;
+                if ((take >> (4 * u)) & 8u) dst[at++] = k[u].w;
+            }
+        }
         __syncthreads();
     }
-    const KeptKeys kept{sh.keep, in_lds ? sh.kept : 1u};
+    if (threadIdx.x == 0) p.N[col * p.slices + slice] = sh.kept;
+}
+
+__global__ __launch_bounds__(kSelThreads) void radix_finish_kernel(SelPlan p, float *out)
+{
+    __shared__ SelShared sh;
+    __shared__ uint32_t keep[kSelKeep];
+    const int64_t col = blockIdx.x;
+    const ColumnKeys column{reinterpret_cast<const uint4 *>(p.K + col * p.cs), p.cs / 4};
+    uint32_t rank = (uint32_t)((p.count - 1) / 2);   // the lower middle (the middle when count is odd)
+    first_digit(p, col, rank, sh);
+    uint32_t prefix = sh.bin << 21, mask = 0x7ffu << 21;
+    rank -= sh.before;
+    const uint32_t total = sh.inside;
+    const bool in_lds = total <= (uint32_t)kSelKeep;   // uniform
+    __syncthreads();
+    if (in_lds) {
+        uint32_t at = 0u;
+        for (int s = 0; s < p.slices; ++s) {
+            const uint32_t n = p.N[col * p.slices + s];
+            const uint32_t *src = p.Kc + (col * p.slices + s) * p.cap;
+            for (uint32_t i = threadIdx.x; i < n; i += kSelThreads) keep[at + i] = src[i];
+            at += n;
+        }
+        __syncthreads();
+    }
+    const KeptKeys kept{keep, in_lds ? total : 1u};
     if (in_lds) radix_pass(kept, prefix, mask, 10, 0x7ffu, rank, sh);
     else radix_pass(column, prefix, mask, 10, 0x7ffu, rank, sh);
     prefix |= sh.bin << 10, mask |= 0x7ffu << 10, rank -= sh.before;
@@ -200,8 +313,8 @@ __global__ __launch_bounds__(kSelThreads) void radix_median_kernel(const uint32_
     const uint32_t key_lo = prefix | sh.bin;
     rank -= sh.before;                              // position among the copies of key_lo
     const uint32_t copies = sh.inside;
-    if (count & 1) {
-        if (threadIdx.x == 0) out[blockIdx.x] = value_of_key(key_lo);
+    if (p.count & 1) {
+        if (threadIdx.x == 0) out[col] = value_of_key(key_lo);
         return;
     }
     uint32_t key_hi = key_lo;
@@ -210,7 +323,7 @@ __global__ __launch_bounds__(kSelThreads) void radix_median_kernel(const uint32_
         if (key_hi == 0xffffffffu) key_hi = min_above(column, key_lo, sh);   // it lies in a later bin
     }
     if (threadIdx.x == 0)
-        out[blockIdx.x] = __fmul_rn(__fadd_rn(value_of_key(key_lo), value_of_key(key_hi)), 0.5f);
+        out[col] = __fmul_rn(__fadd_rn(value_of_key(key_lo), value_of_key(key_hi)), 0.5f);
 }
 
 // ---- streaming Weiszfeld ------------------------------------------------------------------
@@ -380,26 +493,71 @@ hipError_t wz_run(const float *X, int64_t count, int64_t d, int64_t ld, int iter
 
 int64_t many_median_stride(int64_t count) { return (count + kTile - 1) / kTile * kTile; }
 
-size_t many_median_ws_bytes(int64_t count, int64_t d)
+namespace {
+struct SelLayout {
+    int slices;
+    int64_t cap;
+    size_t off_H, off_N, off_Kc, bytes;
+};
+// Workgroups per column: what gives the chip's 256 compute units two workgroups each, at most
+// 16 and at least 1, and never slices shorter than one trip of a workgroup.
+SelLayout sel_layout(int64_t count, int64_t d)
 {
-    return (size_t)many_median_stride(count) * (size_t)d * sizeof(uint32_t);
+    const int64_t cs = many_median_stride(count);
+    int64_t slices = 512 / d;   // all of them resident at once, two to a compute unit
+    const int64_t longest = (cs / 4 + (int64_t)kSelAhead * kSelThreads - 1) / ((int64_t)kSelAhead * kSelThreads);
+    if (slices > longest) slices = longest;
+    if (slices > 16) slices = 16;
+    if (slices < 1) slices = 1;
+    SelLayout L;
+    L.slices = (int)slices;
+    const int64_t slice_keys = (cs / 4 + slices - 1) / slices * 4 + 4;
+    L.cap = slice_keys < kSelKeep ? slice_keys : kSelKeep;
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    L.off_H = up((size_t)cs * (size_t)d * sizeof(uint32_t));
+    L.off_N = L.off_H + up((size_t)d * slices * kSelBins * sizeof(uint32_t));
+    L.off_Kc = L.off_N + up((size_t)d * slices * sizeof(uint32_t));
+    L.bytes = L.off_Kc + up((size_t)d * slices * (size_t)L.cap * sizeof(uint32_t));
+    return L;
 }
+}  // namespace
+
+size_t many_median_ws_bytes(int64_t count, int64_t d) { return sel_layout(count, d).bytes; }
 
 hipError_t launch_many_median(const float *X, int64_t count, int64_t d, int64_t ld, void *ws,
                               float *out, hipStream_t s)
 {
     const int64_t cs = many_median_stride(count);
-    uint32_t *K = static_cast<uint32_t *>(ws);
+    const SelLayout L = sel_layout(count, d);
+    char *base = static_cast<char *>(ws);
+    uint32_t *K = reinterpret_cast<uint32_t *>(base);
+    hipError_t e;
     {
         TraceScope t("transpose_keys", s);
         const dim3 grid((unsigned)(cs / kTile), (unsigned)((d + kTile - 1) / kTile));
         transpose_keys_kernel<<<grid, kBlock, 0, s>>>(reinterpret_cast<const uint32_t *>(X), count, d,
                                                       ld, K, cs);
-        const hipError_t e = hipGetLastError();
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    TraceScope t("radix_median", s);
-    radix_median_kernel<<<(unsigned)d, kSelThreads, 0, s>>>(K, count, cs, out);
+    SelPlan p{K, count, cs, L.slices, reinterpret_cast<uint32_t *>(base + L.off_H),
+              reinterpret_cast<uint32_t *>(base + L.off_N), reinterpret_cast<uint32_t *>(base + L.off_Kc),
+              L.cap};
+    const dim3 grid((unsigned)L.slices, (unsigned)d);
+    {
+        TraceScope t("radix_hist", s);
+        radix_hist_kernel<<<grid, kSelThreads, 0, s>>>(p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    {
+        TraceScope t("radix_gather", s);
+        radix_gather_kernel<<<grid, kSelThreads, 0, s>>>(p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    TraceScope t("radix_finish", s);
+    radix_finish_kernel<<<(unsigned)d, kSelThreads, 0, s>>>(p, out);
     return hipGetLastError();
 }
 
