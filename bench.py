@@ -55,6 +55,52 @@ def time_steps(fn, steps, warmup, torch):
     return start.elapsed_time(stop) / steps, wall_ms / steps
 
 
+def mean_estimation_paths(dx, workloads, torch, np, steps, d=100):
+    """The synthetic mean-estimation setting of Section 5.3 (220000 nodes in groups of 11, d = 100):
+    the DETOX step and the same aggregator over all rows.  A step lasts tens of microseconds, less
+    than the host needs to enqueue it, so each path is timed twice: called from Python, and as a
+    replayed HIP graph of 20 calls (the GPU's own time; every replay is checked against the eager
+    result)."""
+    from paper_1907_12205_amd.binding import StepBuffers
+    w = workloads.mean_estimation(d)
+    n, r, q = w.n, w.r, w.q
+    G = torch.from_numpy(w.matrix()).cuda()
+    B = w.detox[0]["B"]
+    buf = StepBuffers(n, d, r, B, G.device)
+    out = torch.empty(d, dtype=torch.float32, device=G.device)
+    ws_m = torch.empty(dx.workspace_bytes("coord_median_many", n, d), dtype=torch.uint8, device=G.device)
+    ws_g = torch.empty(dx.workspace_bytes("geomedian_many", n, d), dtype=torch.uint8, device=G.device)
+    paths = [
+        (f"DETOX coord-median, B={B}", lambda: dx.detox_step(G, r, q, B, "coord_median", buffers=buf), buf.out),
+        (f"DETOX geometric median, B={B}, 50 iterations", lambda: dx.detox_step(G, r, q, B, "geomedian", buffers=buf), buf.out),
+        (f"vanilla coord-median over {n} rows", lambda: dx.robust_coord_median_many(G, out=out, ws=ws_m), out),
+        (f"vanilla geometric median over {n} rows, 50 iterations", lambda: dx.robust_geomedian_many(G, 50, 1e-8, out=out, ws=ws_g), out),
+    ]
+    rep, res = 20, []
+    for name, fn, result in paths:
+        ms_eager, _ = time_steps(fn, max(steps, 5), 3, torch)
+        want = result.clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(rep):
+                fn()
+        same = True
+        for _ in range(3):
+            result.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            same = same and bool(torch.equal(result, want))
+        ms_graph, _ = time_steps(graph.replay, 10, 2, torch)
+        ms_graph /= rep
+        res.append({"path": name, "ms_per_step_eager": round(ms_eager, 5), "ms_per_step_graph": round(ms_graph, 5),
+                    "GBps_aggregated": round(n * d * 4 / (ms_graph * 1e-3) / 1e9, 1),
+                    "hbm_frac_algorithmic": round(n * d * 4 / (ms_graph * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "graph_replays_match_eager": same})
+        log(f"[bench] mean estimation, {name}: {ms_graph:.4f} ms/step on the GPU ({ms_eager:.4f} called from Python), "
+            f"replays match: {same}")
+    return {"workload": f"{w.name}: n={n}, r={r}, q={q}, d={d}, {w.attack}", "paths": res}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,6 +111,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-vanilla", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other aggregators' timings")
+    ap.add_argument("--no-mean-estimation", action="store_true", help="skip the many-short-rows setting")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the parameter-server step on ONE GPU (the step has no "
@@ -201,6 +248,10 @@ def main():
         for o in others:
             log(f"[bench] {o['path']}: {o['ms_per_step']:.4f} ms/step, {o['hbm_frac_algorithmic'] * 100:.1f}% of HBM peak (algorithmic bytes)")
 
+    mean_est = None
+    if not args.no_others and not args.no_mean_estimation:
+        mean_est = mean_estimation_paths(dx, workloads, torch, np, args.steps)
+
     # ---- CPU oracle on the host cores (a reported baseline, not the target) ------------------
     cpu = None
     if not args.no_cpu:
@@ -235,7 +286,8 @@ def main():
         "step_hbm_frac_algorithmic": (round(step_alg_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                                       if step_alg_bytes else None),
         "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
-        "roofline": roofline, "vanilla": vanilla, "other_paths": others, "cpu_baseline": cpu,
+        "roofline": roofline, "vanilla": vanilla, "other_paths": others, "mean_estimation": mean_est,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
 

@@ -344,18 +344,18 @@ __device__ inline void wz_reduce_partials(const double *partials, int parts, dou
     const int c = t % kWzMaxD, slice = t / kWzMaxD;
     const int per = (parts + kWzSlices - 1) / kWzSlices;
     const int p0 = slice * per, p1 = p0 + per < parts ? p0 + per : parts;
-    // eight loads in flight per thread; the adds keep the order of the list
+    // sixteen loads in flight per thread; the adds keep the order of the list
     double a = 0.0, wa = 0.0;
-    for (int q0 = p0; q0 < p1; q0 += 8) {
-        double z[8], zw[8];
+    for (int q0 = p0; q0 < p1; q0 += 16) {
+        double z[16], zw[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 16; ++u) {
             const int p = q0 + u < p1 ? q0 + u : p1 - 1;
             z[u] = partials[(int64_t)p * kWzStride + c];
             zw[u] = c == 0 ? partials[(int64_t)p * kWzStride + kWzMaxD] : 0.0;
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < 16; ++u)
             if (q0 + u < p1) a += z[u], wa += zw[u];
     }
     slice_sum[slice * kWzStride + c] = a;

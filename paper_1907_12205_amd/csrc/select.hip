@@ -157,61 +157,110 @@ __global__ __launch_bounds__(kRowThreads) void bulyan_select_kernel(int count, i
     }
 }
 
-// Sum of one value per thread over the workgroup (at most two wavefronts), formed in a fixed
-// order (pairwise inside a wavefront, then wavefront 0 + wavefront 1), so every thread returns the
-// same bits.  `slot` is two doubles of LDS; threads beyond the data pass 0.
-__device__ inline double group_sum(double v, double *slot)
+// v + (the value of v in the lane the data-parallel-primitive pattern CTRL pairs this lane with).
+template <int CTRL>
+__device__ inline double add_paired_lane(double v)
 {
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    if (blockDim.x <= kWave) return v;
-    __syncthreads();                               // the previous use of slot is over
-    if ((threadIdx.x & (kWave - 1)) == 0) slot[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return slot[0] + slot[1];
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return v + __hiloint2double(hi, lo);
 }
 
-// Weiszfeld on the Gram matrix: the iterate is x = sum_j w_j x_j with sum w = 1, so
-// ||x - x_j||^2 = w'Gw - 2 (Gw)_j + G_jj.  Exactly `iters` updates from w = 1/count.  One thread
-// per row, the Gram matrix in LDS (dynamic: count*count doubles, read down its columns, which by
-// symmetry are its rows, so the lanes never collide on a bank); the two scalar sums of an update
-// are formed by group_sum, so all threads hold identical values.
-__global__ __launch_bounds__(kMaxCount) void weiszfeld_kernel(const double *Gm, int count,
-                                                              int iters, double eps,
-                                                              double *weights)
+// Sum over the 64 lanes of a wavefront, the same bits in every lane: lane pairs, quads, halves of
+// a row of 16 (mirror inside 8), rows (mirror inside 16), then the four row sums in a fixed order.
+// All 64 lanes must be active.  No LDS traffic, unlike a shuffle.
+__device__ inline double wave_sum(double v)
+{
+    v = add_paired_lane<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = add_paired_lane<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = add_paired_lane<0x141>(v);   // row_half_mirror
+    v = add_paired_lane<0x140>(v);   // row_mirror
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    double row[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        row[q] = __hiloint2double(__builtin_amdgcn_readlane(hi, 16 * q), __builtin_amdgcn_readlane(lo, 16 * q));
+    return (row[0] + row[1]) + (row[2] + row[3]);
+}
+
+constexpr int kWzLanesPerRow = 4;                          // lanes that share a row of the matrix
+constexpr int kWzGramThreads = kMaxCount * kWzLanesPerRow;
+constexpr int kWzGramWaves = kWzGramThreads / kWave;
+
+// Weiszfeld on the Gram matrix: the iterate is x = sum_j u_j x_j / S with S = sum_j u_j, so
+//   ||x - x_j||^2 = u'Gu / S^2 - 2 (Gu)_j / S + G_jj   and   u_j <- 1 / max(||x - x_j||, eps).
+// Exactly `iters` updates from u = 1; the weights written out are u / S.  Four lanes share a row
+// (lane q takes the columns k = q mod 4; the four partial sums are added pairwise), the Gram
+// matrix sits in LDS (dynamic: count*count doubles, read down its columns, which by symmetry are
+// its rows).  The two sums of an update, u'Gu and S, are formed together in a fixed order and with
+// the same bits in every thread; an update costs a quarter pass over the matrix per lane, one such
+// pair of sums and two barriers.
+__global__ __launch_bounds__(kWzGramThreads) void weiszfeld_kernel(const double *Gm, int count,
+                                                                   int iters, double eps,
+                                                                   double *weights)
 {
     extern __shared__ double G[];
-    __shared__ double w[kMaxCount], slot[2];
-    const int j = threadIdx.x;
+    __shared__ double u_all[kMaxCount];
+    __shared__ double cross[2][kWzGramWaves][2];   // [parity of the update][wavefront][u'Gu, S]
+    const int tid = threadIdx.x;
+    const int j = tid / kWzLanesPerRow, q = tid % kWzLanesPerRow;
     const bool live = j < count;
     const int jj = live ? j : 0;
-    for (int e = threadIdx.x; e < count * count; e += blockDim.x) G[e] = Gm[e];
-    if (live) w[j] = 1.0 / (double)count;
+    const int waves = blockDim.x / kWave;
+    const int wave = tid >> 6;
+    for (int e = tid; e < count * count; e += blockDim.x) G[e] = Gm[e];
+    double u = live ? 1.0 : 0.0;
+    if (q == 0 && j < kMaxCount) u_all[j] = u;
     __syncthreads();
     const double gjj = G[jj * count + jj];
-    for (int t = 0; t < iters; ++t) {
-        // (Gw)_j with four partial sums added in a fixed order
-        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-        int k = 0;
-        for (; k + 4 <= count; k += 4) {
-            s0 = fma(G[(k + 0) * count + jj], w[k + 0], s0);
-            s1 = fma(G[(k + 1) * count + jj], w[k + 1], s1);
-            s2 = fma(G[(k + 2) * count + jj], w[k + 2], s2);
-            s3 = fma(G[(k + 3) * count + jj], w[k + 3], s3);
+    const double inv_eps = 1.0 / eps, eps2 = eps * eps;
+
+    // sum over the workgroup of a pair of per-row values (lanes q != 0 and dead rows pass zeros)
+    auto sum_pair = [&](double a, double b, int parity, double &sa, double &sb) {
+        sa = wave_sum(a), sb = wave_sum(b);
+        if (waves > 1) {
+            if ((tid & (kWave - 1)) == 0) cross[parity][wave][0] = sa, cross[parity][wave][1] = sb;
+            __syncthreads();
+            sa = cross[parity][0][0], sb = cross[parity][0][1];
+            for (int w = 1; w < waves; ++w) sa += cross[parity][w][0], sb += cross[parity][w][1];
         }
-        for (; k < count; ++k) s0 = fma(G[k * count + jj], w[k], s0);
-        const double gw = (s0 + s1) + (s2 + s3);
-        const double quad = group_sum(live ? w[jj] * gw : 0.0, slot);
-        double d2 = quad - 2.0 * gw + gjj;
-        if (d2 < 0.0) d2 = 0.0;
-        const double dist = sqrt(d2);
-        const double inv = live ? 1.0 / (dist > eps ? dist : eps) : 0.0;
-        const double inv_sum = group_sum(inv, slot);
-        __syncthreads();                           // every thread has read w
-        if (live) w[j] = inv / inv_sum;
+    };
+
+    for (int t = 0; t < iters; ++t) {
+        // this lane's quarter of (Gu)_j, eight matrix entries in flight
+        double s0 = 0.0, s1 = 0.0;
+        int k = q;
+        for (; k + 7 * kWzLanesPerRow < count; k += 8 * kWzLanesPerRow) {
+            double g[8], w[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                g[e] = G[(k + e * kWzLanesPerRow) * count + jj];
+                w[e] = u_all[k + e * kWzLanesPerRow];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) s0 = fma(g[e], w[e], s0), s1 = fma(g[e + 1], w[e + 1], s1);
+        }
+        for (; k < count; k += kWzLanesPerRow) s0 = fma(G[k * count + jj], u_all[k], s0);
+        double gu = s0 + s1;
+        gu = add_paired_lane<0xB1>(gu);   // lanes q and q^1
+        gu = add_paired_lane<0x4E>(gu);   // and the other pair: (Gu)_j in all four lanes
+        const bool mine = live && q == 0;
+        double quad, S;
+        sum_pair(mine ? u * gu : 0.0, mine ? u : 0.0, t & 1, quad, S);
+        const double rS = 1.0 / S;
+        const double d2 = fma(quad * rS, rS, fma(-2.0 * rS, gu, gjj));
+        // 1 / max(sqrt(d2), eps) without a square root followed by a division
+        u = live ? (d2 > eps2 ? rsqrt(d2) : inv_eps) : 0.0;
+        __syncthreads();                           // every thread is done reading u_all
+        if (mine) u_all[j] = u;
         __syncthreads();
     }
-    if (live) weights[j] = w[j];
+    // the weights of the final iterate
+    const bool mine = live && q == 0;
+    double total, unused;
+    __syncthreads();
+    sum_pair(mine ? u : 0.0, 0.0, 0, total, unused);
+    if (mine) weights[j] = u / total;
 }
 
 // WEIGHTED = false: out = fp32( (sum_i (double) row[rows[i]]) / m ), logical rows in list order.
@@ -354,7 +403,7 @@ hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double e
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    const int threads = count <= 64 ? 64 : kMaxCount;
+    const int threads = (int)((count * kWzLanesPerRow + kWave - 1) / kWave) * kWave;
     TraceScope t("weiszfeld_gram", s);
     weiszfeld_kernel<<<1, threads, lds, s>>>(Gm, (int)count, iters, eps, weights);
     return hipGetLastError();
