@@ -276,7 +276,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
         bad |= win < 0;
     }
     bad = __syncthreads_or(bad);
-    if (threadIdx.x == 0) *redo = bad ? 1 : 0;
+    if (threadIdx.x == 0) redo[0] = bad ? 1 : 0, redo[1] = 0;   // [1]: arrival counter of the redo kernel
     if (bad || q.gram_partials == nullptr) return;   // uniform
     __shared__ double Gl[kSmallCount * kSmallCount];
     small_gram_reduce(q, gv, Gl);

@@ -32,7 +32,8 @@ constexpr int mfma_max_waves(int T) { return 256 * mfma_blocks_per_cu(T) * (kBlo
 // ---------------------------------------------------------------------------------------
 template <int C, int VEC, bool MEANS>
 __global__ __launch_bounds__(kBlock) void gram_small_kernel(RowSet rs, double *partials,
-                                                            const int *run_if)
+                                                            const int *run_if, SmallSelect tail,
+                                                            unsigned *arrived)
 {
     constexpr int NP = C * (C + 1) / 2;
     if (run_if && *run_if == 0) return;   // uniform: the caller's partials are valid already
@@ -75,6 +76,26 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(RowSet rs, double *p
         for (int w = 0; w < kBlock / kWave; ++w) s += red[w][threadIdx.x];
         partials[(int64_t)blockIdx.x * NP + threadIdx.x] = s;
     }
+    if (arrived == nullptr) return;   // uniform
+    // The workgroup that finishes last adds up everybody's partials and, if asked, goes on to
+    // Multi-Krum's scores and selection: stores, fence, count; the one that counts gridDim.x - 1
+    // others fences again and reads.  The counter is left at zero for the next call.
+    __shared__ int last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) last = atomicAdd(arrived, 1u) == gridDim.x - 1 ? 1 : 0;
+    __syncthreads();
+    if (last == 0) return;            // uniform
+    __threadfence();
+    __shared__ double Gl[kSmallCount * kSmallCount];
+    tail.gram_partials = partials;
+    tail.gram_blocks = (int)gridDim.x;
+    tail.slot_stride = NP;
+    tail.pair_stride = 1;
+    tail.count = C;
+    small_gram_reduce<kBlock>(tail, small_gram_load<kBlock>(tail), Gl);
+    if (tail.krum_m > 0) small_multikrum(tail, Gl);
+    if (threadIdx.x == 0) *arrived = 0u;
 }
 
 // One workgroup per pair: thread t adds the partials of workgroups t, t+256, ... in that order,
@@ -258,15 +279,15 @@ __global__ void gram_mfma_reduce2_kernel(const double *slices, int T, int count,
 
 template <int C>
 hipError_t launch_small(const RowSet &rs, double *partials, int grid, int vec, const int *run_if,
-                        hipStream_t s)
+                        const SmallSelect &tail, unsigned *arrived, hipStream_t s)
 {
-    TraceScope t(run_if ? "gram_f64_if_redo" : "gram_f64", s);
+    TraceScope t(run_if ? "gram_select_if_redo" : "gram_f64", s);
 #define DETOX_GS(V)                                                                               \
     do {                                                                                          \
         if (rs.means())                                                                           \
-            gram_small_kernel<C, V, true><<<grid, kBlock, 0, s>>>(rs, partials, run_if);          \
+            gram_small_kernel<C, V, true><<<grid, kBlock, 0, s>>>(rs, partials, run_if, tail, arrived);          \
         else                                                                                      \
-            gram_small_kernel<C, V, false><<<grid, kBlock, 0, s>>>(rs, partials, run_if);         \
+            gram_small_kernel<C, V, false><<<grid, kBlock, 0, s>>>(rs, partials, run_if, tail, arrived);         \
     } while (0)
     if (vec == 4)
         DETOX_GS(4);
@@ -279,7 +300,7 @@ hipError_t launch_small(const RowSet &rs, double *partials, int grid, int vec, c
 }
 
 hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int *grid_out,
-                            hipStream_t s)
+                            const SmallSelect &tail, unsigned *arrived, hipStream_t s)
 {
     const int vec = row_vec_width(rs.base, rs.ld);
     const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
@@ -288,14 +309,14 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
     if (grid > chunks) grid = (int)chunks;
     *grid_out = grid;
     switch (rs.count) {
-    case 1: return launch_small<1>(rs, pp, grid, vec, run_if, s);
-    case 2: return launch_small<2>(rs, pp, grid, vec, run_if, s);
-    case 3: return launch_small<3>(rs, pp, grid, vec, run_if, s);
-    case 4: return launch_small<4>(rs, pp, grid, vec, run_if, s);
-    case 5: return launch_small<5>(rs, pp, grid, vec, run_if, s);
-    case 6: return launch_small<6>(rs, pp, grid, vec, run_if, s);
-    case 7: return launch_small<7>(rs, pp, grid, vec, run_if, s);
-    case 8: return launch_small<8>(rs, pp, grid, vec, run_if, s);
+    case 1: return launch_small<1>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 2: return launch_small<2>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 3: return launch_small<3>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 4: return launch_small<4>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 5: return launch_small<5>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 6: return launch_small<6>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 7: return launch_small<7>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 8: return launch_small<8>(rs, pp, grid, vec, run_if, tail, arrived, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -331,7 +352,7 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
     if (count <= 8) {
         double *pp = static_cast<double *>(partials);
         int grid = 0;
-        e = launch_small_any(rs, pp, nullptr, &grid, s);
+        e = launch_small_any(rs, pp, nullptr, &grid, SmallSelect{}, nullptr, s);
         if (e != hipSuccess) return e;
         const int np = (int)(count * (count + 1) / 2);
         TraceScope t("gram_reduce", s);
@@ -373,28 +394,17 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
     return hipGetLastError();
 }
 
-namespace {
-__global__ __launch_bounds__(kPostThreads) void small_redo_kernel(SmallSelect q, const int *run_if)
-{
-    if (*run_if == 0) return;   // uniform
-    __shared__ double Gl[kSmallCount * kSmallCount];
-    small_gram_reduce(q, small_gram_load(q), Gl);
-    if (q.krum_m > 0) small_multikrum(q, Gl);
-}
-}  // namespace
-
 hipError_t launch_small_redo(const RowSet &rs, void *partials, const int *redo, double *Gm, int krum_f,
                              int krum_m, double *scores, int32_t *selected, hipStream_t s)
 {
     if (rs.count < 1 || rs.count > kSmallCount) return hipErrorInvalidValue;
     double *pp = static_cast<double *>(partials);
     int grid = 0;
-    hipError_t e = launch_small_any(rs, pp, redo, &grid, s);   // runs only if *redo
-    if (e != hipSuccess) return e;
-    SmallSelect q{pp, grid, rs.count * (rs.count + 1) / 2, 1, rs.count, Gm, krum_f, krum_m, scores, selected};
-    TraceScope t("select_if_redo", s);
-    small_redo_kernel<<<1, kPostThreads, 0, s>>>(q, redo);
-    return hipGetLastError();
+    // one launch that does nothing unless *redo; the word after the flag counts its workgroups
+    // (the finalize kernel of the filter pass leaves it at zero)
+    SmallSelect q{nullptr, 0, 0, 0, rs.count, Gm, krum_f, krum_m, scores, selected};
+    unsigned *arrived = reinterpret_cast<unsigned *>(const_cast<int *>(redo)) + 1;
+    return launch_small_any(rs, pp, redo, &grid, q, arrived, s);
 }
 
 }  // namespace detox

@@ -22,16 +22,16 @@ struct SmallSelect {
     int32_t *selected;             // dev, krum_m
 };
 
-// Gm[a][b] (LDS and global) = sum over the workgroup slots, in a fixed order: thread t adds slots
-// t, t+blockDim, ...; lanes are combined by the fixed wavefront butterfly; wavefronts in order.
-// Needs blockDim.x == kPostThreads.  Ends with a barrier.
+// Gm[a][b] (LDS and global) = sum over the workgroup slots, in a fixed order, by a workgroup of
+// THREADS threads (blockDim.x == THREADS).
 // First half (no barrier): thread (pair p, slice k) adds the slots of its slice in slot order.
 // Can be issued early so that the loads overlap other work.
+template <int THREADS = kPostThreads>
 __device__ inline double small_gram_load(const SmallSelect &q)
 {
     if (q.gram_partials == nullptr) return 0.0;
     const int np = q.count * (q.count + 1) / 2;
-    const int slices = kPostThreads / np;
+    const int slices = THREADS / np;
     const int p = threadIdx.x / slices, k = threadIdx.x % slices;
     if (p >= np) return 0.0;
     const int per = (q.gram_blocks + slices - 1) / slices;
@@ -44,13 +44,14 @@ __device__ inline double small_gram_load(const SmallSelect &q)
 }
 
 // Second half: the slice sums of every pair are added in slice order; Gm goes to LDS and to
-// global memory.  Needs blockDim.x == kPostThreads.  Ends with a barrier.
+// global memory.  Ends with a barrier.
+template <int THREADS = kPostThreads>
 __device__ inline void small_gram_reduce(const SmallSelect &q, double mine,
                                          double (&Gl)[kSmallCount * kSmallCount])
 {
-    __shared__ double red[kPostThreads];
+    __shared__ double red[THREADS];
     const int np = q.count * (q.count + 1) / 2;
-    const int slices = kPostThreads / np;
+    const int slices = THREADS / np;
     red[threadIdx.x] = mine;
     __syncthreads();
     if ((int)threadIdx.x < np) {
