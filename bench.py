@@ -258,15 +258,18 @@ def main():
         import oracle
 
         Gh = w.matrix()
-        t1 = time.perf_counter()
         okw = {k: v for k, v in spec.items() if k not in ("B", "aggregator")}
-        ref_out, ref_w, _ = oracle.detox_step(Gh, r, B, agg, **okw)
-        t_cpu = time.perf_counter() - t1
+        ref_out, ref_w, _ = oracle.detox_step(Gh, r, B, agg, **okw)      # untimed: pages in, threads up
+        reps, t1 = 0, time.perf_counter()
+        while reps < 50 and (reps < 3 or time.perf_counter() - t1 < 10.0):
+            ref_out, ref_w, _ = oracle.detox_step(Gh, r, B, agg, **okw)
+            reps += 1
+        t_cpu = (time.perf_counter() - t1) / reps
         got = buf.out.cpu().numpy().astype(np.float64)
         err = float(np.linalg.norm(got - ref_out) / max(np.linalg.norm(ref_out), 1e-300))
         same_w = buf.winner.cpu().numpy().tolist() == ref_w.tolist()
         cpu = {"value": round(in_bytes / t_cpu / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": f"the full workload ({n} x {d}), one repetition of the DETOX step",
+               "kind": "oracle", "sample": f"the full workload ({n} x {d}), mean of {reps} repetitions of the DETOX step",
                "ms_per_step": round(t_cpu * 1e3, 2), "gpu_matches_oracle": bool(same_w and err <= 1e-5),
                "rel_l2_vs_oracle": err}
         log(f"[bench] CPU oracle: {t_cpu * 1e3:.1f} ms on {cpu['cores']} threads; GPU rel-L2 vs oracle {err:.2e}, "
