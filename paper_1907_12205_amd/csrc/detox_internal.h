@@ -145,8 +145,9 @@ size_t gram_partial_bytes(int64_t count);
 // Gram matrix Gm[a][b] = <x_a, x_b> of the logical rows (count x count doubles, full, symmetric).
 hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s);
 // count <= 8, the finalize kernel has produced Gm (and the Multi-Krum selection when krum_m > 0)
-// unless *redo: two kernels that do nothing unless *redo recompute the Gram matrix from the rows
-// and repeat the reduction (and the selection).
+// unless *redo: one kernel that does nothing unless *redo recomputes the Gram matrix from the
+// rows; its last-finishing workgroup repeats the reduction (and the selection).  redo[1] counts
+// the workgroups that have arrived and must be zero at launch (the finalize kernel clears it).
 hipError_t launch_small_redo(const RowSet &rs, void *partials, const int *redo, double *Gm, int krum_f,
                              int krum_m, double *scores, int32_t *selected, hipStream_t s);
 

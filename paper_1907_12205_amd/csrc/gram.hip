@@ -6,7 +6,9 @@
 //   count  > 8 : fp32 MFMA 16x16x4 tiles (upper triangle of the tile grid), one accumulator set
 //                per wavefront over a strided share of the columns.
 // Either way every workgroup / wavefront writes its partial sums to the workspace and a second
-// kernel adds them in a fixed order in fp64.  No atomics: results repeat bit for bit, and rows
+// kernel (or, in the conditional repeat of a small Gram matrix, the workgroup that an integer
+// counter shows to be the last) adds them in a fixed order in fp64.  No floating-point atomics:
+// results repeat bit for bit, and rows
 // that are bit-identical produce bit-identical Gram entries (same products, same order).
 #include "rows.cuh"
 #include "small_select.cuh"
