@@ -17,62 +17,91 @@ namespace {
 
 constexpr int kGroupsPerBlock = kBlock / kWave;
 
+constexpr int kGroupsPerWave = 1;   // node groups per wavefront (two at once measured slower: 21.3 vs 19.6 us)
+
 template <int R>
 __global__ __launch_bounds__(kBlock) void filter_rows_kernel(const uint32_t *G, int64_t d, int64_t ld,
                                                              const int32_t *group_rows,
                                                              int64_t n_votes, int32_t *winner)
 {
+    constexpr int GP = kGroupsPerWave;
     const int lane = threadIdx.x & (kWave - 1);
     // the wavefront index is uniform: say so, and the row table below lives in scalar registers
-    const int64_t j = (int64_t)blockIdx.x * kGroupsPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (j >= n_votes) return;   // whole wavefronts leave together
-    int64_t row[R];
+    const int64_t wave = (int64_t)blockIdx.x * kGroupsPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t j0 = wave * GP;
+    if (j0 >= n_votes) return;   // whole wavefronts leave together
+    // a group beyond the end repeats the last one (valid addresses) and is not written
+    int64_t row[GP][R];
 #pragma unroll
-    for (int k = 0; k < R; ++k) row[k] = group_rows ? group_rows[j * R + k] : j * R + k;
+    for (int g = 0; g < GP; ++g) {
+        const int64_t j = j0 + g < n_votes ? j0 + g : n_votes - 1;
+#pragma unroll
+        for (int k = 0; k < R; ++k) row[g][k] = group_rows ? group_rows[j * R + k] : j * R + k;
+    }
 
     // bits: pair (a, b) differs somewhere in the row.  Each lane compares its two columns as one
     // 64-bit word; the per-pair test over the wavefront is a scalar compare of the lane mask, so
     // `bits` lives in scalar registers and costs the vector unit one compare per pair.
-    unsigned long long bits = 0ull;
+    unsigned long long bits[GP];
+#pragma unroll
+    for (int g = 0; g < GP; ++g) bits[g] = 0ull;
     for (int64_t c0 = 0; c0 < d; c0 += 2 * kWave) {
         // two columns per lane and trip; a column beyond d re-reads column d-1 (always a valid
         // address; both members of a pair read the same column, so it cannot add a difference
         // that is not there), which keeps the loads free of branches
-        unsigned long long x[R];
         const int64_t ca = c0 + lane, cb = c0 + kWave + lane;
         const int64_t cca = ca < d ? ca : d - 1, ccb = cb < d ? cb : d - 1;
+        uint32_t xa[GP][R], xb[GP][R];
 #pragma unroll
-        for (int k = 0; k < R; ++k) {
-            const uint32_t *row_k = G + row[k] * ld;   // rows share cache lines: cached loads
-            x[k] = (unsigned long long)row_k[cca] | ((unsigned long long)row_k[ccb] << 32);
+        for (int g = 0; g < GP; ++g)
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                const uint32_t *row_k = G + row[g][k] * ld;   // rows share cache lines: cached loads
+                xa[g][k] = row_k[cca];
+                xb[g][k] = row_k[ccb];
+            }
+        // every load is in flight before the first value is looked at
+#pragma unroll
+        for (int g = 0; g < GP; ++g)
+#pragma unroll
+            for (int k = 0; k < R; ++k) asm volatile("" : "+v"(xa[g][k]), "+v"(xb[g][k]));
+#pragma unroll
+        for (int g = 0; g < GP; ++g) {
+            unsigned long long x[R];
+#pragma unroll
+            for (int k = 0; k < R; ++k)
+                x[k] = (unsigned long long)xa[g][k] | ((unsigned long long)xb[g][k] << 32);
+            int pair = 0;
+#pragma unroll
+            for (int a = 0; a < R; ++a)
+#pragma unroll
+                for (int b = a + 1; b < R; ++b, ++pair)
+                    if (__any(x[a] != x[b])) bits[g] |= 1ull << pair;
         }
-        int pair = 0;
-#pragma unroll
-        for (int a = 0; a < R; ++a)
-#pragma unroll
-            for (int b = a + 1; b < R; ++b, ++pair)
-                if (__any(x[a] != x[b])) bits |= 1ull << pair;
     }
 
     // Lane a < R looks at member a: how many members hold its value, and their lowest row index.
     // The first member whose value is held by more than R/2 names the winner.
     const int a = lane < R ? lane : 0;
-    int votes = 0;
-    int64_t lowest = INT64_MAX;
 #pragma unroll
-    for (int b = 0; b < R; ++b) {
-        const int lo = a < b ? a : b, hi = a < b ? b : a;
-        const int pair = lo * R - lo * (lo + 1) / 2 + (hi - lo - 1);
-        const bool same = a == b || ((bits >> pair) & 1ull) == 0ull;
-        if (same) {
-            ++votes;
-            lowest = row[b] < lowest ? row[b] : lowest;
+    for (int g = 0; g < GP; ++g) {
+        int votes = 0;
+        int64_t lowest = INT64_MAX;
+#pragma unroll
+        for (int b = 0; b < R; ++b) {
+            const int lo = a < b ? a : b, hi = a < b ? b : a;
+            const int pair = lo * R - lo * (lo + 1) / 2 + (hi - lo - 1);
+            const bool same = a == b || ((bits[g] >> pair) & 1ull) == 0ull;
+            if (same) {
+                ++votes;
+                lowest = row[g][b] < lowest ? row[g][b] : lowest;
+            }
         }
+        const unsigned long long has = __ballot(lane < R && 2 * votes > R);
+        int32_t win = -1;
+        if (has != 0ull) win = (int32_t)__shfl(lowest, __ffsll((long long)has) - 1, kWave);
+        if (lane == 0 && j0 + g < n_votes) winner[j0 + g] = win;
     }
-    const unsigned long long has = __ballot(lane < R && 2 * votes > R);
-    int32_t win = -1;
-    if (has != 0ull) win = (int32_t)__shfl(lowest, __ffsll((long long)has) - 1, kWave);
-    if (lane == 0) winner[j] = win;
 }
 
 constexpr int kBmThreads = 512;                 // 8 wavefronts fetch, the first one adds
@@ -135,7 +164,8 @@ hipError_t launch_filter_rows(const FilterParams &p, bool means, hipStream_t s)
 {
     {
         TraceScope t("filter_rows", s);
-        const unsigned grid = (unsigned)((p.n_votes + kGroupsPerBlock - 1) / kGroupsPerBlock);
+        const int64_t waves = (p.n_votes + kGroupsPerWave - 1) / kGroupsPerWave;
+        const unsigned grid = (unsigned)((waves + kGroupsPerBlock - 1) / kGroupsPerBlock);
         const uint32_t *G = reinterpret_cast<const uint32_t *>(p.G);
         switch (p.r) {
 #define DETOX_ROWS_CASE(R)                                                                         \
