@@ -12,7 +12,7 @@
 //   geometric median       : Weiszfeld's iteration streamed over the rows, one launch per
 //                            iteration (weiszfeld_rows_kernel).  16 lanes share a row; weights,
 //                            distances and sums are fp64; every reduction runs in a fixed order.
-#include "detox_internal.h"
+#include "rows.cuh"
 
 namespace detox {
 namespace {
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kSelThreads) void radix_finish_kernel(SelPlan p, fl
 
 // ---- streaming Weiszfeld ------------------------------------------------------------------
 constexpr int kWzThreads = 1024;
-constexpr int kWzLanes = 16;                          // lanes that share a row
+constexpr int kWzLanes = 16;                          // lanes that share a row (row16_sum adds over exactly these)
 constexpr int kWzGroups = kWzThreads / kWzLanes;      // rows a workgroup has in flight
 constexpr int kWzMaxD = kManyGeomedianMaxD;
 constexpr int kWzStride = kWzMaxD + 1;                // doubles per partial: sums, then the weight sum
@@ -426,8 +426,7 @@ __global__ __launch_bounds__(kWzThreads) void weiszfeld_rows_kernel(
                     const double diff = x[k] - v[u][k];
                     s = fma(diff, diff, s);
                 }
-#pragma unroll
-                for (int off = kWzLanes / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWzLanes);
+                s = row16_sum(s);   // the 16 lanes of a row are one aligned group: no LDS traffic
                 // 1 / max(sqrt(s), eps) without a square root followed by a division
                 w = s > eps * eps ? rsqrt(s) : inv_eps;
             }

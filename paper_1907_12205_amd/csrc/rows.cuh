@@ -117,4 +117,39 @@ __device__ inline double wave_sum_fixed(double v)
     return v;
 }
 
+// v + (the value of v in the lane the data-parallel-primitive pattern CTRL pairs this lane with).
+template <int CTRL>
+__device__ inline double add_paired_lane(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return v + __hiloint2double(hi, lo);
+}
+
+// Sum over each aligned group of 16 lanes (a "row" of the wavefront), the same bits in all 16.
+__device__ inline double row16_sum(double v)
+{
+    v = add_paired_lane<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = add_paired_lane<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = add_paired_lane<0x141>(v);   // row_half_mirror
+    return add_paired_lane<0x140>(v);   // row_mirror
+}
+
+// Sum over the 64 lanes of a wavefront, the same bits in every lane: lane pairs, quads, halves of
+// a row of 16 (mirror inside 8), rows (mirror inside 16), then the four row sums in a fixed order.
+// All 64 lanes must be active.  No LDS traffic, unlike a shuffle.
+__device__ inline double wave_sum(double v)
+{
+    v = add_paired_lane<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = add_paired_lane<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = add_paired_lane<0x141>(v);   // row_half_mirror
+    v = add_paired_lane<0x140>(v);   // row_mirror
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    double row[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        row[q] = __hiloint2double(__builtin_amdgcn_readlane(hi, 16 * q), __builtin_amdgcn_readlane(lo, 16 * q));
+    return (row[0] + row[1]) + (row[2] + row[3]);
+}
+
 }  // namespace detox
