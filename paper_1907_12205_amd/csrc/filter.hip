@@ -27,18 +27,29 @@ namespace {
 
 // Loads the R member rows of node group j at this thread's columns (zeros where invalid) and
 // returns the pairs that differ anywhere in the wavefront's columns (a uniform value).
+//   full (uniform): every thread of the workgroup has all VEC columns inside d.  Then the R loads
+//   carry no per-thread condition and are issued back to back; with a condition around each the
+//   compiler waits for every load before it issues the next.
 template <int R, int VEC>
 __device__ inline unsigned long long load_group(const FilterParams &p, int64_t j, int64_t col,
-                                                int valid, uint32_t (&x)[R][VEC])
+                                                int valid, bool full, uint32_t (&x)[R][VEC])
 {
+    if (full) {
+        int64_t row[R];
 #pragma unroll
-    for (int k = 0; k < R; ++k) {
-        const int64_t row = p.group_rows ? p.group_rows[j * R + k] : j * R + k;
-        if (valid > 0) {
-            load_words<VEC>(p.G + row * p.ld + col, valid, x[k]);
-        } else {
+        for (int k = 0; k < R; ++k) row[k] = p.group_rows ? p.group_rows[j * R + k] : j * R + k;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) x[k][i] = 0u;
+        for (int k = 0; k < R; ++k) load_words<VEC>(p.G + row[k] * p.ld + col, VEC, x[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const int64_t row = p.group_rows ? p.group_rows[j * R + k] : j * R + k;
+            if (valid > 0) {
+                load_words<VEC>(p.G + row * p.ld + col, valid, x[k]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) x[k][i] = 0u;
+            }
         }
     }
     // per-thread pair bits first (pure vector work), then one wavefront-wide test; the
@@ -148,6 +159,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
         const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
         const int64_t left = p.d - col;
         const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+        const bool full = (chunk + 1) * kBlock * VEC <= p.d;   // uniform
         // one vote group: votes, pair bits, and (MEAN) its mean
         auto do_block = [&](int64_t b, float (&acc)[VEC]) {
             const int64_t lo = (b * p.n_votes) / B, hi = ((b + 1) * p.n_votes) / B;
@@ -156,7 +168,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
             for (int64_t pos = lo; pos < hi; ++pos) {
                 const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
                 uint32_t x[R][VEC];
-                const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, x);
+                const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, full, x);
                 if (wave_bits != 0ull && lane == 0) atomicOr(&sbits[j], wave_bits);   // LDS, integer
                 if constexpr (MEAN) {
                     float v[VEC];
@@ -300,6 +312,7 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(FilterParams p)
     const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
     const int64_t left = p.d - col;
     const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+    const bool full = ((int64_t)blockIdx.x + 1) * kBlock * VEC <= p.d;   // uniform
     const int lane = threadIdx.x & (kWave - 1);
 
     float acc[VEC];
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(FilterParams p)
     for (int64_t pos = lo; pos < hi; ++pos) {
         const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
         uint32_t x[R][VEC];
-        const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, x);
+        const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, full, x);
         if (wave_bits != 0ull && lane == 0) {
             // one conditional atomic per wavefront; skipped once the bits are known
             const unsigned long long seen = __atomic_load_n(&p.flags[j], __ATOMIC_RELAXED);
