@@ -207,7 +207,8 @@ int robust_geomedian_many(const float *X, int64_t count, int64_t d, int64_t ld, 
 /* The whole parameter-server step: filter -> B block means -> aggregator, with one pass over
  * G.  The pass that votes also forms the block means; for B <= 8 it accumulates their Gram
  * matrix (Multi-Krum, Bulyan, geometric median) or takes their coordinate-wise median on the
- * fly.  If Zhat is NULL the block means are never written: kernels that need them later
+ * fly; with B = n/r between 9 and 16 (every vote its own block, e.g. Bulyan over 15 votes) and
+ * Zhat NULL it forms the Gram matrix of the votes on the matrix cores during the same pass.  If Zhat is NULL the block means are never written: kernels that need them later
  * (averaging the selected means, Bulyan's trimming, the Weiszfeld combination) re-form them from
  * the winner rows of G, with the same arithmetic and bit-identical values.  That is the faster
  * mode; pass Zhat only if the means themselves are wanted.

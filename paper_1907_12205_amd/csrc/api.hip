@@ -45,6 +45,12 @@ struct Carver {
 
 size_t filter_bytes(int64_t groups) { return round_up(filter_ws_bytes(groups)); }
 
+// Tiles the filter pass writes when it forms the Gram matrix of 9..16 votes on the side.
+size_t pass_gram_bytes(int64_t count)
+{
+    return count > 8 && count <= kPassGramMaxVotes ? (size_t)kPassGramMaxWaves * 256 * sizeof(float) : 0;
+}
+
 // Gram partials + Gram matrix + the count x count scratch of the selection kernels.
 size_t aggregator_ws_bytes(int64_t count)
 {
@@ -52,7 +58,7 @@ size_t aggregator_ws_bytes(int64_t count)
     const size_t c2 = (size_t)(count * count);
     return round_up(gram_partial_bytes(count)) + round_up(c2 * sizeof(double)) * 3 +
            round_up(c2 * sizeof(int32_t)) + round_up((size_t)count * sizeof(double)) * 2 +
-           round_up((size_t)count * sizeof(int32_t)) * 2;
+           round_up((size_t)count * sizeof(int32_t)) * 2 + round_up(pass_gram_bytes(count));
 }
 
 struct AggWs {
@@ -61,6 +67,7 @@ struct AggWs {
     SelectScratch sc;
     int32_t *row_index;   // count entries: row table of a vote row set
     int32_t *trim_rows;   // count entries: physical rows of Bulyan's selected votes
+    float *pass_gram;     // tiles of the filter pass (9..16 rows), else null
 };
 
 AggWs carve_aggregator(void *ws, int64_t count)
@@ -77,6 +84,7 @@ AggWs carve_aggregator(void *ws, int64_t count)
     a.sc.weights = c.take<double>((size_t)count);
     a.row_index = c.take<int32_t>((size_t)count);
     a.trim_rows = c.take<int32_t>((size_t)count);
+    a.pass_gram = pass_gram_bytes(count) ? c.take<float>(pass_gram_bytes(count) / sizeof(float)) : nullptr;
     return a;
 }
 
@@ -97,12 +105,15 @@ struct FusedGram {
     int blocks = 0;
     const int *redo = nullptr;
     bool reduced = false;   // Gm (and the Multi-Krum selection) already produced unless *redo
+    int vote_waves = 0;     // > 0: MFMA tiles of the votes' Gram matrix in AggWs::pass_gram (unless *redo)
 };
 
 hipError_t gram_for(const RowSet &rs, const AggWs &a, const FusedGram &fg, hipStream_t s)
 {
     if (fg.reduced)
         return launch_small_redo(rs, a.partials, fg.redo, a.Gm, 0, 0, a.sc.scores, nullptr, s);
+    if (fg.vote_waves > 0)
+        return launch_gram_after_pass(rs, a.partials, a.pass_gram, fg.vote_waves, fg.redo, a.Gm, s);
     return launch_gram(rs, a.partials, a.Gm, s);
 }
 
@@ -398,17 +409,21 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
+    void *aws = static_cast<char *>(ws) + fbytes;
+    const AggWs aw = carve_aggregator(aws, B);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, out, agg == DETOX_AGG_TRIMMED_MEAN ? f : 0};
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, out,
+                   agg == DETOX_AGG_TRIMMED_MEAN ? f : 0, aw.pass_gram};
     // One pass over G.  With Zhat the block means are also written out; without it they exist
     // only in registers during this pass and are re-formed from the winners where a later
     // kernel needs them (that is the faster way on this chip).
     FilterWant want = agg == DETOX_AGG_COORD_MEDIAN ? FilterWant::kMedian
                       : (agg == DETOX_AGG_TRIMMED_MEAN ? FilterWant::kTrimmed : FilterWant::kGram);
-    if (Zhat == nullptr && (B > 8 || groups > kFusedMaxVotes)) want = FilterWant::kVotes;   // B = n/r
+    if (Zhat == nullptr && (B > 8 || groups > kFusedMaxVotes)) {   // B = n/r: the rows are the votes
+        const bool gram_based = agg == DETOX_AGG_MULTIKRUM || agg == DETOX_AGG_BULYAN || agg == DETOX_AGG_GEOMEDIAN;
+        want = gram_based && aw.pass_gram != nullptr ? FilterWant::kVotesGram : FilterWant::kVotes;
+    }
     FilterDone done;
-    void *aws = static_cast<char *>(ws) + fbytes;
-    const AggWs aw = carve_aggregator(aws, B);
     // what the finalize kernel can do on the side when the Gram matrix comes with the pass
     SmallSelect tail{nullptr, 0, 0, 0, (int)B, aw.Gm, f, agg == DETOX_AGG_MULTIKRUM ? m : 0, aw.sc.scores, selected};
     hipError_t e = launch_filter(p, want, &tail, &done, s);
@@ -439,6 +454,7 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     fg.blocks = done.gram_blocks;
     fg.redo = fw.redo;
     fg.reduced = done.gram_reduced;
+    fg.vote_waves = done.vote_gram_waves;
     switch (agg) {
     case DETOX_AGG_MULTIKRUM: return multikrum_impl(rs, f, m, out, selected, nullptr, aws, fg, s);
     case DETOX_AGG_BULYAN: return bulyan_impl(rs, f, out, selected, aws, fg, s);

@@ -13,6 +13,8 @@ constexpr int kMaxR = 11;              // node-group size limit (pair flags fit 
 constexpr int kMaxCount = 128;         // rows per robust aggregation
 constexpr int kFusedMaxVotes = 1024;   // node groups the persistent filter kernel handles
 constexpr int kFusedMaxGrid = 2048;    // its largest grid (sizes the per-workgroup slots)
+constexpr int kPassGramMaxVotes = 16;  // votes whose Gram matrix the filter pass can form on the side
+constexpr int kPassGramMaxWaves = 4096;  // wavefront tiles it may write (sizes the workspace)
 constexpr int kRowParMaxD = 2048;      // widest rows the row-parallel filter / block mean take
 constexpr int kManyGeomedianMaxD = 128;       // widest rows of the streaming Weiszfeld kernels
 constexpr int kManyGeomedianMaxParts = 1024;  // most workgroups (partial sums) of one of its launches
@@ -85,6 +87,7 @@ struct FilterParams {
     int32_t *winner;                    // dev, n_votes
     float *out;                         // dev, d: coordinate-wise median / trimmed mean (those modes)
     int trim_g;                         // trimmed-mean mode: values dropped at each end
+    float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats (kVotesGram)
 };
 struct FilterWs {
     int *redo;
@@ -96,6 +99,8 @@ FilterWs carve_filter_ws(void *ws, int64_t n_votes);
 // What one pass over G should produce besides winner[] and *redo.
 enum class FilterWant {
     kVotes,    // nothing else
+    kVotesGram,  // every vote its own block (B = n_votes <= kPassGramMaxVotes): the Gram matrix of the
+               //   votes as per-wavefront MFMA tiles in vote_gram_partials; degrades to kVotes
     kMeans,    // block means in Zhat (must be non-null)
     kGram,     // block means (in Zhat if non-null) and, when B <= 8, the Gram matrix of the means
     kMedian,   // block means (in Zhat if non-null) and, when B <= 8, their coordinate-wise median
@@ -108,6 +113,8 @@ struct FilterDone {
     bool gram_reduced = false;    // the finalize kernel already produced Gm (and, if asked, the
                                   //   Multi-Krum selection) unless *redo
     bool median_written = false;  // kMedian / kTrimmed honoured: `out` holds the result unless *redo
+    int vote_gram_waves = 0;      // > 0: kVotesGram honoured, that many wavefront tiles written (valid
+                                  //   unless *redo)
 };
 struct SmallSelect;               // small_select.cuh: what the finalize kernel should go on to do
 // kGram / kMedian with B > 8 (or more than kFusedMaxVotes groups) degrade to kMeans; then Zhat
@@ -144,6 +151,11 @@ hipError_t launch_many_geomedian(const float *X, int64_t count, int64_t d, int64
 size_t gram_partial_bytes(int64_t count);
 // Gram matrix Gm[a][b] = <x_a, x_b> of the logical rows (count x count doubles, full, symmetric).
 hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s);
+// count <= 16 rows whose Gram tiles the filter pass has written (pass_waves wavefront tiles in
+// pass_partials, valid unless *redo): adds them up into Gm; if *redo, the matrix is first formed
+// again from the rows (one more launch, which does nothing otherwise).
+hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float *pass_partials,
+                                  int pass_waves, const int *redo, double *Gm, hipStream_t s);
 // count <= 8, the finalize kernel has produced Gm (and the Multi-Krum selection when krum_m > 0)
 // unless *redo: one kernel that does nothing unless *redo recomputes the Gram matrix from the
 // rows; its last-finishing workgroup repeats the reduction (and the selection).  redo[1] counts

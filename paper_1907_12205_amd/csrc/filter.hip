@@ -25,6 +25,8 @@
 namespace detox {
 namespace {
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
 // Loads the R member rows of node group j at this thread's columns (zeros where invalid) and
 // returns the pairs that differ anywhere in the wavefront's columns (a uniform value).
 //   full (uniform): every thread of the workgroup has all VEC columns inside d.  Then the R loads
@@ -133,18 +135,30 @@ __device__ inline int32_t winner_from_bits(unsigned long long bits, const int32_
 //   kMedian     : + block means kept in registers (NB = B <= 8), their coordinate-wise median
 //                 written to `out` (the whole DETOX-median step in one pass over G); Zhat
 //                 written only if non-null.
+//   kVotesGram  : every vote its own block, at most 16 votes (VEC = 4 only): + the Gram matrix
+//                 of the votes on the matrix cores.  Each lane holds the per-coordinate majority
+//                 values of all votes for its four columns; they go through a small LDS tile
+//                 (16 rows x 64 columns per wavefront, one column component at a time) into the
+//                 operand layout of V_MFMA_F32_16X16X4_F32 (lane l: row l%16, summation index
+//                 l/16), and every wavefront leaves its 16x16 fp32 accumulator tile in
+//                 vote_gram_partials in the layout of the stand-alone Gram kernel.
 // ---------------------------------------------------------------------------------------
-enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3, kTrimmedMean = 4 };
+enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3, kTrimmedMean = 4, kVotesGram = 5 };
 
 template <int R, int VEC, int NB, int MODE>
 __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
 {
-    constexpr bool MEAN = MODE != kFilterOnly;
+    constexpr bool MEAN = MODE != kFilterOnly && MODE != kVotesGram;
     constexpr bool REGS = MODE == kGram || MODE == kMedian || MODE == kTrimmedMean;   // means of all blocks in registers
     constexpr int NP = MODE == kGram ? NB * (NB + 1) / 2 : 1;
     static_assert(!REGS || NB > 0, "register modes need the block count at compile time");
     __shared__ unsigned long long sbits[kFusedMaxVotes];
     __shared__ double red[kBlock / kWave][NP];
+    // kVotesGram: rows 68 floats apart, so that the 16-byte reads of a quarter wavefront (16 rows,
+    // one column group) spread over the banks
+    constexpr int kTileLd = 68;
+    __shared__ __attribute__((aligned(16))) float vtile[MODE == kVotesGram ? kBlock / kWave : 1][16][kTileLd];
+    [[maybe_unused]] f32x4_t macc = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock) sbits[j] = 0ull;
     __syncthreads();
 
@@ -185,6 +199,41 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
                     store_floats<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
             }
         };
+        if constexpr (MODE == kVotesGram) {
+            static_assert(MODE != kVotesGram || VEC == 4, "the tile feed is written for four columns per lane");
+            float v[kPassGramMaxVotes][VEC];
+#pragma unroll
+            for (int pos = 0; pos < kPassGramMaxVotes; ++pos) {
+                if (pos < p.n_votes) {   // uniform
+                    const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
+                    uint32_t x[R][VEC];
+                    const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, full, x);
+                    if (wave_bits != 0ull && lane == 0) atomicOr(&sbits[j], wave_bits);   // LDS, integer
+                    majority_values<R, VEC>(x, v[pos]);   // columns beyond d were loaded as zeros
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) v[pos][i] = 0.0f;
+                }
+            }
+            // The tile is private to the wavefront, whose LDS instructions execute in order: the
+            // writes of one component are seen by the reads that follow, and those are done
+            // before the next component is written.
+            const int wv = threadIdx.x / kWave, ti = lane & 15, tk = lane >> 4;
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) {
+#pragma unroll
+                for (int pos = 0; pos < kPassGramMaxVotes; ++pos) vtile[wv][pos][lane] = v[pos][q];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float4 a = *reinterpret_cast<const float4 *>(&vtile[wv][ti][16 * u + 4 * tk]);
+                    macc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, a.x, macc, 0, 0, 0);
+                    macc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, a.y, macc, 0, 0, 0);
+                    macc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, a.z, macc, 0, 0, 0);
+                    macc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, a.w, macc, 0, 0, 0);
+                }
+            }
+            continue;
+        }
         float z[REGS ? NB : 1][VEC];
         if constexpr (REGS) {
 #pragma unroll
@@ -239,6 +288,12 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
     __syncthreads();
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock)
         p.flag_partials[(int64_t)blockIdx.x * p.n_votes + j] = sbits[j];
+    if constexpr (MODE == kVotesGram) {
+        // C[4*(l/16)+v][l%16] in component v of lane l, as the stand-alone Gram kernel stores it
+        float *tile_out = p.vote_gram_partials + ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * 256;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) tile_out[v * 64 + lane] = macc[v];
+    }
     if constexpr (MODE == kGram) {
         const int wave = threadIdx.x / kWave;
 #pragma unroll
@@ -445,6 +500,12 @@ template <int R, int VEC, int NB>
 hipError_t launch_fused_rvn(const FilterParams &p, int mode, int *grid, int64_t chunks, hipStream_t s)
 {
     if constexpr (NB == 0) {
+        if (mode == kVotesGram) {
+            if constexpr (VEC == 4)
+                return launch_fused_mode<R, VEC, 0, kVotesGram>(p, "filter_votes_gram", grid, chunks, s);
+            else
+                return hipErrorInvalidValue;
+        }
         if (mode == kMeans)
             return launch_fused_mode<R, VEC, 0, kMeans>(p, "filter_block_mean", grid, chunks, s);
         return launch_fused_mode<R, VEC, 0, kFilterOnly>(p, "filter", grid, chunks, s);
@@ -564,7 +625,7 @@ FilterWs carve_filter_ws(void *ws, int64_t n_votes)
 hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tail, FilterDone *done,
                          hipStream_t s)
 {
-    const bool mean = want != FilterWant::kVotes;
+    const bool mean = want != FilterWant::kVotes && want != FilterWant::kVotesGram;
     if (row_parallel(p.d, p.n_votes)) {
         if (mean && p.Zhat == nullptr) return hipErrorInvalidValue;
         if (done) {
@@ -587,7 +648,11 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
     // few vote groups.  A pure filter is the same kernel with every group its own block.
     const bool fused = p.n_votes <= kFusedMaxVotes;
     int mode = kFilterOnly, nb = 0;
-    if (mean) {
+    const bool votes_gram = want == FilterWant::kVotesGram && fused && p.B == p.n_votes &&
+                            p.n_votes <= kPassGramMaxVotes && vec == 4 && p.vote_gram_partials != nullptr;
+    if (want == FilterWant::kVotesGram) {
+        if (votes_gram) mode = kVotesGram;
+    } else if (mean) {
         mode = kMeans;
         if (fused && p.B <= 8 && want == FilterWant::kGram) mode = kGram, nb = (int)p.B;
         if (fused && p.B <= 8 && want == FilterWant::kMedian) mode = kMedian, nb = (int)p.B;
@@ -600,6 +665,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
     int grid = 0;
     if (fused) {
         grid = num_compute_units() * (p.n_votes <= 128 ? 4 : 2);   // wanted; trimmed to what is resident
+        if (votes_gram && grid * (kBlock / kWave) > kPassGramMaxWaves) grid = kPassGramMaxWaves / (kBlock / kWave);
     } else {
         // the redo word (first 256 bytes of the workspace) and the flag words that follow it
         TraceScope t("fill_flags", s);
@@ -641,6 +707,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
             done->gram_blocks = mode == kGram ? grid : 0;
             done->gram_reduced = mode == kGram && tail != nullptr;
             done->median_written = mode == kMedian || mode == kTrimmedMean;
+            done->vote_gram_waves = mode == kVotesGram ? grid * (kBlock / kWave) : 0;
         }
     } else {
         filter_finalize_kernel<<<(unsigned)((p.n_votes + 255) / 256), 256, 0, s>>>(

@@ -189,8 +189,10 @@ __device__ inline void gram_mfma_step(const float4 (&buf)[T][2], f32x4 (&acc)[ti
 }
 
 template <int T, bool ALIGNED>
-__global__ __launch_bounds__(kBlock) void gram_mfma_kernel(RowSet rs, float *partials)
+__global__ __launch_bounds__(kBlock) void gram_mfma_kernel(RowSet rs, float *partials,
+                                                           const int *run_if)
 {
+    if (run_if && *run_if == 0) return;   // uniform
     const int count = rs.count;
     const int64_t d = rs.d;
     constexpr int NT = tiles_for(T);
@@ -244,11 +246,15 @@ __global__ __launch_bounds__(kBlock) void gram_mfma_kernel(RowSet rs, float *par
 // load is coalesced), then the slice sums are added in slice order and scattered into the matrix.
 constexpr int kReduceSlices = 32;
 
+// alt (may be null): tiles written by the filter pass; they are the ones to add unless *redo.
 __global__ __launch_bounds__(kBlock) void gram_mfma_reduce1_kernel(const float *partials, int waves,
-                                                                   int elems, double *slices)
+                                                                   int elems, double *slices,
+                                                                   const float *alt, int alt_waves,
+                                                                   const int *redo)
 {
     const int e = blockIdx.x * kBlock + threadIdx.x;
     if (e >= elems) return;
+    if (alt != nullptr && *redo == 0) partials = alt, waves = alt_waves;   // uniform
     const int slice = blockIdx.y;
     const int per = (waves + kReduceSlices - 1) / kReduceSlices;
     const int w0 = slice * per, w1 = w0 + per < waves ? w0 + per : waves;
@@ -324,13 +330,14 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
 }
 
 template <int T>
-hipError_t launch_mfma(const RowSet &rs, float *partials, int grid, bool aligned, hipStream_t s)
+hipError_t launch_mfma(const RowSet &rs, float *partials, int grid, bool aligned, const int *run_if,
+                       hipStream_t s)
 {
-    TraceScope t("gram_mfma_f32", s);
+    TraceScope t(run_if ? "gram_mfma_f32_if_redo" : "gram_mfma_f32", s);
     if (aligned)
-        gram_mfma_kernel<T, true><<<grid, kBlock, 0, s>>>(rs, partials);
+        gram_mfma_kernel<T, true><<<grid, kBlock, 0, s>>>(rs, partials, run_if);
     else
-        gram_mfma_kernel<T, false><<<grid, kBlock, 0, s>>>(rs, partials);
+        gram_mfma_kernel<T, false><<<grid, kBlock, 0, s>>>(rs, partials, run_if);
     return hipGetLastError();
 }
 
@@ -370,14 +377,14 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
     float *pp = static_cast<float *>(partials);
     const bool aligned = vec == 4;
     switch (T) {
-    case 1: e = launch_mfma<1>(rs, pp, grid, aligned, s); break;
-    case 2: e = launch_mfma<2>(rs, pp, grid, aligned, s); break;
-    case 3: e = launch_mfma<3>(rs, pp, grid, aligned, s); break;
-    case 4: e = launch_mfma<4>(rs, pp, grid, aligned, s); break;
-    case 5: e = launch_mfma<5>(rs, pp, grid, aligned, s); break;
-    case 6: e = launch_mfma<6>(rs, pp, grid, aligned, s); break;
-    case 7: e = launch_mfma<7>(rs, pp, grid, aligned, s); break;
-    case 8: e = launch_mfma<8>(rs, pp, grid, aligned, s); break;
+    case 1: e = launch_mfma<1>(rs, pp, grid, aligned, nullptr, s); break;
+    case 2: e = launch_mfma<2>(rs, pp, grid, aligned, nullptr, s); break;
+    case 3: e = launch_mfma<3>(rs, pp, grid, aligned, nullptr, s); break;
+    case 4: e = launch_mfma<4>(rs, pp, grid, aligned, nullptr, s); break;
+    case 5: e = launch_mfma<5>(rs, pp, grid, aligned, nullptr, s); break;
+    case 6: e = launch_mfma<6>(rs, pp, grid, aligned, nullptr, s); break;
+    case 7: e = launch_mfma<7>(rs, pp, grid, aligned, nullptr, s); break;
+    case 8: e = launch_mfma<8>(rs, pp, grid, aligned, nullptr, s); break;
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
@@ -387,12 +394,41 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
     {
         TraceScope t("gram_reduce", s);
         gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
-            pp, grid * (kBlock / kWave), elems, slices);
+            pp, grid * (kBlock / kWave), elems, slices, nullptr, 0, nullptr);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     TraceScope t("gram_scatter", s);
     gram_mfma_reduce2_kernel<<<(elems + 255) / 256, 256, 0, s>>>(slices, T, (int)count, Gm);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float *pass_partials,
+                                  int pass_waves, const int *redo, double *Gm, hipStream_t s)
+{
+    if (rs.count < 1 || rs.count > 16 || pass_waves < 1 || pass_partials == nullptr || redo == nullptr)
+        return hipErrorInvalidValue;
+    constexpr int T = 1;
+    int grid = num_compute_units() * mfma_blocks_per_cu(T);
+    if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
+    const int64_t steps = (rs.d + 31) / 32;
+    const int64_t need = (steps + kBlock / kWave - 1) / (kBlock / kWave);
+    if (grid > need) grid = (int)need;
+    float *pp = static_cast<float *>(partials);
+    // only if some vote had no majority: the tiles of the pass are of no use then
+    hipError_t e = launch_mfma<T>(rs, pp, grid, row_vec_width(rs.base, rs.ld) == 4, redo, s);
+    if (e != hipSuccess) return e;
+    const int elems = tiles_for(T) * 256;
+    double *slices = reinterpret_cast<double *>(pp + (size_t)mfma_max_waves(T) * elems);
+    {
+        TraceScope t("gram_reduce", s);
+        gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
+            pp, grid * (kBlock / kWave), elems, slices, pass_partials, pass_waves, redo);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    TraceScope t("gram_scatter", s);
+    gram_mfma_reduce2_kernel<<<(elems + 255) / 256, 256, 0, s>>>(slices, T, rs.count, Gm);
     return hipGetLastError();
 }
 

@@ -265,3 +265,36 @@ def test_robust_aggregator_inside_vote_groups(dx, a0, B, f, m):
             if B > 1:
                 assert rel_l2(host(blocks), ref_blocks) <= TOL
             assert rel_l2(host(out), ref_out) <= TOL
+
+
+@pytest.mark.parametrize("groups,r", [(9, 3), (11, 5), (13, 3), (16, 3), (16, 1), (10, 2)])
+@pytest.mark.parametrize("aggregator", ["multikrum", "bulyan", "geomedian"])
+def test_gram_of_the_votes_formed_in_the_filter_pass(dx, groups, r, aggregator):
+    """9 to 16 votes, every vote its own block, block means not materialised: the filter pass
+    forms the Gram matrix of the votes on the matrix cores.  Every group has a majority here, so
+    those tiles are the ones used (the repair path is covered by the test above); two replicated
+    votes must give exactly tied distances, which the selections make visible."""
+    import torch
+    rng = np.random.default_rng(100 * groups + r)
+    d = 70_003
+    base = rng.standard_normal((groups, d)).astype(np.float32) * np.float32(0.05)
+    base[3] = base[1]                                  # two identical votes: exact ties
+    G = np.repeat(base, r, axis=0)
+    if r >= 3:
+        G[0] = 5.0                                     # one Byzantine member, outvoted
+        G[r * 4 + 1] = -5.0
+    w = workloads.Workload("votes", groups * r, r, 2, d, base, {})
+    f = 1 if groups < 11 else 2
+    spec = dict(B=groups, aggregator=aggregator)
+    if aggregator == "multikrum":
+        spec.update(f=f, m=groups - f - 1)
+    if aggregator == "bulyan":
+        spec.update(f=f)
+    vote_perm = rng.permutation(groups).astype(np.int32)
+    for ld, vp in ((None, None), (d + 1, None), ((d + 63) // 64 * 64, vote_perm)):
+        _run(dx, w, spec, G=G, ld=ld, materialise=False, vote_perm=vp)
+    with dx.trace() as tr:
+        dx.detox_step(dev_matrix(G, (d + 3) // 4 * 4), r, 2, groups, aggregator, f=spec.get("f", -1),
+                      m=spec.get("m", -1), materialise=False)
+        names = [n for n, _ in tr.records()]
+    assert "filter_votes_gram" in names and "gram_mfma_f32" not in names
