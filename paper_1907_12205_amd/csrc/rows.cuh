@@ -109,6 +109,51 @@ __device__ inline void row_load(const RowSet &rs, int b, int64_t col, int valid,
     }
 }
 
+// The same for a thread whose VEC columns all lie inside d, written without per-thread
+// conditions around the loads (a row that stands for the zero vector re-reads row 0 and is
+// masked afterwards), so that the loads of neighbouring calls can be in flight together.
+template <bool MEANS, int VEC, bool NT = true>
+__device__ inline void row_load_full(const RowSet &rs, int b, int64_t col, float (&out)[VEC])
+{
+    if constexpr (!MEANS) {
+        const int64_t row = rs.index ? (int64_t)rs.index[b] : (int64_t)b;
+        float x[VEC];
+        load_floats<VEC, NT>(rs.base + (row < 0 ? 0 : row) * rs.ld + col, VEC, x);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) out[i] = row < 0 ? 0.0f : x[i];
+    } else {
+        const int64_t lo = ((int64_t)b * rs.n_votes) / rs.count;
+        const int64_t hi = ((int64_t)(b + 1) * rs.n_votes) / rs.count;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) out[i] = 0.0f;
+        for (int64_t pos = lo; pos < hi; pos += 4) {
+            const int cnt = hi - pos < 4 ? (int)(hi - pos) : 4;   // uniform
+            int32_t w[4];
+            float x[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (u < cnt) {
+                    w[u] = rs.winner[rs.vote_perm ? rs.vote_perm[pos + u] : pos + u];
+                    load_floats<VEC, NT>(rs.base + (int64_t)(w[u] < 0 ? 0 : w[u]) * rs.ld + col, VEC, x[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (u < cnt) {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) {
+                        const float xv = w[u] < 0 ? 0.0f : x[u][i];
+                        out[i] = (pos + u == lo) ? xv : __fadd_rn(out[i], xv);
+                    }
+                }
+            }
+        }
+        const float size = (float)(hi - lo);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) out[i] = __fdiv_rn(out[i], size);
+    }
+}
+
 __device__ inline double wave_sum_fixed(double v)
 {
     // fixed butterfly: the same tree for every call, so equal inputs give equal sums

@@ -251,7 +251,8 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const i
     double acc[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.0;
-    for (int k = 0; k < m; ++k) {
+    const bool full = ((int64_t)blockIdx.x + 1) * kBlock * VEC <= rs.d;   // uniform
+    auto logical_row = [&](int k) {
         int b = k;
         if constexpr (!WEIGHTED) {
             if (rows) {   // written by the selection kernel; clamped so a bad index cannot fault
@@ -259,8 +260,9 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const i
                 b = b < 0 ? 0 : (b >= rs.count ? rs.count - 1 : b);
             }
         }
-        float x[VEC];
-        row_load<MEANS, VEC>(rs, b, col, valid, x);
+        return b;
+    };
+    auto add_row = [&](int k, const float (&x)[VEC]) {
         if constexpr (WEIGHTED) {
             const double wk = weights[k];
 #pragma unroll
@@ -268,6 +270,25 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const i
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] += (double)x[i];
+        }
+    };
+    if (full) {
+        // four logical rows at a time, their loads free of per-thread conditions
+        for (int k0 = 0; k0 < m; k0 += 4) {
+            const int cnt = m - k0 < 4 ? m - k0 : 4;   // uniform
+            float x[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (u < cnt) row_load_full<MEANS, VEC>(rs, logical_row(k0 + u), col, x[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (u < cnt) add_row(k0 + u, x[u]);
+        }
+    } else {
+        for (int k = 0; k < m; ++k) {
+            float x[VEC];
+            row_load<MEANS, VEC>(rs, logical_row(k), col, valid, x);
+            add_row(k, x);
         }
     }
     float o[VEC];
