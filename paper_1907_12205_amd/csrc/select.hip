@@ -65,8 +65,10 @@ __global__ __launch_bounds__(kRowThreads) void sort_rows_kernel(const double *Gm
             if (dbl_before(y, x) || (!dbl_before(x, y) && c < b)) ++rank;
         }
         srow[rank] = x;
-        sc.sorted[a * count + rank] = x;
-        sc.sorted_idx[a * count + rank] = b;
+        // laid out as the Bulyan selection copies them into LDS: lists (count-1)|1 doubles apart
+        // (never more than count), and for every row b its position in the list of row a
+        sc.sorted[a * ((count - 1) | 1) + rank] = x;
+        sc.sorted_idx[a * count + b] = rank;
     }
     __syncthreads();
     if (nb > 0 && b == 0) {
@@ -92,69 +94,148 @@ __global__ __launch_bounds__(kRowThreads) void top_m_kernel(const double *scores
     if (rank < m) selected[rank] = a;
 }
 
+// Minimum of a 64-bit unsigned value over the 64 lanes of a wavefront, in every lane (all lanes
+// active): lane pairs, quads, half rows, rows by cross-lane moves, then the four row minima.
+template <int CTRL>
+__device__ inline unsigned long long min_paired_lane(unsigned long long v)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)v, CTRL, 0xf, 0xf, false);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(v >> 32), CTRL, 0xf, 0xf, false);
+    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    return o < v ? o : v;
+}
+__device__ inline unsigned long long wave_min_u64(unsigned long long v)
+{
+    v = min_paired_lane<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = min_paired_lane<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = min_paired_lane<0x141>(v);   // row_half_mirror
+    v = min_paired_lane<0x140>(v);   // row_mirror
+    unsigned long long m = ~0ull;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, 16 * q);
+        const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), 16 * q);
+        const unsigned long long r = ((unsigned long long)hi << 32) | lo;
+        m = r < m ? r : m;
+    }
+    return m;
+}
+
+// Position of the n-th set bit (n >= 1) of the 128-bit mask hi:lo, or -1 if fewer are set.
+__device__ inline int nth_set_bit(unsigned long long lo, unsigned long long hi, int n)
+{
+    int base = 0;
+    unsigned long long w = lo;
+    const int in_lo = __popcll(lo);
+    if (n > in_lo) n -= in_lo, w = hi, base = 64;
+#pragma unroll
+    for (int width = 32; width >= 1; width >>= 1) {
+        const int below = __popcll(w & ((1ull << width) - 1ull));
+        if (n > below) n -= below, w >>= width, base += width;
+    }
+    return ((w & 1ull) != 0ull && n == 1) ? base : -1;
+}
+
 // Bulyan stage 1: count-2f rounds of Krum over the rows still in the pool, on the sorted
-// neighbour lists held in LDS (dynamic: count*(count-1) doubles + as many bytes).  One thread per
-// row; the pool is a 128-bit mask every thread keeps in step; the arg-min runs over wavefront
-// shuffles, so a round costs one barrier.
+// neighbour lists held in LDS (dynamic: count*(count-1) doubles, then count*count bytes giving the
+// position of every row in every list).  One thread per row.  A thread keeps, as a bit mask over
+// the positions of its list, which of its neighbours are still in the pool: removing the round's
+// winner clears one bit (and zeroes that entry of the list), and the score is the sum of the
+// values up to the nb-th set bit, taken in ascending position (= ascending distance).
 __global__ __launch_bounds__(kRowThreads) void bulyan_select_kernel(int count, int f,
                                                                     SelectScratch sc,
                                                                     int32_t *selected)
 {
     extern __shared__ double lds[];
     const int nbrs = count - 1;
-    double *sval = lds;                                                 // [count][nbrs]
-    unsigned char *sidx = reinterpret_cast<unsigned char *>(lds + (size_t)count * nbrs);
-    __shared__ double wave_key[2][kRowThreads / kWave];
+    // [count][stride]: a row's list is contiguous (constant offsets in the walk); the odd stride
+    // keeps the rows' threads on different banks
+    const int stride = nbrs | 1;
+    double *sval = lds;
+    unsigned char *where = reinterpret_cast<unsigned char *>(lds + (size_t)count * stride);   // [count][count]
+    __shared__ unsigned long long wave_key[2][kRowThreads / kWave];
     __shared__ int wave_row[2][kRowThreads / kWave];
-    for (int e = threadIdx.x; e < count * nbrs; e += blockDim.x) {
-        const int a = e / nbrs, i = e % nbrs;
-        sval[e] = sc.sorted[a * count + i];
-        sidx[e] = (unsigned char)sc.sorted_idx[a * count + i];
+    __shared__ int picked[kMaxCount];
+    // straight copies (the sorting kernel wrote both tables in this layout), four loads in flight
+    for (int e0 = threadIdx.x; e0 < count * count; e0 += 4 * kRowThreads) {
+        double v[4];
+        int q[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * kRowThreads;
+            v[u] = e < count * stride ? sc.sorted[e] : 0.0;
+            q[u] = e < count * count ? sc.sorted_idx[e] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * kRowThreads;
+            if (e < count * stride) sval[e] = v[u];
+            if (e < count * count) where[e] = (unsigned char)q[u];
+        }
     }
     __syncthreads();
-    unsigned long long pool_lo = count >= 64 ? ~0ull : ((1ull << count) - 1ull);
-    unsigned long long pool_hi = count <= 64 ? 0ull : (count >= 128 ? ~0ull : ((1ull << (count - 64)) - 1ull));
-    auto in_pool = [&](int r) { return ((r < 64 ? pool_lo >> r : pool_hi >> (r - 64)) & 1ull) != 0ull; };
-    const int a = threadIdx.x, lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int a = threadIdx.x;
+    bool alive = a < count;
+    // positions 0 .. nbrs-1 of this row's list that are still in the pool
+    unsigned long long m_lo = nbrs >= 64 ? ~0ull : ((1ull << nbrs) - 1ull);
+    unsigned long long m_hi = nbrs <= 64 ? 0ull : (nbrs >= 128 ? ~0ull : ((1ull << (nbrs - 64)) - 1ull));
+    double *mine = sval + (size_t)(a < count ? a : 0) * stride;   // this row's list
     const int theta = count - 2 * f;
     for (int it = 0; it < theta; ++it) {
         const int pool = count - it;
         int nb = pool - f - 2;
         if (nb < 1) nb = 1;
         double key = INFINITY;
-        int row = 1 << 30;
-        if (a < count && in_pool(a)) {
+        if (alive) {
+            // The sum runs over the positions up to the nb-th one that is still in the pool.
+            // The entries of removed rows have been overwritten with +0.0, which leaves a sum of
+            // non-negative terms bit for bit as it is, so the walk is a plain ordered sum: this
+            // thread is alone on its SIMD, every instruction costs its full latency, and the
+            // cheapest walk is the one with the fewest of them.
+            const int last = nth_set_bit(m_lo, m_hi, nb);   // >= 0: at least nb neighbours are left
             double s = 0.0;
-            int taken = 0;
-            for (int i = 0; i < nbrs; ++i) {      // full length, predicated: the loads pipeline
-                const int r = sidx[a * nbrs + i];
-                const double v = sval[a * nbrs + i];
-                if (in_pool(r) && taken < nb) {
-                    s += v;
-                    ++taken;
-                }
-            }
-            key = s != s ? INFINITY : s;
-            row = a;
-        }
+            int i0 = 0;
+            for (; i0 + 15 <= last; i0 += 16) {   // whole batches: sixteen loads, sixteen adds
+                double v[16];
 #pragma unroll
-        for (int off = kWave / 2; off > 0; off >>= 1) {
-            const double k2 = __shfl_xor(key, off, kWave);
-            const int r2 = __shfl_xor(row, off, kWave);
-            if (k2 < key || (k2 == key && r2 < row)) key = k2, row = r2;
+                for (int u = 0; u < 16; ++u) v[u] = mine[i0 + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) s += v[u];
+            }
+            for (; i0 <= last; ++i0) s += mine[i0];
+            key = s != s ? INFINITY : s;
         }
-        if (lane == 0) wave_key[it & 1][wave] = key, wave_row[it & 1][wave] = row;
+        // The winner: smallest score, ties to the lower row; a NaN score ranks with +inf.  Scores
+        // are non-negative (or +inf), so their bit patterns order like unsigned integers.  Each
+        // wavefront finds its minimum by cross-lane moves and its lowest lane holding it by a
+        // ballot; the two wavefronts meet in LDS (two slots used in turn, one barrier a round).
+        const unsigned long long kb = alive ? (unsigned long long)__double_as_longlong(key) : ~0ull;
+        const unsigned long long wmin = wave_min_u64(kb);
+        const unsigned long long who = __ballot(alive && kb == wmin);
+        if ((threadIdx.x & (kWave - 1)) == 0) {
+            wave_key[it & 1][threadIdx.x >> 6] = wmin;
+            wave_row[it & 1][threadIdx.x >> 6] = who != 0ull ? (int)(threadIdx.x + __ffsll((long long)who) - 1) : 1 << 30;
+        }
         __syncthreads();
-        double bk = wave_key[it & 1][0];
         int best = wave_row[it & 1][0];
-        for (int w = 1; w < kRowThreads / kWave; ++w) {
-            const double k2 = wave_key[it & 1][w];
-            const int r2 = wave_row[it & 1][w];
-            if (k2 < bk || (k2 == bk && r2 < best)) bk = k2, best = r2;
+        {
+            const unsigned long long k0 = wave_key[it & 1][0], k1 = wave_key[it & 1][1];
+            const int r0 = wave_row[it & 1][0], r1 = wave_row[it & 1][1];
+            if (r0 == 1 << 30 || (r1 != 1 << 30 && k1 < k0)) best = r1;
         }
-        if (best < 64) pool_lo &= ~(1ull << best); else pool_hi &= ~(1ull << (best - 64));
-        if (threadIdx.x == 0) selected[it] = best;
+        if (a == best) {
+            alive = false;
+        } else if (a < count) {
+            const int q = where[a * count + best];
+            if (q < 64) m_lo &= ~(1ull << q); else m_hi &= ~(1ull << (q - 64));
+            mine[q] = 0.0;   // this row's own entry: read back by this thread only
+        }
+        // kept in LDS until the end: a store to memory here would make every barrier of the
+        // next round wait for it to complete
+        if (threadIdx.x == 0) picked[it] = best;
     }
+    __syncthreads();
+    for (int it = threadIdx.x; it < theta; it += blockDim.x) selected[it] = picked[it];
 }
 
 constexpr int kWzLanesPerRow = 4;                          // lanes that share a row of the matrix
@@ -377,7 +458,7 @@ hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const Se
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t lds = (size_t)count * (count - 1) * (sizeof(double) + 1) + 16;
+    const size_t lds = (size_t)count * ((count - 1) | 1) * sizeof(double) + (size_t)count * count + 16;
     if (lds > 64 * 1024) {
         // gfx950 has 160 KB of LDS per workgroup; more than 64 KB has to be asked for
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(bulyan_select_kernel),
