@@ -223,8 +223,10 @@ def main():
             timed("DETOX geometric median, B=5, 50 iterations", lambda: dx.detox_step(G, r, q, 5, "geomedian", buffers=bm), n + groups + 1)
         if groups >= 7:
             bb = StepBuffers(n, d, r, groups, G.device, materialise=False)
+            # 9..16 votes: their Gram matrix comes out of the filter pass, so the votes are read once more
+            # only for the trimming (more votes: also once for the Gram matrix)
             timed(f"DETOX Bulyan over the {groups} votes, f=1", lambda: dx.detox_step(G, r, q, groups, "bulyan", f=1, buffers=bb),
-                  n + groups + (groups - 2) + 1)
+                  n + (0 if 8 < groups <= 16 else groups) + (groups - 2) + 1)
         if groups >= 14:
             # the hierarchy the paper deployed (Section 5.2): robust aggregator inside vote groups, mean across
             ws_h = torch.empty(dx.workspace_bytes("step", n, d, groups) + 4 * groups + 512, dtype=torch.uint8, device=G.device)
