@@ -229,11 +229,13 @@ def main():
                   n + (0 if 8 < groups <= 16 else groups) + (groups - 2) + 1)
         if groups >= 14:
             # the hierarchy the paper deployed (Section 5.2): robust aggregator inside vote groups, mean across
-            ws_h = torch.empty(dx.workspace_bytes("step", n, d, groups) + 4 * groups + 512, dtype=torch.uint8, device=G.device)
+            gram_rows = 0 if 8 < groups <= 16 else groups   # 9..16 votes: their Gram matrix comes with the filter pass
+            ws_h = torch.empty(max(dx.robust_blocks_workspace_bytes(n, d, r, 1), dx.robust_blocks_workspace_bytes(n, d, r, 2)),
+                               dtype=torch.uint8, device=G.device)
             timed(f"DETOX A0=Multi-Krum(f=2,m=3) on {groups // 2}+{groups - groups // 2} votes, A1=mean",
-                  lambda: dx.detox_step_robust_blocks(G, r, 2, "multikrum", 2, 3, out=out_o, ws=ws_h), n + groups + 2 * 3 + 2 + 2 + 1)
+                  lambda: dx.detox_step_robust_blocks(G, r, 2, "multikrum", 2, 3, out=out_o, ws=ws_h), n + gram_rows + 2 * 3 + 2 + 2 + 1)
             timed(f"DETOX A0=Bulyan(f=2) on all {groups} votes",
-                  lambda: dx.detox_step_robust_blocks(G, r, 1, "bulyan", 2, out=out_o, ws=ws_h), n + groups + (groups - 4) + 1)
+                  lambda: dx.detox_step_robust_blocks(G, r, 1, "bulyan", 2, out=out_o, ws=ws_h), n + gram_rows + (groups - 4) + 1)
         timed(f"vanilla coord-median over {n} rows", lambda: dx.robust_coord_median(G, out=out_o), n + 1)
         timed(f"vanilla trimmed mean over {n} rows, {n // 4} off each end",
               lambda: dx.robust_trimmed_mean(G, n // 4, out=out_o), n + 1)

@@ -245,7 +245,9 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
  *              fills m entries there, Bulyan size-2f
  *   out        dev, d floats
  *   ws         DETOX_OP_STEP bytes with count = n and aux = the largest group size
- *              ceil((n/r)/B)                                                              */
+ *              ceil((n/r)/B).  With 9 <= n/r <= 16 and DETOX_OP_MULTIKRUM bytes for count = n/r
+ *              on top of that, the Gram matrix of all votes is formed during the filter pass
+ *              and the vote groups cut theirs out of it (one pass less over the winner rows). */
 int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, int r,
                              const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
                              int a0, int f, int m, int32_t *winner, float *block_out,

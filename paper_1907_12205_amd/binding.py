@@ -304,8 +304,19 @@ def detox_step(G, r: int, q: int, B: int, aggregator: str, f: int = -1, m: int =
     return b
 
 
+def robust_blocks_workspace_bytes(n: int, d: int, r: int, B: int, gram_in_pass: bool = True) -> int:
+    """Workspace of detox_step_robust_blocks; with gram_in_pass (and 9..16 votes) the extra room
+    that lets the filter pass form the Gram matrix of all votes."""
+    groups = n // max(r, 1)
+    largest = -(-groups // max(B, 1))
+    need = workspace_bytes("step", n, d, largest) + 4 * groups + 512
+    if gram_in_pass and 8 < groups <= 16:
+        need += workspace_bytes("multikrum", groups, d)
+    return need
+
+
 def detox_step_robust_blocks(G, r: int, B: int, a0: str, f: int, m: int = -1, group_rows=None, vote_perm=None,
-                             out=None, ws=None):
+                             out=None, ws=None, gram_in_pass: bool = True):
     """Robust aggregator inside every vote group, mean over the groups.
     Returns (out[d], winner[n/r], block_out[B x d] or None, selected[n/r])."""
     torch = _torch()
@@ -317,8 +328,7 @@ def detox_step_robust_blocks(G, r: int, B: int, a0: str, f: int, m: int = -1, gr
     block_out = torch.empty((B, d), dtype=torch.float32, device=G.device) if B > 1 else None
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=G.device)
-    largest = -(-groups // max(B, 1))
-    ws, nb = _ws(ws, workspace_bytes("step", n, d, largest) + 4 * groups + 512, G.device)
+    ws, nb = _ws(ws, robust_blocks_workspace_bytes(n, d, r, B, gram_in_pass), G.device)
     rc = lib().detox_step_robust_blocks(p, n, d, ld, r, _ptr(gr), B, _ptr(vp), AGG[a0], f, m, _ptr(winner),
                                         _ptr(block_out), d, _ptr(selected), _ptr(out), _ptr(ws), nb, _stream())
     _check(rc, "detox_step_robust_blocks")

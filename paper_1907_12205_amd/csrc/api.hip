@@ -106,12 +106,15 @@ struct FusedGram {
     const int *redo = nullptr;
     bool reduced = false;   // Gm (and the Multi-Krum selection) already produced unless *redo
     int vote_waves = 0;     // > 0: MFMA tiles of the votes' Gram matrix in AggWs::pass_gram (unless *redo)
+    const double *whole = nullptr;   // non-null: Gram matrix (whole_ld wide) of a row set of which
+    int whole_ld = 0, whole_off = 0; //   these rows are the run starting at whole_off
 };
 
 hipError_t gram_for(const RowSet &rs, const AggWs &a, const FusedGram &fg, hipStream_t s)
 {
     if (fg.reduced)
         return launch_small_redo(rs, a.partials, fg.redo, a.Gm, 0, 0, a.sc.scores, nullptr, s);
+    if (fg.whole != nullptr) return launch_gram_cut(fg.whole, fg.whole_ld, fg.whole_off, rs.count, a.Gm, s);
     if (fg.vote_waves > 0)
         return launch_gram_after_pass(rs, a.partials, a.pass_gram, fg.vote_waves, fg.redo, a.Gm, s);
     return launch_gram(rs, a.partials, a.Gm, s);
@@ -488,13 +491,23 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
     }
     const size_t fbytes = filter_bytes(groups);
     const size_t tbytes = round_up((size_t)groups * sizeof(int32_t));
-    if (!ws_ok(ws, ws_bytes, fbytes + tbytes + aggregator_ws_bytes(largest))) return DETOX_EWORKSPACE;
+    const size_t base_bytes = fbytes + tbytes + aggregator_ws_bytes(largest);
+    if (!ws_ok(ws, ws_bytes, base_bytes)) return DETOX_EWORKSPACE;
+    // 9..16 votes and room for one more aggregator workspace (of n/r rows): the Gram matrix of all
+    // votes comes out of the filter pass and every vote group cuts its own matrix out of it
+    const size_t all_bytes = pass_gram_bytes(groups) ? aggregator_ws_bytes(groups) : 0;
+    const bool in_pass = all_bytes != 0 && ws_bytes >= base_bytes + all_bytes;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
-    FilterParams p{G, d, ld, r, group_rows, nullptr, groups, groups, nullptr, 0,
-                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0};
-    hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, nullptr, s);
+    void *aws = static_cast<char *>(ws) + fbytes + tbytes;
+    AggWs all{};
+    if (in_pass) all = carve_aggregator(static_cast<char *>(aws) + aggregator_ws_bytes(largest), groups);
+    FilterParams p{G, d, ld, r, group_rows, in_pass ? vote_perm : nullptr, groups, groups, nullptr, 0,
+                   fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0,
+                   in_pass ? all.pass_gram : nullptr};
+    FilterDone done;
+    hipError_t e = launch_filter(p, in_pass ? FilterWant::kVotesGram : FilterWant::kVotes, nullptr, &done, s);
     if (e != hipSuccess) return status_of(e);
     // row table of the votes in vote order: winner itself, or winner o vote_perm
     const int32_t *table = winner;
@@ -504,16 +517,24 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
         if (e != hipSuccess) return status_of(e);
         table = t;
     }
-    void *aws = static_cast<char *>(ws) + fbytes + tbytes;
+    FusedGram fg;
+    if (done.vote_gram_waves > 0) {
+        const RowSet votes{G, d, ld, (int)n, (int)groups, table, nullptr, nullptr, 0};
+        e = launch_gram_after_pass(votes, all.partials, all.pass_gram, done.vote_gram_waves, fw.redo, all.Gm, s);
+        if (e != hipSuccess) return status_of(e);
+        fg.whole = all.Gm;
+        fg.whole_ld = (int)groups;
+    }
     for (int64_t b = 0; b < B; ++b) {
         const int64_t lo = (b * groups) / B, hi = ((b + 1) * groups) / B;
         const RowSet rs{G, d, ld, (int)n, (int)(hi - lo), table + lo, nullptr, nullptr, 0};
         float *target = B == 1 ? out : block_out + b * ldb;
+        fg.whole_off = (int)lo;
         if (a0 == DETOX_AGG_MULTIKRUM)
             rc = multikrum_impl(rs, f, m < 0 ? (int)(hi - lo) - f : m, target, selected + lo, nullptr,
-                                aws, FusedGram{}, s);
+                                aws, fg, s);
         else
-            rc = bulyan_impl(rs, f, target, selected + lo, aws, FusedGram{}, s);
+            rc = bulyan_impl(rs, f, target, selected + lo, aws, fg, s);
         if (rc) return rc;
     }
     if (B > 1) e = launch_rows_mean(direct_rows(block_out, B, d, ldb), nullptr, (int)B, out, s);

@@ -156,6 +156,9 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
 // again from the rows (one more launch, which does nothing otherwise).
 hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float *pass_partials,
                                   int pass_waves, const int *redo, double *Gm, hipStream_t s);
+// Gm[a][b] = full[(off+a)*ld + off+b] for a, b < count: the Gram matrix of a run of rows cut out of
+// the Gram matrix of a larger row set.
+hipError_t launch_gram_cut(const double *full, int ld, int off, int count, double *Gm, hipStream_t s);
 // count <= 8, the finalize kernel has produced Gm (and the Multi-Krum selection when krum_m > 0)
 // unless *redo: one kernel that does nothing unless *redo recomputes the Gram matrix from the
 // rows; its last-finishing workgroup repeats the reduction (and the selection).  redo[1] counts

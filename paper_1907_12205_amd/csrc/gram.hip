@@ -403,6 +403,23 @@ hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t
     return hipGetLastError();
 }
 
+namespace {
+__global__ void gram_cut_kernel(const double *full, int ld, int off, int count, double *Gm)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= count * count) return;
+    const int a = e / count, b = e % count;
+    Gm[e] = full[(off + a) * ld + off + b];
+}
+}  // namespace
+
+hipError_t launch_gram_cut(const double *full, int ld, int off, int count, double *Gm, hipStream_t s)
+{
+    TraceScope t("gram_cut", s);
+    gram_cut_kernel<<<(count * count + 255) / 256, 256, 0, s>>>(full, ld, off, count, Gm);
+    return hipGetLastError();
+}
+
 hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float *pass_partials,
                                   int pass_waves, const int *redo, double *Gm, hipStream_t s)
 {

@@ -250,13 +250,20 @@ def test_robust_aggregator_inside_vote_groups(dx, a0, B, f, m):
     """The hierarchy of Section 5.2 (A0 robust, A1 mean), e.g. Multi-Krum on 7 + 8 votes and Bulyan
     on all 15 (Appendix B.1), with a group without majority and a vote permutation."""
     w = workloads.config(3, d=40009)
-    G = w.matrix()
-    G[12] = 7; G[13] = 8; G[14] = 9          # group 4 has no majority: its vote is the zero vector
     rng = np.random.default_rng(B * 10 + f)
-    for vote_perm in (None, rng.permutation(15).astype(np.int32)):
+    # with and without a group that has no majority (its vote is the zero vector; the Gram matrix
+    # formed in the filter pass is then replaced), with and without a vote permutation, aligned
+    # and unaligned rows, and with the smaller workspace that keeps the Gram matrices out of the pass
+    for broken, vote_perm, ld, in_pass in ((True, None, None, True), (True, rng.permutation(15).astype(np.int32), 40064, True),
+                                           (False, None, 40064, True), (False, rng.permutation(15).astype(np.int32), 40064, True),
+                                           (False, None, None, True), (False, None, 40064, False), (True, None, 40064, False)):
+        G = w.matrix()
+        if broken:
+            G[12] = 7; G[13] = 8; G[14] = 9
         ref_out, ref_w, ref_blocks, ref_sels = oracle.detox_step_robust_blocks(G, 3, B, a0, f, m, vote_perm=vote_perm)
-        for ld in (None, 40064):
-            out, winner, blocks, selected = dx.detox_step_robust_blocks(dev_matrix(G, ld), 3, B, a0, f, m, vote_perm=vote_perm)
+        for _ in range(1):
+            out, winner, blocks, selected = dx.detox_step_robust_blocks(dev_matrix(G, ld), 3, B, a0, f, m, vote_perm=vote_perm,
+                                                                        gram_in_pass=in_pass)
             assert host(winner).tolist() == ref_w.tolist()
             sel = host(selected)
             for b, rs in enumerate(ref_sels):
