@@ -114,7 +114,7 @@ hipError_t gram_for(const RowSet &rs, const AggWs &a, const FusedGram &fg, hipSt
 {
     if (fg.reduced)
         return launch_small_redo(rs, a.partials, fg.redo, a.Gm, 0, 0, a.sc.scores, nullptr, s);
-    if (fg.whole != nullptr) return launch_gram_cut(fg.whole, fg.whole_ld, fg.whole_off, rs.count, a.Gm, s);
+    if (fg.whole != nullptr) return launch_gram_cut(fg.whole, fg.whole_ld, fg.whole_off, rs.count, a.Gm, s);   // (a copy when the run is the whole set)
     if (fg.vote_waves > 0)
         return launch_gram_after_pass(rs, a.partials, a.pass_gram, fg.vote_waves, fg.redo, a.Gm, s);
     return launch_gram(rs, a.partials, a.Gm, s);
@@ -525,11 +525,23 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
         fg.whole = all.Gm;
         fg.whole_ld = (int)groups;
     }
+    // Multi-Krum in groups of at most 8 votes with the Gram matrix of all votes at hand: the
+    // scores and selections of every group in one launch, then only the averages are left
+    const bool select_at_once = fg.whole != nullptr && a0 == DETOX_AGG_MULTIKRUM && largest <= 8;
+    if (select_at_once) {
+        e = launch_cut_multikrum(all.Gm, (int)groups, (int)B, f, m, all.sc.scores, selected, s);
+        if (e != hipSuccess) return status_of(e);
+    }
     for (int64_t b = 0; b < B; ++b) {
         const int64_t lo = (b * groups) / B, hi = ((b + 1) * groups) / B;
         const RowSet rs{G, d, ld, (int)n, (int)(hi - lo), table + lo, nullptr, nullptr, 0};
         float *target = B == 1 ? out : block_out + b * ldb;
         fg.whole_off = (int)lo;
+        if (select_at_once) {
+            e = launch_rows_mean(rs, selected + lo, m < 0 ? (int)(hi - lo) - f : m, target, s);
+            if (e != hipSuccess) return status_of(e);
+            continue;
+        }
         if (a0 == DETOX_AGG_MULTIKRUM)
             rc = multikrum_impl(rs, f, m < 0 ? (int)(hi - lo) - f : m, target, selected + lo, nullptr,
                                 aws, fg, s);

@@ -159,6 +159,11 @@ hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float 
 // Gm[a][b] = full[(off+a)*ld + off+b] for a, b < count: the Gram matrix of a run of rows cut out of
 // the Gram matrix of a larger row set.
 hipError_t launch_gram_cut(const double *full, int ld, int off, int count, double *Gm, hipStream_t s);
+// Multi-Krum inside every one of B runs of rows (run b = rows [b*V/B, (b+1)*V/B) of a V-row set
+// whose Gram matrix `full` is given; every run at most 8 rows): scores and the m (m < 0: size - f)
+// selected positions of run b at scores + lo and selected + lo, one workgroup per run.
+hipError_t launch_cut_multikrum(const double *full, int V, int B, int f, int m, double *scores,
+                                int32_t *selected, hipStream_t s);
 // count <= 8, the finalize kernel has produced Gm (and the Multi-Krum selection when krum_m > 0)
 // unless *redo: one kernel that does nothing unless *redo recomputes the Gram matrix from the
 // rows; its last-finishing workgroup repeats the reduction (and the selection).  redo[1] counts

@@ -413,6 +413,32 @@ __global__ void gram_cut_kernel(const double *full, int ld, int off, int count, 
 }
 }  // namespace
 
+namespace {
+__global__ __launch_bounds__(kBlock) void cut_multikrum_kernel(const double *full, int V, int B, int f,
+                                                               int m, double *scores, int32_t *selected)
+{
+    __shared__ double Gl[kSmallCount * kSmallCount];
+    const int b = blockIdx.x;
+    const int lo = (int)(((int64_t)b * V) / B), hi = (int)(((int64_t)(b + 1) * V) / B);
+    const int cnt = hi - lo;
+    if ((int)threadIdx.x < cnt * cnt) {
+        const int a = threadIdx.x / cnt, c = threadIdx.x % cnt;
+        Gl[a * cnt + c] = full[(lo + a) * V + lo + c];
+    }
+    __syncthreads();
+    const SmallSelect q{nullptr, 0, 0, 0, cnt, nullptr, f, m < 0 ? cnt - f : m, scores + lo, selected + lo};
+    small_multikrum(q, Gl);
+}
+}  // namespace
+
+hipError_t launch_cut_multikrum(const double *full, int V, int B, int f, int m, double *scores,
+                                int32_t *selected, hipStream_t s)
+{
+    TraceScope t("multikrum_select_in_groups", s);
+    cut_multikrum_kernel<<<B, kBlock, 0, s>>>(full, V, B, f, m, scores, selected);
+    return hipGetLastError();
+}
+
 hipError_t launch_gram_cut(const double *full, int ld, int off, int count, double *Gm, hipStream_t s)
 {
     TraceScope t("gram_cut", s);
