@@ -306,7 +306,9 @@ __global__ __launch_bounds__(kWzGramThreads) void weiszfeld_kernel(const double 
         const double d2 = fma(quad * rS, rS, fma(-2.0 * rS, gu, gjj));
         // 1 / max(sqrt(d2), eps) without a square root followed by a division
         u = live ? (d2 > eps2 ? rsqrt(d2) : inv_eps) : 0.0;
-        __syncthreads();                           // every thread is done reading u_all
+        // every thread must be done reading u_all: with several wavefronts the barrier inside
+        // sum_pair (after the pass over the matrix) has already seen to that
+        if (waves == 1) __syncthreads();
         if (mine) u_all[j] = u;
         __syncthreads();
     }
