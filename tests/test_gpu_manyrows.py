@@ -167,3 +167,24 @@ def test_mean_estimation_at_full_size(dx, d):
     # the claim of Section 5.3: the estimate after DETOX is much closer to the true mean (0)
     assert np.linalg.norm(host(b.out)) < 0.3 * np.linalg.norm(got_gm)
     assert np.linalg.norm(ref_med) < 0.3 * np.linalg.norm(got)
+
+
+def test_largest_number_of_node_groups(dx):
+    """n/r = 65535 is the limit of this build; one more is refused before anything is launched."""
+    import torch
+    rng = np.random.default_rng(65535)
+    groups, r, d = 65535, 2, 5
+    base = rng.standard_normal((groups, d)).astype(np.float32)
+    G = np.repeat(base, r, axis=0)
+    odd = rng.choice(groups, size=500, replace=False)
+    G[odd * r + 1, 2] += 1.0                                   # two members that differ: no majority
+    ref_w = oracle.majority_filter(G, r)
+    assert (ref_w < 0).sum() == 500
+    Gd = dev_matrix(G)
+    w, Zhat = dx.detox_filter_block_mean(Gd, r, 101)
+    assert host(w).tolist() == ref_w.tolist()
+    assert host(Zhat).tobytes() == oracle.block_mean(G, ref_w, 101).tobytes()
+    too_many = torch.zeros(((groups + 1) * r, d), device="cuda:0")
+    with pytest.raises(dx.DetoxError) as e:
+        dx.detox_majority_filter(too_many, r)
+    assert e.value.code == 1
