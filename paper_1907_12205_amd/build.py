@@ -78,7 +78,23 @@ def build(jobs: int = 8, force: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+    build_example()
     return LIB
+
+
+EXAMPLE_SRC = os.path.join(HERE, "..", "examples", "detox_step_main.cpp")
+EXAMPLE_BIN = os.path.join(HERE, "..", "examples", "detox_step_main")
+
+
+def build_example() -> str:
+    """The C-ABI-only caller under examples/ (HIP runtime + libdetox.so, no Python, no torch)."""
+    cmd = [HIPCC, "-O2", "-std=c++17", "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", EXAMPLE_SRC,
+           "-o", EXAMPLE_BIN, "-L" + HERE, "-ldetox", "-L/opt/rocm/lib", "-lamdhip64",
+           "-Wl,-rpath," + HERE, "-Wl,-rpath,/opt/rocm/lib"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the example failed:\n" + r.stdout + r.stderr)
+    return EXAMPLE_BIN
 
 
 if __name__ == "__main__":
