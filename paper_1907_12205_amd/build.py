@@ -43,14 +43,19 @@ def units():
 
 
 def _stale(obj: str, src: str) -> bool:
-    """An object is stale when its source, any header beside it, the public header or this file
-    is newer."""
+    """An object is stale when its source, any header it included when it was last compiled (the
+    compiler's dependency file beside it; without one: every header) or this file is newer."""
     if not os.path.exists(obj):
         return True
     t = os.path.getmtime(obj)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if not f.endswith(".hip")]
-    deps += [os.path.join(CSRC, src), os.path.join(HERE, "..", "include", "detox.h"), __file__]
-    return any(os.path.getmtime(d) > t for d in deps)
+    deps = [os.path.join(CSRC, src), __file__]
+    try:
+        text = open(obj[:-2] + ".d").read().replace("\\\n", " ")
+        deps += [w for w in text.split()[1:] if not w.startswith("/opt/") and not w.startswith("/usr/")]
+    except OSError:
+        deps += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if not f.endswith(".hip")]
+        deps.append(os.path.join(HERE, "..", "include", "detox.h"))
+    return any((not os.path.exists(d)) or os.path.getmtime(d) > t for d in deps)
 
 
 def _compile(unit, force=True) -> str:
@@ -58,7 +63,7 @@ def _compile(unit, force=True) -> str:
     obj = os.path.join(OBJ, objname)
     if not force and not _stale(obj, src):
         return obj
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *extra, "-MD", "-MF", obj[:-2] + ".d", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                     if "packed-fp32-ops" not in l)       # the host pass does not know the feature

@@ -52,7 +52,7 @@ inline int row_vec_width(const void *base, int64_t ld)
     return 1;
 }
 
-// A set of logical rows handed to an aggregator (see rows.cuh for the device side).
+// A set of logical rows handed to an aggregator (see rows.h for the device side).
 struct RowSet {
     const float *base;          // the matrix the rows are read from
     int64_t d, ld;
@@ -68,6 +68,34 @@ inline RowSet direct_rows(const float *X, int64_t count, int64_t d, int64_t ld)
 {
     return RowSet{X, d, ld, (int)count, (int)count, nullptr, nullptr, nullptr, 0};
 }
+
+// ---- refrow.hip ------------------------------------------------------------
+// The logical rows among which the reference row of an fp32 Gram matrix is picked (rows.h,
+// pick_reference).  Three kinds:
+//   n_votes == 0          : logical row b = row index[b] of base (null: row b; -1: zeros);
+//   n_votes > 0, r == 0   : logical row b = mean of the votes of vote group b of `count`, vote j
+//                           being row winner[j] of base (-1: zeros);
+//   n_votes > 0, r > 0    : the same before the winners are known: vote j is the per-coordinate
+//                           majority value among the r member rows of node group j.
+struct RefRows {
+    const float *base;
+    int64_t d, ld;
+    int count;
+    const int32_t *index;
+    int r;
+    const int32_t *group_rows;   // with r > 0: members of node group j (null: rows j*r .. j*r+r-1)
+    const int32_t *winner;
+    const int32_t *vote_perm;    // with n_votes > 0: vote order (null: identity)
+    int n_votes;
+};
+inline RefRows ref_rows_of(const RowSet &rs)
+{
+    return RefRows{rs.base, rs.d, rs.ld, rs.count, rs.index, 0, nullptr, rs.winner, rs.vote_perm,
+                   rs.means() ? rs.n_votes : 0};
+}
+// keys: dev, count words (see pick_reference).  run_if (dev, may be null): skip unless *run_if.
+hipError_t launch_reference_keys(const RefRows &q, unsigned long long *keys, const int *run_if,
+                                 hipStream_t s);
 
 // ---- filter.hip ------------------------------------------------------------
 struct FilterParams {
@@ -87,7 +115,9 @@ struct FilterParams {
     int32_t *winner;                    // dev, n_votes
     float *out;                         // dev, d: coordinate-wise median / trimmed mean (those modes)
     int trim_g;                         // trimmed-mean mode: values dropped at each end
-    float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats (kVotesGram)
+    float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats, then kMaxCount
+                                        //   reference keys (kVotesGram)
+    unsigned long long *vote_ref_keys;  // set by launch_filter
 };
 struct FilterWs {
     int *redo;
@@ -116,7 +146,7 @@ struct FilterDone {
     int vote_gram_waves = 0;      // > 0: kVotesGram honoured, that many wavefront tiles written (valid
                                   //   unless *redo)
 };
-struct SmallSelect;               // small_select.cuh: what the finalize kernel should go on to do
+struct SmallSelect;               // small_select.h: what the finalize kernel should go on to do
 // kGram / kMedian with B > 8 (or more than kFusedMaxVotes groups) degrade to kMeans; then Zhat
 // must be non-null (hipErrorInvalidValue otherwise).
 //   tail (may be null): with kGram honoured, the finalize kernel also reduces the Gram partials

@@ -18,9 +18,9 @@
 //                      into one zero-initialised word per group with integer atomic ORs.
 #include <cstdlib>
 
-#include "rows.cuh"
-#include "small_select.cuh"
-#include "sortnet.cuh"
+#include "rows.h"
+#include "small_select.h"
+#include "sortnet.h"
 
 namespace detox {
 namespace {
@@ -159,6 +159,9 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
     constexpr int kTileLd = 68;
     __shared__ __attribute__((aligned(16))) float vtile[MODE == kVotesGram ? kBlock / kWave : 1][16][kTileLd];
     [[maybe_unused]] f32x4_t macc = {0.0f, 0.0f, 0.0f, 0.0f};
+    // kVotesGram: the vote subtracted from every vote before the products (rows.h, pick_reference)
+    [[maybe_unused]] int refpos = 0;
+    if constexpr (MODE == kVotesGram) refpos = pick_reference(p.vote_ref_keys, (int)p.n_votes);
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock) sbits[j] = 0ull;
     __syncthreads();
 
@@ -215,14 +218,25 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
                     for (int i = 0; i < VEC; ++i) v[pos][i] = 0.0f;
                 }
             }
+            float rv[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) rv[i] = v[0][i];
+#pragma unroll
+            for (int pos = 1; pos < kPassGramMaxVotes; ++pos)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) rv[i] = pos == refpos ? v[pos][i] : rv[i];   // uniform
             // The tile is private to the wavefront, whose LDS instructions execute in order: the
             // writes of one component are seen by the reads that follow, and those are done
-            // before the next component is written.
+            // before the next component is written (the fences keep the compiler to that order).
             const int wv = threadIdx.x / kWave, ti = lane & 15, tk = lane >> 4;
 #pragma unroll
             for (int q = 0; q < VEC; ++q) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int pos = 0; pos < kPassGramMaxVotes; ++pos) vtile[wv][pos][lane] = v[pos][q];
+                for (int pos = 0; pos < kPassGramMaxVotes; ++pos) vtile[wv][pos][lane] = v[pos][q] - rv[q];
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const float4 a = *reinterpret_cast<const float4 *>(&vtile[wv][ti][16 * u + 4 * tk]);
@@ -663,6 +677,14 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
     if (done) *done = FilterDone{};
     hipError_t e;
     int grid = 0;
+    if (mode == kVotesGram) {
+        // the winners are not known yet: the reference vote is picked among the per-coordinate
+        // majority values of the node groups, which is what the pass multiplies
+        p.vote_ref_keys = reinterpret_cast<unsigned long long *>(p.vote_gram_partials + (size_t)kPassGramMaxWaves * 256);
+        const RefRows q{p.G, p.d, p.ld, (int)p.n_votes, nullptr, p.r, p.group_rows, nullptr, p.vote_perm, (int)p.n_votes};
+        e = launch_reference_keys(q, p.vote_ref_keys, nullptr, s);
+        if (e != hipSuccess) return e;
+    }
     if (fused) {
         grid = num_compute_units() * (p.n_votes <= 128 ? 4 : 2);   // wanted; trimmed to what is resident
         if (votes_gram && grid * (kBlock / kWave) > kPassGramMaxWaves) grid = kPassGramMaxWaves / (kBlock / kWave);

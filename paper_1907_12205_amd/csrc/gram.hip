@@ -10,8 +10,8 @@
 // counter shows to be the last) adds them in a fixed order in fp64.  No floating-point atomics:
 // results repeat bit for bit, and rows
 // that are bit-identical produce bit-identical Gram entries (same products, same order).
-#include "rows.cuh"
-#include "small_select.cuh"
+#include "rows.h"
+#include "small_select.h"
 
 namespace detox {
 namespace {
@@ -132,107 +132,170 @@ __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double 
 // ---------------------------------------------------------------------------------------
 // count > 8: fp32 MFMA.  V_MFMA_F32_16X16X4_F32 takes A (16x4) with lane l holding
 // A[l%16][l/16] and B (4x16) with lane l holding B[l/16][l%16]; for a Gram tile both operands
-// are slices of X in the same layout, so one register per row tile feeds both sides.  The k
-// index is a summation index: lane (i, kk) reads 4 consecutive columns of its own row with one
-// 16-byte load and the four components serve four successive MFMA steps.  The accumulator of
-// tile (ti, tj) holds C[4*(l/16)+v][l%16] in component v of lane l.
+// are slices of X in the same layout, so one register per row tile feeds both sides.  The
+// accumulator of tile (ti, tj) holds C[4*(l/16)+v][l%16] in component v of lane l.
+//
+// A wavefront works on tiles of kTileCols columns of all (padded) rows.  It fetches a tile with
+// loads that are contiguous along the rows (16 lanes x 16 bytes = one 256-byte segment of a row,
+// four rows per instruction, non-temporal), parks it in an LDS tile of its own and reads the MFMA
+// operands back from there: lane (i, kk) takes 16 bytes of row 16t+i at columns 16s+4kk, whose
+// four components serve four successive MFMA steps (the summation index may be assigned to
+// columns in any order as long as both operands agree).  The loads of the next tile are issued
+// before the current one is consumed.  The reference row's segment is read from the same LDS
+// tile and subtracted from every operand before the products (rows.h, pick_reference).
 // ---------------------------------------------------------------------------------------
-// rowp[t]: this lane's row of row tile t; zero[t]: that logical row is the zero vector (a vote
-// without majority), in which case the loaded values are discarded.  Plain (temporal) loads:
-// the four lanes of a row and the two halves of a step share 128-byte lines through the caches.
-template <int T, bool ALIGNED>
-__device__ inline void gram_load_step(const float *const (&rowp)[T], const bool (&zero)[T],
-                                      int64_t c0, int kk, int64_t d, bool guarded,
-                                      float4 (&buf)[T][2])
+constexpr int kTileCols = 64;
+constexpr int kTilePitch = kTileCols + 4;   // floats between LDS rows: the 16-byte reads of 16 rows hit 64 banks
+
+// Fetches this lane's 4T pieces of a tile: piece g is 16 bytes of logical row 4g + lane/16 at
+// column `col` (= tile column + 4*(lane%16)).  rows: LDS table with, for every padded logical row,
+// the element offset in rs.base of the row behind it (a zero or padded row: some valid row); with
+// MEANS, the logical row itself.
+template <int T, bool ALIGNED, bool MEANS>
+__device__ inline void tile_fetch(const RowSet &rs, const int64_t *rows, int64_t col, bool guarded,
+                                  f32x4 (&buf)[4 * T])
 {
+    const int sub = (int)((threadIdx.x & (kWave - 1)) >> 4);
 #pragma unroll
-    for (int t = 0; t < T; ++t)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int64_t c = c0 + 16 * u + 4 * kk;
-            const float *q = rowp[t] + c;
-            float4 v;
+    for (int g = 0; g < 4 * T; ++g) {
+        if constexpr (MEANS) {
+            const int b = (int)rows[4 * g + sub];
+            float x[4];
+            const int64_t left = rs.d - col;
+            if (!guarded)
+                row_load_full<true, 4>(rs, b, col, x);
+            else if (left > 0)
+                row_load<true, 4>(rs, b, col, left >= 4 ? 4 : (int)left, x);
+            else
+                x[0] = x[1] = x[2] = x[3] = 0.0f;
+            buf[g] = f32x4{x[0], x[1], x[2], x[3]};
+        } else {
+            const float *q = rs.base + rows[4 * g + sub] + col;
             if (!guarded) {
-                if constexpr (ALIGNED) {
-                    v = *reinterpret_cast<const float4 *>(q);
-                } else {
-                    v = make_float4(q[0], q[1], q[2], q[3]);
-                }
+                if constexpr (ALIGNED)
+                    buf[g] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(q));
+                else
+                    buf[g] = f32x4{q[0], q[1], q[2], q[3]};
             } else {
-                v = make_float4(c + 0 < d ? q[0] : 0.0f, c + 1 < d ? q[1] : 0.0f,
-                                c + 2 < d ? q[2] : 0.0f, c + 3 < d ? q[3] : 0.0f);
+                const int64_t d = rs.d;
+                buf[g] = f32x4{col + 0 < d ? q[0] : 0.0f, col + 1 < d ? q[1] : 0.0f,
+                               col + 2 < d ? q[2] : 0.0f, col + 3 < d ? q[3] : 0.0f};
             }
-            buf[t][u] = zero[t] ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : v;
         }
+    }
 }
 
+// Parks the fetched pieces in the wavefront's LDS tile.  wr: this lane's position for piece 0;
+// zero: bit g set = that logical row is the zero vector (a vote without majority), whose piece
+// is overwritten with zeros (rare: a uniform test keeps the common case free of it).
+// The tile is private to the wavefront, whose LDS instructions execute in order; the fences keep
+// the compiler from moving the reads of one tile across the writes of the next.
 template <int T>
-__device__ inline void gram_mfma_step(const float4 (&buf)[T][2], f32x4 (&acc)[tiles_for(T)])
+__device__ inline void tile_park(const f32x4 (&buf)[4 * T], unsigned zero, float *wr)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int g = 0; g < 4 * T; ++g) *reinterpret_cast<f32x4 *>(wr + g * 4 * kTilePitch) = buf[g];
+    if (__any(zero != 0u)) {
+#pragma unroll
+        for (int g = 0; g < 4 * T; ++g)
+            if ((zero >> g) & 1u)
+                *reinterpret_cast<f32x4 *>(wr + g * 4 * kTilePitch) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Accumulates the products of the parked tile.  rd: this lane's operand position for row tile 0,
+// s = 0; ref: the reference row's position for s = 0 (a row of zeros: nothing is subtracted).
+template <int T>
+__device__ inline void tile_products(const float *rd, const float *ref, f32x4 (&acc)[tiles_for(T)])
 {
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int s = 0; s < kTileCols / 16; ++s) {
+        const f32x4 c = *reinterpret_cast<const f32x4 *>(ref + 16 * s);
+        f32x4 a[T];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            float a[T];
+        for (int t = 0; t < T; ++t)
+            a[t] = *reinterpret_cast<const f32x4 *>(rd + t * 16 * kTilePitch + 16 * s) - c;
 #pragma unroll
-            for (int t = 0; t < T; ++t) {
-                const float4 v = buf[t][u];
-                a[t] = s == 0 ? v.x : (s == 1 ? v.y : (s == 2 ? v.z : v.w));
-            }
+        for (int e = 0; e < 4; ++e) {
             int tile = 0;
 #pragma unroll
             for (int ti = 0; ti < T; ++ti)
 #pragma unroll
                 for (int tj = ti; tj < T; ++tj, ++tile)
-                    acc[tile] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti], a[tj], acc[tile], 0, 0, 0);
+                    acc[tile] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti][e], a[tj][e], acc[tile], 0, 0, 0);
         }
+    }
 }
 
-template <int T, bool ALIGNED>
+// ref_keys (may be null: no centring): the keys the reference row is picked from.
+template <int T, bool ALIGNED, bool MEANS>
 __global__ __launch_bounds__(kBlock) void gram_mfma_kernel(RowSet rs, float *partials,
+                                                           const unsigned long long *ref_keys,
                                                            const int *run_if)
 {
     if (run_if && *run_if == 0) return;   // uniform
+    __shared__ __attribute__((aligned(16))) float lds_tiles[(kBlock / kWave) * 16 * T * kTilePitch];
+    __shared__ int64_t lds_rows[16 * T];
+    __shared__ __attribute__((aligned(16))) float lds_zeros[kTilePitch];
     const int count = rs.count;
     const int64_t d = rs.d;
     constexpr int NT = tiles_for(T);
     const int lane = threadIdx.x & (kWave - 1);
-    const int i = lane & 15, kk = lane >> 4;
-    const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const int wv = threadIdx.x / kWave;
+    const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + wv;
     const int64_t waves = (int64_t)gridDim.x * (kBlock / kWave);
 
-    const float *rowp[T];
-    bool zero[T];
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-        int row = 16 * t + i;
-        row = row < count ? row : count - 1;   // padded rows re-read the last row; never reported
-        const int64_t phys = rs.index ? (int64_t)rs.index[row] : (int64_t)row;
-        zero[t] = phys < 0;
-        rowp[t] = rs.base + (phys < 0 ? 0 : phys) * rs.ld;
+    // padded rows repeat the last row (their entries are never reported); a row that stands for
+    // the zero vector is fetched from row 0 and zeroed when it is parked
+    if ((int)threadIdx.x < 16 * T) {
+        int64_t row = (int)threadIdx.x < count ? (int)threadIdx.x : count - 1;
+        if constexpr (!MEANS) {
+            if (rs.index) row = rs.index[row];
+            row = row < 0 ? -1 : row * rs.ld;
+        }
+        lds_rows[threadIdx.x] = row;
     }
+    if (threadIdx.x < kTilePitch) lds_zeros[threadIdx.x] = 0.0f;
+    __syncthreads();
+    unsigned zero = 0u;
+#pragma unroll
+    for (int g = 0; g < 4 * T; ++g)
+        if (lds_rows[4 * g + (lane >> 4)] < 0) zero |= 1u << g;
+    __syncthreads();
+    if ((int)threadIdx.x < 16 * T && lds_rows[threadIdx.x] < 0) lds_rows[threadIdx.x] = 0;
+    __syncthreads();
+
+    float *tile = lds_tiles + (size_t)wv * (16 * T * kTilePitch);
+    float *wr = tile + (lane >> 4) * kTilePitch + 4 * (lane & 15);
+    const float *rd = tile + (lane & 15) * kTilePitch + 4 * (lane >> 4);
+    const float *ref = lds_zeros + 4 * (lane >> 4);
+    if (ref_keys != nullptr) ref = tile + pick_reference(ref_keys, count) * kTilePitch + 4 * (lane >> 4);
+
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    const int64_t full_steps = d / 32;   // 32 columns per step
-    float4 cur[T][2], nxt[T][2];
+    // fetch, park, fetch the next tile, multiply the parked one while those loads are in flight
+    const int64_t full_tiles = d / kTileCols;
+    const int64_t lane_col = 4 * (lane & 15);
+    f32x4 buf[4 * T];
     int64_t step = wave;
-    if (step < full_steps) gram_load_step<T, ALIGNED>(rowp, zero, step * 32, kk, d, false, cur);
-    while (step < full_steps) {
-        const int64_t next = step + waves;
-        if (next < full_steps) gram_load_step<T, ALIGNED>(rowp, zero, next * 32, kk, d, false, nxt);
-        gram_mfma_step<T>(cur, acc);
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) cur[t][u] = nxt[t][u];
-        step = next;
+    if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * kTileCols + lane_col, false, buf);
+    while (step < full_tiles) {
+        tile_park<T>(buf, zero, wr);
+        step += waves;
+        if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * kTileCols + lane_col, false, buf);
+        tile_products<T>(rd, ref, acc);
     }
-    // the ragged last step (d % 32 columns) goes to one wavefront
-    if ((d % 32) != 0 && wave == full_steps % waves) {
-        gram_load_step<T, ALIGNED>(rowp, zero, full_steps * 32, kk, d, true, cur);
-        gram_mfma_step<T>(cur, acc);
+    // the ragged last tile (d % kTileCols columns) goes to one wavefront
+    if ((d % kTileCols) != 0 && wave == full_tiles % waves) {
+        tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, full_tiles * kTileCols + lane_col, true, buf);
+        tile_park<T>(buf, zero, wr);
+        tile_products<T>(rd, ref, acc);
     }
     float *out = partials + wave * (int64_t)(NT * 256);
 #pragma unroll
@@ -330,14 +393,81 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
 }
 
 template <int T>
-hipError_t launch_mfma(const RowSet &rs, float *partials, int grid, bool aligned, const int *run_if,
-                       hipStream_t s)
+hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long long *keys, int grid,
+                       bool aligned, const int *run_if, hipStream_t s)
 {
     TraceScope t(run_if ? "gram_mfma_f32_if_redo" : "gram_mfma_f32", s);
-    if (aligned)
-        gram_mfma_kernel<T, true><<<grid, kBlock, 0, s>>>(rs, partials, run_if);
-    else
-        gram_mfma_kernel<T, false><<<grid, kBlock, 0, s>>>(rs, partials, run_if);
+    if (rs.means()) {
+        // block means formed on the fly: offered for the row counts a hierarchical step can have
+        if constexpr (T <= 2) {
+            if (!aligned) return hipErrorInvalidValue;
+            gram_mfma_kernel<T, true, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else if (aligned) {
+        gram_mfma_kernel<T, true, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+    } else {
+        gram_mfma_kernel<T, false, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+    }
+    return hipGetLastError();
+}
+
+// Workspace of the MFMA path: the wavefront tiles (room for the largest grid), the slice sums of
+// the first reduction level, the reference keys.
+struct MfmaWs {
+    float *tiles;
+    double *slices;
+    unsigned long long *keys;
+};
+MfmaWs carve_mfma(void *partials, int T)
+{
+    MfmaWs w;
+    const size_t elems = (size_t)tiles_for(T) * 256;
+    w.tiles = static_cast<float *>(partials);
+    w.slices = reinterpret_cast<double *>(w.tiles + (size_t)mfma_max_waves(T) * elems);
+    w.keys = reinterpret_cast<unsigned long long *>(w.slices + (size_t)kReduceSlices * elems);
+    return w;
+}
+
+// Gram matrix of more than 8 logical rows.  run_if (may be null): the kernels that touch the rows
+// run only if *run_if; alt (may be null): tiles left by the filter pass, added up instead of this
+// call's own unless *run_if.
+hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const float *alt,
+                     int alt_waves, double *Gm, hipStream_t s)
+{
+    const int T = (rs.count + 15) / 16;
+    if (T < 1 || T > 8) return hipErrorInvalidValue;
+    const MfmaWs w = carve_mfma(partials, T);
+    int grid = num_compute_units() * mfma_blocks_per_cu(T);
+    if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
+    const int64_t tiles = (rs.d + kTileCols - 1) / kTileCols;
+    const int64_t need = (tiles + kBlock / kWave - 1) / (kBlock / kWave);
+    if (grid > need) grid = (int)need;
+    hipError_t e = launch_reference_keys(ref_rows_of(rs), w.keys, run_if, s);
+    if (e != hipSuccess) return e;
+    bool aligned = row_vec_width(rs.base, rs.ld) == 4;
+    switch (T) {
+    case 1: e = launch_mfma<1>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    case 2: e = launch_mfma<2>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    case 3: e = launch_mfma<3>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    case 4: e = launch_mfma<4>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    case 5: e = launch_mfma<5>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    case 6: e = launch_mfma<6>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    case 7: e = launch_mfma<7>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    default: e = launch_mfma<8>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    }
+    if (e != hipSuccess) return e;
+    const int elems = tiles_for(T) * 256;
+    {
+        TraceScope t("gram_reduce", s);
+        gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
+            w.tiles, grid * (kBlock / kWave), elems, w.slices, alt, alt_waves, run_if);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    TraceScope t("gram_scatter", s);
+    gram_mfma_reduce2_kernel<<<(elems + 255) / 256, 256, 0, s>>>(w.slices, T, rs.count, Gm);
     return hipGetLastError();
 }
 
@@ -348,58 +478,20 @@ size_t gram_partial_bytes(int64_t count)
     if (count <= 8) return (size_t)kMaxGramWaves * (size_t)(count * (count + 1) / 2) * sizeof(double);
     const int T = (int)((count + 15) / 16);
     return (size_t)mfma_max_waves(T) * (size_t)tiles_for(T) * 256 * sizeof(float) +
-           (size_t)kReduceSlices * (size_t)tiles_for(T) * 256 * sizeof(double);
+           (size_t)kReduceSlices * (size_t)tiles_for(T) * 256 * sizeof(double) +
+           (size_t)kMaxCount * sizeof(unsigned long long);
 }
 
 hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s)
 {
-    if (rs.means() && rs.count > 8) return hipErrorInvalidValue;   // MFMA path reads rows only
-    const int cus = num_compute_units();
-    const int vec = row_vec_width(rs.base, rs.ld);
-    const int64_t count = rs.count, d = rs.d;
-    hipError_t e;
-    if (count <= 8) {
-        double *pp = static_cast<double *>(partials);
-        int grid = 0;
-        e = launch_small_any(rs, pp, nullptr, &grid, SmallSelect{}, nullptr, s);
-        if (e != hipSuccess) return e;
-        const int np = (int)(count * (count + 1) / 2);
-        TraceScope t("gram_reduce", s);
-        gram_small_reduce_kernel<<<np, kBlock, 0, s>>>(pp, grid, (int)count, Gm);
-        return hipGetLastError();
-    }
-    const int T = (int)((count + 15) / 16);
-    int grid = cus * mfma_blocks_per_cu(T);
-    if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
-    const int64_t steps = (d + 31) / 32;
-    const int64_t need = (steps + kBlock / kWave - 1) / (kBlock / kWave);
-    if (grid > need) grid = (int)need;
-    float *pp = static_cast<float *>(partials);
-    const bool aligned = vec == 4;
-    switch (T) {
-    case 1: e = launch_mfma<1>(rs, pp, grid, aligned, nullptr, s); break;
-    case 2: e = launch_mfma<2>(rs, pp, grid, aligned, nullptr, s); break;
-    case 3: e = launch_mfma<3>(rs, pp, grid, aligned, nullptr, s); break;
-    case 4: e = launch_mfma<4>(rs, pp, grid, aligned, nullptr, s); break;
-    case 5: e = launch_mfma<5>(rs, pp, grid, aligned, nullptr, s); break;
-    case 6: e = launch_mfma<6>(rs, pp, grid, aligned, nullptr, s); break;
-    case 7: e = launch_mfma<7>(rs, pp, grid, aligned, nullptr, s); break;
-    case 8: e = launch_mfma<8>(rs, pp, grid, aligned, nullptr, s); break;
-    default: return hipErrorInvalidValue;
-    }
+    if (rs.count > 8) return gram_mfma(rs, partials, nullptr, nullptr, 0, Gm, s);
+    double *pp = static_cast<double *>(partials);
+    int grid = 0;
+    hipError_t e = launch_small_any(rs, pp, nullptr, &grid, SmallSelect{}, nullptr, s);
     if (e != hipSuccess) return e;
-    const int elems = tiles_for(T) * 256;
-    // the slice sums live behind the largest possible set of wavefront partials
-    double *slices = reinterpret_cast<double *>(pp + (size_t)mfma_max_waves(T) * elems);
-    {
-        TraceScope t("gram_reduce", s);
-        gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
-            pp, grid * (kBlock / kWave), elems, slices, nullptr, 0, nullptr);
-    }
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    TraceScope t("gram_scatter", s);
-    gram_mfma_reduce2_kernel<<<(elems + 255) / 256, 256, 0, s>>>(slices, T, (int)count, Gm);
+    const int np = rs.count * (rs.count + 1) / 2;
+    TraceScope t("gram_reduce", s);
+    gram_small_reduce_kernel<<<np, kBlock, 0, s>>>(pp, grid, rs.count, Gm);
     return hipGetLastError();
 }
 
@@ -449,30 +541,11 @@ hipError_t launch_gram_cut(const double *full, int ld, int off, int count, doubl
 hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float *pass_partials,
                                   int pass_waves, const int *redo, double *Gm, hipStream_t s)
 {
-    if (rs.count < 1 || rs.count > 16 || pass_waves < 1 || pass_partials == nullptr || redo == nullptr)
+    if (rs.count <= 8 || rs.count > kPassGramMaxVotes || pass_waves < 1 || pass_partials == nullptr ||
+        redo == nullptr)
         return hipErrorInvalidValue;
-    constexpr int T = 1;
-    int grid = num_compute_units() * mfma_blocks_per_cu(T);
-    if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
-    const int64_t steps = (rs.d + 31) / 32;
-    const int64_t need = (steps + kBlock / kWave - 1) / (kBlock / kWave);
-    if (grid > need) grid = (int)need;
-    float *pp = static_cast<float *>(partials);
-    // only if some vote had no majority: the tiles of the pass are of no use then
-    hipError_t e = launch_mfma<T>(rs, pp, grid, row_vec_width(rs.base, rs.ld) == 4, redo, s);
-    if (e != hipSuccess) return e;
-    const int elems = tiles_for(T) * 256;
-    double *slices = reinterpret_cast<double *>(pp + (size_t)mfma_max_waves(T) * elems);
-    {
-        TraceScope t("gram_reduce", s);
-        gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
-            pp, grid * (kBlock / kWave), elems, slices, pass_partials, pass_waves, redo);
-    }
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    TraceScope t("gram_scatter", s);
-    gram_mfma_reduce2_kernel<<<(elems + 255) / 256, 256, 0, s>>>(slices, T, rs.count, Gm);
-    return hipGetLastError();
+    // the rows are touched only if some vote had no majority: the tiles of the pass are of no use then
+    return gram_mfma(rs, partials, redo, pass_partials, pass_waves, Gm, s);
 }
 
 hipError_t launch_small_redo(const RowSet &rs, void *partials, const int *redo, double *Gm, int krum_f,

@@ -12,7 +12,7 @@
 //   geometric median       : Weiszfeld's iteration streamed over the rows, one launch per
 //                            iteration (weiszfeld_rows_kernel).  16 lanes share a row; weights,
 //                            distances and sums are fp64; every reduction runs in a fixed order.
-#include "rows.cuh"
+#include "rows.h"
 
 namespace detox {
 namespace {

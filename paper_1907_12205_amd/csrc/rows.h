@@ -197,4 +197,53 @@ __device__ inline double wave_sum(double v)
     return (row[0] + row[1]) + (row[2] + row[3]);
 }
 
+// Minimum of a 64-bit unsigned value over the 64 lanes of a wavefront, in every lane (all lanes
+// active): lane pairs, quads, half rows, rows by cross-lane moves, then the four row minima.
+template <int CTRL>
+__device__ inline unsigned long long min_paired_lane(unsigned long long v)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)v, CTRL, 0xf, 0xf, false);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(v >> 32), CTRL, 0xf, 0xf, false);
+    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    return o < v ? o : v;
+}
+__device__ inline unsigned long long wave_min_u64(unsigned long long v)
+{
+    v = min_paired_lane<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = min_paired_lane<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = min_paired_lane<0x141>(v);   // row_half_mirror
+    v = min_paired_lane<0x140>(v);   // row_mirror
+    unsigned long long m = ~0ull;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, 16 * q);
+        const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), 16 * q);
+        const unsigned long long r = ((unsigned long long)hi << 32) | lo;
+        m = r < m ? r : m;
+    }
+    return m;
+}
+
+
+// ---- reference row of a row set ---------------------------------------------------------------
+// Squared distances are formed from fp32 Gram matrices as G_aa + G_bb - 2 G_ab, which loses the
+// distance when the rows share a component much larger than their spread.  They do not change
+// when one vector is subtracted from every row, so the fp32 kernels subtract a reference row as
+// they load.  The reference is picked by a pass over a sample of the columns (refrow.hip): every
+// logical row gets a 64-bit key
+//     (number of non-finite sample distances) << 40 | bits(sum of the finite distances) << 8 | row
+// and the row with the smallest key -- the sample medoid, a member of the cluster that holds more
+// than half of the rows whenever there is one -- is the reference.  All lanes must be active.
+__device__ inline int pick_reference(const unsigned long long *keys, int count)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    unsigned long long k = ~0ull;
+    if (lane < count) k = keys[lane];
+    if (lane + kWave < count) {
+        const unsigned long long k2 = keys[lane + kWave];
+        k = k2 < k ? k2 : k;
+    }
+    return (int)(wave_min_u64(k) & 0xffull);
+}
+
 }  // namespace detox

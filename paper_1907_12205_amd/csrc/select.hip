@@ -1,7 +1,7 @@
 // The count x count part of the robust aggregators (scores, selections, Weiszfeld weights), run
 // by a single workgroup in fp64 so that no host round trip interrupts the stream, and the two
 // streaming kernels that turn a selection / a weight vector into the output d-vector.
-#include "rows.cuh"
+#include "rows.h"
 
 namespace detox {
 namespace {
@@ -92,33 +92,6 @@ __global__ __launch_bounds__(kRowThreads) void top_m_kernel(const double *scores
     for (int c = 0; c < count; ++c)
         if (c != a && score_before(s[c], c, s[a], a)) ++rank;
     if (rank < m) selected[rank] = a;
-}
-
-// Minimum of a 64-bit unsigned value over the 64 lanes of a wavefront, in every lane (all lanes
-// active): lane pairs, quads, half rows, rows by cross-lane moves, then the four row minima.
-template <int CTRL>
-__device__ inline unsigned long long min_paired_lane(unsigned long long v)
-{
-    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)v, CTRL, 0xf, 0xf, false);
-    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(v >> 32), CTRL, 0xf, 0xf, false);
-    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
-    return o < v ? o : v;
-}
-__device__ inline unsigned long long wave_min_u64(unsigned long long v)
-{
-    v = min_paired_lane<0xB1>(v);    // quad_perm [1,0,3,2]
-    v = min_paired_lane<0x4E>(v);    // quad_perm [2,3,0,1]
-    v = min_paired_lane<0x141>(v);   // row_half_mirror
-    v = min_paired_lane<0x140>(v);   // row_mirror
-    unsigned long long m = ~0ull;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, 16 * q);
-        const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), 16 * q);
-        const unsigned long long r = ((unsigned long long)hi << 32) | lo;
-        m = r < m ? r : m;
-    }
-    return m;
 }
 
 // Position of the n-th set bit (n >= 1) of the 128-bit mask hi:lo, or -1 if fewer are set.

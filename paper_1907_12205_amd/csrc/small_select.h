@@ -3,7 +3,7 @@
 // so that the common case needs one small launch instead of four.
 #pragma once
 
-#include "rows.cuh"
+#include "rows.h"
 
 namespace detox {
 

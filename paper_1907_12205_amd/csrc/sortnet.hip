@@ -9,8 +9,8 @@
 // is used the compiler drops the comparators that cannot reach it.
 #include <type_traits>
 
-#include "rows.cuh"
-#include "sortnet.cuh"
+#include "rows.h"
+#include "sortnet.h"
 
 namespace detox {
 namespace {

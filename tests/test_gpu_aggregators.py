@@ -168,3 +168,78 @@ def test_trimmed_mean(dx, count, g):
         assert rel_l2(got, ref) <= TOL
         if 2 * g == count - 1:          # a single value survives: the median, bit for bit
             assert got.tobytes() == oracle.coord_median(X).tobytes()
+
+
+# ---- rows that share a component much larger than their spread ------------------------------------
+# Honest gradients are a common gradient plus noise (the case Krum is defined for); distances do not
+# depend on the common part, and neither may the fp32 Gram path (more than 8 rows).
+OFFSET_COUNTS = [9, 16, 45, 105]
+OFFSETS = [10, 100, 1000]       # common component, in units of the spread
+
+
+@pytest.mark.parametrize("k", OFFSETS)
+@pytest.mark.parametrize("count", OFFSET_COUNTS)
+def test_pairwise_sqdist_with_a_common_offset(dx, count, k):
+    d, sigma = 20011, 0.03
+    X = workloads.distinct_rows(2000 + count, count, d, sigma=sigma, mean=k * sigma)
+    ref = oracle.pairwise_sqdist(X)
+    for ld, off in ((None, 0), ((d + 63) // 64 * 64, 0), (None, 1)):
+        D = host(dx.robust_pairwise_sqdist(dev_matrix(X, ld, off)))
+        assert (D == D.T).all() and (np.diag(D) == 0).all()
+        assert np.abs(D - ref).max() <= 2e-6 * ref.max(), (count, k, ld, off)
+
+
+@pytest.mark.parametrize("k", OFFSETS)
+@pytest.mark.parametrize("count", OFFSET_COUNTS)
+def test_selections_and_geomedian_with_a_common_offset(dx, count, k):
+    d, sigma = 30011, 0.03
+    X = workloads.distinct_rows(3000 + count, count, d, sigma=sigma, mean=k * sigma)
+    X[count // 2] += np.float32(0.01)
+    f = (count - 3) // 4
+    _multikrum_case(dx, X, f, count - f)
+    ref_out, ref_sel = oracle.bulyan(X, f)
+    out, sel = dx.robust_bulyan(dev_matrix(X), f)
+    assert host(sel).tolist() == ref_sel.tolist()
+    assert rel_l2(host(out), ref_out) <= TOL
+    X[1] = np.float32(-5.0)                              # a far outlier as well
+    ref = oracle.geomedian(X, iters=30, eps=1e-8)
+    got = host(dx.robust_geomedian(dev_matrix(X), iters=30, eps=1e-8))
+    assert rel_l2(got, ref) <= TOL
+
+
+@pytest.mark.parametrize("count", OFFSET_COUNTS)
+def test_selection_does_not_change_under_translation(dx, count):
+    """GPU twin of the oracle's translation pin: adding one vector to every row (exactly, here:
+    small integers plus multiples of 1/8) leaves Multi-Krum's and Bulyan's selections unchanged."""
+    d = 8192
+    X = workloads.integer_rows(count, count, d, -8, 8) / np.float32(8.0)
+    f = (count - 3) // 4
+    sel0 = host(dx.robust_multikrum(dev_matrix(X), f, count - f)[1]).tolist()
+    bul0 = host(dx.robust_bulyan(dev_matrix(X), f)[1]).tolist()
+    assert sel0 == oracle.multikrum(X, f, count - f)[1].tolist()
+    assert bul0 == oracle.bulyan(X, f)[1].tolist()
+    shift = (workloads.integer_rows(99, 1, d, -4096, 4096) / np.float32(8.0))[0]
+    Y = X + shift                                         # exact in fp32
+    assert ((Y - shift) == X).all()
+    assert host(dx.robust_multikrum(dev_matrix(Y), f, count - f)[1]).tolist() == sel0
+    assert host(dx.robust_bulyan(dev_matrix(Y), f)[1]).tolist() == bul0
+
+
+@pytest.mark.parametrize("bad", ["far", "nan", "inf"])
+@pytest.mark.parametrize("count", [15, 45])
+def test_reference_row_is_not_taken_from_the_outliers(dx, count, bad):
+    """Row 0 (and a few more) far away, NaN or infinite while the others share a large common
+    component: the distances among the clean rows must keep their accuracy."""
+    d, sigma = 20011, 0.03
+    X = workloads.distinct_rows(4000 + count, count, d, sigma=sigma, mean=1000 * sigma)
+    nbad = max(1, count // 5)
+    for i in range(nbad):
+        X[2 * i] = {"far": np.float32(-100.0 * (i + 1)), "nan": np.float32(np.nan), "inf": np.float32(np.inf)}[bad]
+    clean = [i for i in range(count) if not (i % 2 == 0 and i // 2 < nbad)]
+    ref = oracle.pairwise_sqdist(X)
+    D = host(dx.robust_pairwise_sqdist(dev_matrix(X)))
+    sub, rsub = D[np.ix_(clean, clean)], ref[np.ix_(clean, clean)]
+    assert np.abs(sub - rsub).max() <= 2e-6 * rsub.max()
+    if bad == "far":
+        assert np.abs(D - ref).max() <= 2e-6 * ref.max()
+        _multikrum_case(dx, X, nbad, count - nbad - 2)

@@ -305,3 +305,24 @@ def test_gram_of_the_votes_formed_in_the_filter_pass(dx, groups, r, aggregator):
                       m=spec.get("m", -1), materialise=False)
         names = [n for n, _ in tr.records()]
     assert "filter_votes_gram" in names and "gram_mfma_f32" not in names
+
+
+@pytest.mark.parametrize("k", [10, 100, 1000])
+@pytest.mark.parametrize("aggregator", ["multikrum", "bulyan", "geomedian"])
+def test_step_over_15_votes_with_a_common_offset(dx, aggregator, k):
+    """The Gram matrix of the 15 votes formed in the filter pass, on votes that share a component
+    k times their spread, with Byzantine members far away: selections as the oracle's."""
+    d, sigma = 70_003, 0.03
+    rng = np.random.default_rng(k)
+    base = (rng.standard_normal((15, d)) * sigma + k * sigma).astype(np.float32)
+    G = np.repeat(base, 3, axis=0)
+    G[0] = -50.0; G[3 * 7 + 2] = 80.0                    # outvoted
+    G[3 * 11] = G[3 * 11 + 1] = 1000.0                   # a Byzantine vote survives the filter
+    w = workloads.Workload("votes", 45, 3, 4, d, base, {})
+    spec = dict(B=15, aggregator=aggregator)
+    if aggregator == "multikrum":
+        spec.update(f=2, m=11)
+    if aggregator == "bulyan":
+        spec.update(f=2)
+    _run(dx, w, spec, G=G, ld=(d + 63) // 64 * 64, materialise=False)
+    _run(dx, w, spec, G=G, materialise=False, vote_perm=rng.permutation(15).astype(np.int32))
