@@ -54,11 +54,11 @@ size_t pass_gram_bytes(int64_t count)
 }
 
 // Gram partials + Gram matrix + the count x count scratch of the selection kernels.
-size_t aggregator_ws_bytes(int64_t count)
+size_t aggregator_ws_bytes(int64_t count, int64_t d)
 {
     if (count < 1 || count > kMaxCount) return 0;
     const size_t c2 = (size_t)(count * count);
-    return round_up(gram_partial_bytes(count)) + round_up(c2 * sizeof(double)) * 3 +
+    return round_up(gram_partial_bytes(count, d)) + round_up(c2 * sizeof(double)) * 3 +
            round_up(c2 * sizeof(int32_t)) + round_up((size_t)count * sizeof(double)) * 2 +
            round_up((size_t)count * sizeof(int32_t)) * 2 + round_up(pass_gram_bytes(count));
 }
@@ -72,12 +72,12 @@ struct AggWs {
     float *pass_gram;     // tiles of the filter pass (9..16 rows), else null
 };
 
-AggWs carve_aggregator(void *ws, int64_t count)
+AggWs carve_aggregator(void *ws, int64_t count, int64_t d)
 {
     Carver c(ws);
     AggWs a;
     const size_t c2 = (size_t)(count * count);
-    a.partials = c.take<char>(gram_partial_bytes(count));
+    a.partials = c.take<char>(gram_partial_bytes(count, d));
     a.Gm = c.take<double>(c2);
     a.sc.D = c.take<double>(c2);
     a.sc.sorted = c.take<double>(c2);
@@ -125,7 +125,7 @@ hipError_t gram_for(const RowSet &rs, const AggWs &a, const FusedGram &fg, hipSt
 int multikrum_impl(const RowSet &rs, int f, int m, float *out, int32_t *selected, double *scores,
                    void *ws, const FusedGram &fg, hipStream_t s)
 {
-    AggWs a = carve_aggregator(ws, rs.count);
+    AggWs a = carve_aggregator(ws, rs.count, rs.d);
     hipError_t e;
     if (fg.reduced) {
         // scores and selection came with the finalize kernel; repeat them only if *redo
@@ -142,7 +142,7 @@ int multikrum_impl(const RowSet &rs, int f, int m, float *out, int32_t *selected
 int bulyan_impl(const RowSet &rs, int f, float *out, int32_t *selected, void *ws,
                 const FusedGram &fg, hipStream_t s)
 {
-    AggWs a = carve_aggregator(ws, rs.count);
+    AggWs a = carve_aggregator(ws, rs.count, rs.d);
     const int theta = rs.count - 2 * f, beta = theta - 2 * f;
     hipError_t e = gram_for(rs, a, fg, s);
     if (e == hipSuccess) e = launch_bulyan_select(a.Gm, rs.count, f, a.sc, selected, s);
@@ -153,7 +153,7 @@ int bulyan_impl(const RowSet &rs, int f, float *out, int32_t *selected, void *ws
 int geomedian_impl(const RowSet &rs, int iters, double eps, float *out, void *ws,
                    const FusedGram &fg, hipStream_t s)
 {
-    AggWs a = carve_aggregator(ws, rs.count);
+    AggWs a = carve_aggregator(ws, rs.count, rs.d);
     hipError_t e = gram_for(rs, a, fg, s);
     if (e == hipSuccess) e = launch_weiszfeld(a.Gm, rs.count, iters, eps, a.sc.weights, s);
     if (e == hipSuccess) e = launch_weighted_sum(rs, a.sc.weights, out, s);
@@ -231,10 +231,10 @@ size_t detox_workspace_bytes(int op, int64_t count, int64_t d, int64_t aux)
     case DETOX_OP_PAIRWISE_SQDIST:
     case DETOX_OP_MULTIKRUM:
     case DETOX_OP_BULYAN:
-    case DETOX_OP_GEOMEDIAN: return aggregator_ws_bytes(count);
+    case DETOX_OP_GEOMEDIAN: return d < 1 ? 0 : aggregator_ws_bytes(count, d);
     case DETOX_OP_STEP: {
         if (aux < 1 || aux > kMaxCount) return 0;
-        return filter_bytes(count) + aggregator_ws_bytes(aux);
+        return filter_bytes(count) + aggregator_ws_bytes(aux, d);
     }
     case DETOX_OP_BLOCK_MEAN:
     case DETOX_OP_COORD_MEDIAN: return 0;
@@ -297,9 +297,9 @@ int robust_pairwise_sqdist(const float *X, int64_t count, int64_t d, int64_t ld,
                            void *ws, size_t ws_bytes, void *stream)
 {
     if (!matrix_ok(X, count, d, ld) || !D || count > kMaxCount) return DETOX_EINVAL;
-    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count, d))) return DETOX_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    AggWs a = carve_aggregator(ws, count);
+    AggWs a = carve_aggregator(ws, count, d);
     hipError_t e = launch_gram(direct_rows(X, count, d, ld), a.partials, a.Gm, s);
     if (e == hipSuccess) e = launch_sqdist_from_gram(a.Gm, count, D, s);
     return status_of(e);
@@ -312,7 +312,7 @@ int robust_multikrum(const float *X, int64_t count, int64_t d, int64_t ld, int f
     if (!matrix_ok(X, count, d, ld) || !out || !selected || count > kMaxCount || f < 0)
         return DETOX_EINVAL;
     if (count < 2 * (int64_t)f + 3 || m < 1 || m > count - f) return DETOX_EPRECOND;
-    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count, d))) return DETOX_EWORKSPACE;
     return multikrum_impl(direct_rows(X, count, d, ld), f, m, out, selected, scores, ws, FusedGram{},
                           static_cast<hipStream_t>(stream));
 }
@@ -323,7 +323,7 @@ int robust_bulyan(const float *X, int64_t count, int64_t d, int64_t ld, int f, f
     if (!matrix_ok(X, count, d, ld) || !out || !selected || count > kMaxCount || f < 0)
         return DETOX_EINVAL;
     if (count < 4 * (int64_t)f + 3) return DETOX_EPRECOND;
-    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count, d))) return DETOX_EWORKSPACE;
     return bulyan_impl(direct_rows(X, count, d, ld), f, out, selected, ws, FusedGram{},
                        static_cast<hipStream_t>(stream));
 }
@@ -350,7 +350,7 @@ int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
 {
     if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount || iters < 0 || !(eps > 0.0))
         return DETOX_EINVAL;
-    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count))) return DETOX_EWORKSPACE;
+    if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count, d))) return DETOX_EWORKSPACE;
     return geomedian_impl(direct_rows(X, count, d, ld), iters, eps, out, ws, FusedGram{},
                           static_cast<hipStream_t>(stream));
 }
@@ -409,13 +409,13 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     }
     if (agg == DETOX_AGG_GEOMEDIAN && (iters < 0 || !(eps > 0.0))) return DETOX_EINVAL;
     const size_t fbytes = filter_bytes(groups);
-    const size_t abytes = aggregator_ws_bytes(B);
+    const size_t abytes = aggregator_ws_bytes(B, d);
     if (!ws_ok(ws, ws_bytes, fbytes + abytes)) return DETOX_EWORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     void *aws = static_cast<char *>(ws) + fbytes;
-    const AggWs aw = carve_aggregator(aws, B);
+    const AggWs aw = carve_aggregator(aws, B, d);
     FilterParams p{G, d, ld, r, group_rows, vote_perm, groups, B, Zhat, ldo,
                    fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, out,
                    agg == DETOX_AGG_TRIMMED_MEAN ? f : 0, aw.pass_gram};
@@ -493,18 +493,18 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
     }
     const size_t fbytes = filter_bytes(groups);
     const size_t tbytes = round_up((size_t)groups * sizeof(int32_t));
-    const size_t base_bytes = fbytes + tbytes + aggregator_ws_bytes(largest);
+    const size_t base_bytes = fbytes + tbytes + aggregator_ws_bytes(largest, d);
     if (!ws_ok(ws, ws_bytes, base_bytes)) return DETOX_EWORKSPACE;
     // 9..16 votes and room for one more aggregator workspace (of n/r rows): the Gram matrix of all
     // votes comes out of the filter pass and every vote group cuts its own matrix out of it
-    const size_t all_bytes = pass_gram_bytes(groups) ? aggregator_ws_bytes(groups) : 0;
+    const size_t all_bytes = pass_gram_bytes(groups) ? aggregator_ws_bytes(groups, d) : 0;
     const bool in_pass = all_bytes != 0 && ws_bytes >= base_bytes + all_bytes;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     void *aws = static_cast<char *>(ws) + fbytes + tbytes;
     AggWs all{};
-    if (in_pass) all = carve_aggregator(static_cast<char *>(aws) + aggregator_ws_bytes(largest), groups);
+    if (in_pass) all = carve_aggregator(static_cast<char *>(aws) + aggregator_ws_bytes(largest, d), groups, d);
     FilterParams p{G, d, ld, r, group_rows, in_pass ? vote_perm : nullptr, groups, groups, nullptr, 0,
                    fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0,
                    in_pass ? all.pass_gram : nullptr};

@@ -178,7 +178,7 @@ hipError_t launch_many_geomedian(const float *X, int64_t count, int64_t d, int64
                                  double eps, void *ws, float *out, hipStream_t s);
 
 // ---- gram.hip --------------------------------------------------------------
-size_t gram_partial_bytes(int64_t count);
+size_t gram_partial_bytes(int64_t count, int64_t d);
 // Gram matrix Gm[a][b] = <x_a, x_b> of the logical rows (count x count doubles, full, symmetric).
 hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s);
 // count <= 16 rows whose Gram tiles the filter pass has written (pass_waves wavefront tiles in

@@ -22,10 +22,9 @@ constexpr int kMaxGramWaves = 4096;   // upper bound used to size the workspace
 
 __host__ __device__ constexpr int tiles_for(int T) { return T * (T + 1) / 2; }
 
-// Workgroups (of 4 wavefronts) per CU for the MFMA kernel, from sweeps on MI355X: few row
-// tiles mean few loads in flight per wavefront, so more wavefronts are needed to cover the HBM
-// latency; from 5 row tiles on the kernel is MFMA-bound and one wavefront per SIMD is best.
-constexpr int mfma_blocks_per_cu(int T) { return T <= 2 ? 4 : (T <= 4 ? 3 : 1); }
+// Workgroups (of 4 wavefronts) per CU for the MFMA kernel: what its LDS tiles and registers let
+// stay resident (the kernel's launch bounds hold the register count to these numbers).
+constexpr int mfma_blocks_per_cu(int T) { return T <= 2 ? 4 : (T <= 3 ? 3 : 2); }
 // Bound on the wavefront partials (sizes the workspace; assumes at most 256 CUs, more are clamped).
 constexpr int mfma_max_waves(int T) { return 256 * mfma_blocks_per_cu(T) * (kBlock / kWave); }
 
@@ -135,7 +134,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double 
 // are slices of X in the same layout, so one register per row tile feeds both sides.  The
 // accumulator of tile (ti, tj) holds C[4*(l/16)+v][l%16] in component v of lane l.
 //
-// A wavefront works on tiles of kTileCols columns of all (padded) rows.  It fetches a tile with
+// A wavefront works on tiles of 64 (or 32) columns of all (padded) rows.  It fetches a tile with
 // loads that are contiguous along the rows (16 lanes x 16 bytes = one 256-byte segment of a row,
 // four rows per instruction, non-temporal), parks it in an LDS tile of its own and reads the MFMA
 // operands back from there: lane (i, kk) takes 16 bytes of row 16t+i at columns 16s+4kk, whose
@@ -144,22 +143,37 @@ __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double 
 // before the current one is consumed.  The reference row's segment is read from the same LDS
 // tile and subtracted from every operand before the products (rows.h, pick_reference).
 // ---------------------------------------------------------------------------------------
-constexpr int kTileCols = 64;
-constexpr int kTilePitch = kTileCols + 4;   // floats between LDS rows: the 16-byte reads of 16 rows hit 64 banks
+constexpr int kChainCols = 2048;   // products an MFMA accumulator takes in before it is emptied
 
-// Fetches this lane's 4T pieces of a tile: piece g is 16 bytes of logical row 4g + lane/16 at
-// column `col` (= tile column + 4*(lane%16)).  rows: LDS table with, for every padded logical row,
-// the element offset in rs.base of the row behind it (a zero or padded row: some valid row); with
-// MEANS, the logical row itself.
+// Columns per tile: 64 (one 256-byte segment of every row per tile, four rows per load
+// instruction) while the kernel is bound by memory; 32 and then 16 (eight and sixteen rows per
+// instruction) from five and seven row tiles on, where the matrix cores are the bound and the
+// registers are needed for accumulators.
+constexpr int tile_cols(int T) { return T <= 4 ? 64 : (T <= 6 ? 32 : 16); }
+constexpr int tile_pitch(int T) { return tile_cols(T) + 4; }   // floats between LDS rows: the 16-byte reads of 16 rows hit 64 banks
+
+// Geometry of a tile of COLS columns: a load instruction covers RPI rows (COLS/4 lanes x 16 bytes
+// each), a lane fetches NP pieces per tile: piece g is 16 bytes of logical row RPI*g + lane/LPR at
+// column 4*(lane%LPR) of the tile.
+template <int T>
+struct TileGeo {
+    static constexpr int COLS = tile_cols(T), PITCH = tile_pitch(T);
+    static constexpr int LPR = COLS / 4, RPI = kWave / LPR, NP = 16 * T / RPI;
+};
+
+// Fetches this lane's pieces of the tile whose first column is col - 4*(lane%LPR).  rows: LDS
+// table with, for every padded logical row, the element offset in rs.base of the row behind it
+// (a zero or padded row: some valid row); with MEANS, the logical row itself.
 template <int T, bool ALIGNED, bool MEANS>
 __device__ inline void tile_fetch(const RowSet &rs, const int64_t *rows, int64_t col, bool guarded,
-                                  f32x4 (&buf)[4 * T])
+                                  f32x4 (&buf)[TileGeo<T>::NP])
 {
-    const int sub = (int)((threadIdx.x & (kWave - 1)) >> 4);
+    using G = TileGeo<T>;
+    const int sub = (int)(threadIdx.x & (kWave - 1)) / G::LPR;
 #pragma unroll
-    for (int g = 0; g < 4 * T; ++g) {
+    for (int g = 0; g < G::NP; ++g) {
         if constexpr (MEANS) {
-            const int b = (int)rows[4 * g + sub];
+            const int b = (int)rows[G::RPI * g + sub];
             float x[4];
             const int64_t left = rs.d - col;
             if (!guarded)
@@ -170,7 +184,7 @@ __device__ inline void tile_fetch(const RowSet &rs, const int64_t *rows, int64_t
                 x[0] = x[1] = x[2] = x[3] = 0.0f;
             buf[g] = f32x4{x[0], x[1], x[2], x[3]};
         } else {
-            const float *q = rs.base + rows[4 * g + sub] + col;
+            const float *q = rs.base + rows[G::RPI * g + sub] + col;
             if (!guarded) {
                 if constexpr (ALIGNED)
                     buf[g] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(q));
@@ -191,17 +205,18 @@ __device__ inline void tile_fetch(const RowSet &rs, const int64_t *rows, int64_t
 // The tile is private to the wavefront, whose LDS instructions execute in order; the fences keep
 // the compiler from moving the reads of one tile across the writes of the next.
 template <int T>
-__device__ inline void tile_park(const f32x4 (&buf)[4 * T], unsigned zero, float *wr)
+__device__ inline void tile_park(const f32x4 (&buf)[TileGeo<T>::NP], unsigned long long zero, float *wr)
 {
+    using G = TileGeo<T>;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int g = 0; g < 4 * T; ++g) *reinterpret_cast<f32x4 *>(wr + g * 4 * kTilePitch) = buf[g];
-    if (__any(zero != 0u)) {
+    for (int g = 0; g < G::NP; ++g) *reinterpret_cast<f32x4 *>(wr + g * G::RPI * G::PITCH) = buf[g];
+    if (__any(zero != 0ull)) {
 #pragma unroll
-        for (int g = 0; g < 4 * T; ++g)
-            if ((zero >> g) & 1u)
-                *reinterpret_cast<f32x4 *>(wr + g * 4 * kTilePitch) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int g = 0; g < G::NP; ++g)
+            if ((zero >> g) & 1ull)
+                *reinterpret_cast<f32x4 *>(wr + g * G::RPI * G::PITCH) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -212,13 +227,14 @@ __device__ inline void tile_park(const f32x4 (&buf)[4 * T], unsigned zero, float
 template <int T>
 __device__ inline void tile_products(const float *rd, const float *ref, f32x4 (&acc)[tiles_for(T)])
 {
+    using G = TileGeo<T>;
 #pragma unroll
-    for (int s = 0; s < kTileCols / 16; ++s) {
+    for (int s = 0; s < G::COLS / 16; ++s) {
         const f32x4 c = *reinterpret_cast<const f32x4 *>(ref + 16 * s);
         f32x4 a[T];
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            a[t] = *reinterpret_cast<const f32x4 *>(rd + t * 16 * kTilePitch + 16 * s) - c;
+            a[t] = *reinterpret_cast<const f32x4 *>(rd + t * 16 * G::PITCH + 16 * s) - c;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             int tile = 0;
@@ -232,15 +248,17 @@ __device__ inline void tile_products(const float *rd, const float *ref, f32x4 (&
 }
 
 // ref_keys (may be null: no centring): the keys the reference row is picked from.
+//   chain_tiles, flushes: T >= 5 only (see below).
 template <int T, bool ALIGNED, bool MEANS>
-__global__ __launch_bounds__(kBlock) void gram_mfma_kernel(RowSet rs, float *partials,
-                                                           const unsigned long long *ref_keys,
-                                                           const int *run_if)
+__global__ __launch_bounds__(kBlock, (T <= 3 ? 3 : 2)) void gram_mfma_kernel(
+    RowSet rs, float *partials, const unsigned long long *ref_keys, const int *run_if, int chain_tiles,
+    int flushes)
 {
     if (run_if && *run_if == 0) return;   // uniform
-    __shared__ __attribute__((aligned(16))) float lds_tiles[(kBlock / kWave) * 16 * T * kTilePitch];
+    using G = TileGeo<T>;
+    __shared__ __attribute__((aligned(16))) float lds_tiles[(kBlock / kWave) * 16 * T * G::PITCH];
     __shared__ int64_t lds_rows[16 * T];
-    __shared__ __attribute__((aligned(16))) float lds_zeros[kTilePitch];
+    __shared__ __attribute__((aligned(16))) float lds_zeros[G::PITCH];
     const int count = rs.count;
     const int64_t d = rs.d;
     constexpr int NT = tiles_for(T);
@@ -259,49 +277,87 @@ __global__ __launch_bounds__(kBlock) void gram_mfma_kernel(RowSet rs, float *par
         }
         lds_rows[threadIdx.x] = row;
     }
-    if (threadIdx.x < kTilePitch) lds_zeros[threadIdx.x] = 0.0f;
+    if (threadIdx.x < G::PITCH) lds_zeros[threadIdx.x] = 0.0f;
     __syncthreads();
-    unsigned zero = 0u;
+    unsigned long long zero = 0ull;
 #pragma unroll
-    for (int g = 0; g < 4 * T; ++g)
-        if (lds_rows[4 * g + (lane >> 4)] < 0) zero |= 1u << g;
+    for (int g = 0; g < G::NP; ++g)
+        if (lds_rows[G::RPI * g + lane / G::LPR] < 0) zero |= 1ull << g;
     __syncthreads();
     if ((int)threadIdx.x < 16 * T && lds_rows[threadIdx.x] < 0) lds_rows[threadIdx.x] = 0;
     __syncthreads();
 
-    float *tile = lds_tiles + (size_t)wv * (16 * T * kTilePitch);
-    float *wr = tile + (lane >> 4) * kTilePitch + 4 * (lane & 15);
-    const float *rd = tile + (lane & 15) * kTilePitch + 4 * (lane >> 4);
+    float *tile = lds_tiles + (size_t)wv * (16 * T * G::PITCH);
+    float *wr = tile + (lane / G::LPR) * G::PITCH + 4 * (lane % G::LPR);
+    const float *rd = tile + (lane & 15) * G::PITCH + 4 * (lane >> 4);
     const float *ref = lds_zeros + 4 * (lane >> 4);
-    if (ref_keys != nullptr) ref = tile + pick_reference(ref_keys, count) * kTilePitch + 4 * (lane >> 4);
+    if (ref_keys != nullptr) ref = tile + pick_reference(ref_keys, count) * G::PITCH + 4 * (lane >> 4);
 
+    // The matrix cores add the products of an instruction to the accumulator with a few guard
+    // bits and no more, which shows as a small bias that grows with the number of products an
+    // accumulator takes in (about 1.6e-10 of the sum per product).  So the accumulators are
+    // emptied now and then.  Up to four row tiles: every kChainCols columns, with ordinary rounded
+    // additions, into a second set of registers.  From five row tiles on, where registers are
+    // short: every chain_tiles tiles into one more slot of the partial sums, `flushes` slots per
+    // wavefront in all (slot f of wavefront w is number f * waves + w; all of them are written).
+    constexpr bool kRegisterTotals = T <= 4;
     f32x4 acc[NT];
+    f32x4 total[kRegisterTotals ? NT : 1];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int t = 0; t < (kRegisterTotals ? NT : 1); ++t) total[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (kRegisterTotals) chain_tiles = kChainCols / G::COLS;
+    int flushed = 0;
+    auto empty_accumulators = [&]() {
+        if constexpr (kRegisterTotals) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) total[t] += acc[t];
+        } else {
+            // C[4*(l/16)+v][l%16] of tile t at [t][v][l]
+            float *out = partials + ((int64_t)flushed * waves + wave) * (NT * 256) + lane;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) out[t * 256 + v * 64] = acc[t][v];
+            ++flushed;
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    };
 
     // fetch, park, fetch the next tile, multiply the parked one while those loads are in flight
-    const int64_t full_tiles = d / kTileCols;
-    const int64_t lane_col = 4 * (lane & 15);
-    f32x4 buf[4 * T];
+    const int64_t full_tiles = d / G::COLS;
+    const int64_t lane_col = 4 * (lane % G::LPR);
+    f32x4 buf[G::NP];
     int64_t step = wave;
-    if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * kTileCols + lane_col, false, buf);
+    int chain = 0;
+    if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
     while (step < full_tiles) {
         tile_park<T>(buf, zero, wr);
         step += waves;
-        if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * kTileCols + lane_col, false, buf);
+        if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
         tile_products<T>(rd, ref, acc);
+        if (++chain == chain_tiles && (kRegisterTotals || flushed + 1 < flushes)) {   // uniform
+            chain = 0;
+            empty_accumulators();
+        }
     }
-    // the ragged last tile (d % kTileCols columns) goes to one wavefront
-    if ((d % kTileCols) != 0 && wave == full_tiles % waves) {
-        tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, full_tiles * kTileCols + lane_col, true, buf);
+    // the ragged last tile (d % COLS columns) goes to one wavefront
+    if ((d % G::COLS) != 0 && wave == full_tiles % waves) {
+        tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, full_tiles * G::COLS + lane_col, true, buf);
         tile_park<T>(buf, zero, wr);
         tile_products<T>(rd, ref, acc);
     }
-    float *out = partials + wave * (int64_t)(NT * 256);
+    if constexpr (kRegisterTotals) {
+        float *out = partials + wave * (int64_t)(NT * 256) + lane;
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) out[t * 256 + v * 64 + lane] = acc[t][v];
+            for (int v = 0; v < 4; ++v) out[t * 256 + v * 64] = total[t][v] + acc[t][v];
+    } else {
+        do empty_accumulators(); while (flushed < flushes);   // the rest of the slots get zeros
+    }
 }
 
 // Adds the per-wavefront tiles in fp64, in two fixed-order levels: kReduceSlices contiguous
@@ -394,39 +450,53 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
 
 template <int T>
 hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long long *keys, int grid,
-                       bool aligned, const int *run_if, hipStream_t s)
+                       bool aligned, const int *run_if, int chain_tiles, int flushes, hipStream_t s)
 {
     TraceScope t(run_if ? "gram_mfma_f32_if_redo" : "gram_mfma_f32", s);
     if (rs.means()) {
         // block means formed on the fly: offered for the row counts a hierarchical step can have
         if constexpr (T <= 2) {
             if (!aligned) return hipErrorInvalidValue;
-            gram_mfma_kernel<T, true, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+            gram_mfma_kernel<T, true, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if, chain_tiles, flushes);
         } else {
             return hipErrorInvalidValue;
         }
     } else if (aligned) {
-        gram_mfma_kernel<T, true, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+        gram_mfma_kernel<T, true, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if, chain_tiles, flushes);
     } else {
-        gram_mfma_kernel<T, false, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+        gram_mfma_kernel<T, false, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if, chain_tiles, flushes);
     }
     return hipGetLastError();
 }
 
-// Workspace of the MFMA path: the wavefront tiles (room for the largest grid), the slice sums of
-// the first reduction level, the reference keys.
+// Slots of partial sums a wavefront writes (see the kernel): one, or from five row tiles on as
+// many as keep the chain of products behind one accumulator near kLongChainCols columns.
+constexpr int kLongChainCols = 4096, kMaxFlushes = 8;
+int flushes_for(int T, int64_t d, int waves)
+{
+    if (T <= 4) return 1;
+    const int64_t per_wave = (d + waves - 1) / waves;
+    const int64_t f = (per_wave + kLongChainCols - 1) / kLongChainCols;
+    return f < 1 ? 1 : (f > kMaxFlushes ? kMaxFlushes : (int)f);
+}
+
+// Workspace of the MFMA path: the slots of partial sums (room for the largest grid), the slice
+// sums of the first reduction level, the reference keys.
 struct MfmaWs {
     float *tiles;
     double *slices;
     unsigned long long *keys;
 };
-MfmaWs carve_mfma(void *partials, int T)
+size_t mfma_slot_floats(int T, int64_t d)
+{
+    return (size_t)mfma_max_waves(T) * (size_t)flushes_for(T, d, mfma_max_waves(T)) * (size_t)tiles_for(T) * 256;
+}
+MfmaWs carve_mfma(void *partials, int T, int64_t d)
 {
     MfmaWs w;
-    const size_t elems = (size_t)tiles_for(T) * 256;
     w.tiles = static_cast<float *>(partials);
-    w.slices = reinterpret_cast<double *>(w.tiles + (size_t)mfma_max_waves(T) * elems);
-    w.keys = reinterpret_cast<unsigned long long *>(w.slices + (size_t)kReduceSlices * elems);
+    w.slices = reinterpret_cast<double *>(w.tiles + mfma_slot_floats(T, d));
+    w.keys = reinterpret_cast<unsigned long long *>(w.slices + (size_t)kReduceSlices * tiles_for(T) * 256);
     return w;
 }
 
@@ -438,31 +508,37 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
 {
     const int T = (rs.count + 15) / 16;
     if (T < 1 || T > 8) return hipErrorInvalidValue;
-    const MfmaWs w = carve_mfma(partials, T);
+    const MfmaWs w = carve_mfma(partials, T, rs.d);
     int grid = num_compute_units() * mfma_blocks_per_cu(T);
     if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
-    const int64_t tiles = (rs.d + kTileCols - 1) / kTileCols;
+    const int64_t tiles = (rs.d + tile_cols(T) - 1) / tile_cols(T);
     const int64_t need = (tiles + kBlock / kWave - 1) / (kBlock / kWave);
     if (grid > need) grid = (int)need;
+    const int waves = grid * (kBlock / kWave);
+    // never more slots than the workspace was sized for (its bound assumes the largest grid)
+    int flushes = flushes_for(T, rs.d, waves);
+    while (flushes > 1 && (size_t)waves * flushes * tiles_for(T) * 256 > mfma_slot_floats(T, rs.d)) --flushes;
+    const int64_t tiles_per_wave = (tiles + waves - 1) / waves;
+    const int chain_tiles = (int)((tiles_per_wave + flushes - 1) / flushes);
     hipError_t e = launch_reference_keys(ref_rows_of(rs), w.keys, run_if, s);
     if (e != hipSuccess) return e;
-    bool aligned = row_vec_width(rs.base, rs.ld) == 4;
+    const bool aligned = row_vec_width(rs.base, rs.ld) == 4;
     switch (T) {
-    case 1: e = launch_mfma<1>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
-    case 2: e = launch_mfma<2>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
-    case 3: e = launch_mfma<3>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
-    case 4: e = launch_mfma<4>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
-    case 5: e = launch_mfma<5>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
-    case 6: e = launch_mfma<6>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
-    case 7: e = launch_mfma<7>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
-    default: e = launch_mfma<8>(rs, w.tiles, w.keys, grid, aligned, run_if, s); break;
+    case 1: e = launch_mfma<1>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 2: e = launch_mfma<2>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 3: e = launch_mfma<3>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 4: e = launch_mfma<4>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 5: e = launch_mfma<5>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 6: e = launch_mfma<6>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 7: e = launch_mfma<7>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    default: e = launch_mfma<8>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
     }
     if (e != hipSuccess) return e;
     const int elems = tiles_for(T) * 256;
     {
         TraceScope t("gram_reduce", s);
         gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
-            w.tiles, grid * (kBlock / kWave), elems, w.slices, alt, alt_waves, run_if);
+            w.tiles, waves * flushes, elems, w.slices, alt, alt_waves, run_if);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -473,11 +549,11 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
 
 }  // namespace
 
-size_t gram_partial_bytes(int64_t count)
+size_t gram_partial_bytes(int64_t count, int64_t d)
 {
     if (count <= 8) return (size_t)kMaxGramWaves * (size_t)(count * (count + 1) / 2) * sizeof(double);
     const int T = (int)((count + 15) / 16);
-    return (size_t)mfma_max_waves(T) * (size_t)tiles_for(T) * 256 * sizeof(float) +
+    return mfma_slot_floats(T, d) * sizeof(float) +
            (size_t)kReduceSlices * (size_t)tiles_for(T) * 256 * sizeof(double) +
            (size_t)kMaxCount * sizeof(unsigned long long);
 }
