@@ -229,6 +229,24 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
                int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
                int32_t *selected, float *out, void *ws, size_t ws_bytes, void *stream);
 
+/* detox_step for callers that cannot allocate device memory or carry a workspace along (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same step
+ * with the same arguments and results, but its scratch memory is an array of
+ * DETOX_STATIC_SCRATCH_BYTES that lives inside the library, one copy per GPU, held from the first
+ * such call on that GPU until the process ends.  The call allocates nothing and frees nothing.
+ *   - A step that needs more scratch than that (detox_workspace_bytes(DETOX_OP_STEP, n, d, B) >
+ *     DETOX_STATIC_SCRATCH_BYTES: many node groups, or B beyond about 32) returns
+ *     DETOX_EWORKSPACE and has touched nothing; use detox_step with a workspace then.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU
+ *     (different streams or threads) race.  Calls on one stream, or ordered by events, are fine;
+ *     nothing needs clearing between them.
+ *   - Per-kernel tracing (detox_trace_enable) creates events and so allocates; leave it off.  */
+#define DETOX_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+int detox_step_static(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
+                      const int32_t *group_rows, int64_t B, const int32_t *vote_perm, int agg, int f,
+                      int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
+                      int32_t *selected, float *out, void *stream);
+
 /* The hierarchy the paper deployed (Section 5.2, setups 2 and 3; Appendix B.1): Algorithm 2 with
  * A0 = a robust aggregator applied inside every vote group and A1 = mean over the B results.
  * The votes, in the order vote_perm, are cut into B vote groups as in detox_block_mean (15 votes

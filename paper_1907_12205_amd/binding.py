@@ -17,7 +17,7 @@ EXPORTS = ["detox_strerror", "detox_last_hip_error", "detox_workspace_bytes",
            "detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
            "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan", "robust_coord_median",
            "robust_geomedian", "robust_trimmed_mean", "robust_coord_median_many",
-           "robust_geomedian_many", "detox_step", "detox_step_robust_blocks", "detox_sign_majority", "detox_trace_enable",
+           "robust_geomedian_many", "detox_step", "detox_step_static", "detox_step_robust_blocks", "detox_sign_majority", "detox_trace_enable",
            "detox_trace_read"]
 
 
@@ -68,6 +68,9 @@ def lib() -> ctypes.CDLL:
         L.robust_geomedian_many.restype = i32
         L.detox_step.argtypes = [vp, i64, i64, i64, i32, i32, vp, i64, vp, i32, i32, i32, i32, dbl,
                                  vp, vp, i64, vp, vp, vp, sz, vp]
+        L.detox_step_static.argtypes = [vp, i64, i64, i64, i32, i32, vp, i64, vp, i32, i32, i32, i32, dbl,
+                                        vp, vp, i64, vp, vp, vp]
+        L.detox_step_static.restype = i32
         L.detox_step_robust_blocks.argtypes = [vp, i64, i64, i64, i32, vp, i64, vp, i32, i32, i32, vp, vp, i64,
                                                vp, vp, vp, sz, vp]
         L.detox_step_robust_blocks.restype = i32
@@ -273,8 +276,10 @@ def robust_geomedian_many(X, iters: int = 50, eps: float = 1e-8, out=None, ws=No
 class StepBuffers:
     """Outputs and workspace of detox_step, allocated once and reused across steps."""
 
-    def __init__(self, n, d, r, B, device, ldo: Optional[int] = None, materialise: bool = True):
-        """materialise=False: the block means are not written to memory (Zhat = NULL)."""
+    def __init__(self, n, d, r, B, device, ldo: Optional[int] = None, materialise: bool = True,
+                 workspace: bool = True):
+        """materialise=False: the block means are not written to memory (Zhat = NULL);
+        workspace=False: outputs only (for detox_step_static)."""
         torch = _torch()
         ldo = ldo or ((d + 63) // 64 * 64)
         self.winner = torch.empty(n // r, dtype=torch.int32, device=device)
@@ -284,7 +289,8 @@ class StepBuffers:
             self.Zhat = self.Zhat_buf[:, :d]
         self.selected = torch.full((max(B, 1),), -1, dtype=torch.int32, device=device)
         self.out = torch.empty(d, dtype=torch.float32, device=device)
-        self.ws = torch.empty(max(workspace_bytes("step", n, d, B), 256), dtype=torch.uint8, device=device)
+        self.ws = (torch.empty(max(workspace_bytes("step", n, d, B), 256), dtype=torch.uint8, device=device)
+                   if workspace else None)
 
 
 def detox_step(G, r: int, q: int, B: int, aggregator: str, f: int = -1, m: int = -1, iters: int = 50,
@@ -301,6 +307,20 @@ def detox_step(G, r: int, q: int, B: int, aggregator: str, f: int = -1, m: int =
                           _ptr(b.selected), _ptr(b.out),
                           _ptr(b.ws), b.ws.numel(), _stream())
     _check(rc, "detox_step")
+    return b
+
+
+def detox_step_static(G, r: int, q: int, B: int, aggregator: str, buffers: StepBuffers, f: int = -1, m: int = -1,
+                      iters: int = 50, eps: float = 1e-8, group_rows=None, vote_perm=None):
+    """detox_step on the library's own scratch array: no workspace, nothing allocated.  `buffers`
+    holds the outputs (StepBuffers(..., workspace=False)); index arrays must be device tensors."""
+    p, n, d, ld = _matrix(G)
+    b = buffers
+    rc = lib().detox_step_static(p, n, d, ld, r, q, _ptr(group_rows), B, _ptr(vote_perm), AGG[aggregator], f, m,
+                                 iters, float(eps), _ptr(b.winner), _ptr(b.Zhat),
+                                 b.Zhat.stride(0) if b.Zhat is not None else 0, _ptr(b.selected), _ptr(b.out),
+                                 _stream())
+    _check(rc, "detox_step_static")
     return b
 
 

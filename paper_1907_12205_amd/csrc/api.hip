@@ -1,6 +1,7 @@
 // C ABI of libdetox (declared in include/detox.h): argument validation, workspace carving and
 // the order in which the kernels of one call are enqueued.  No arithmetic of the method lives
 // here; every step runs in the kernels of the other translation units.
+#include <mutex>
 #include <vector>
 
 #include "../../include/detox.h"
@@ -204,6 +205,32 @@ int num_compute_units()
 
 using namespace detox;
 
+// ---- scratch memory of detox_step_static ------------------------------------------------------
+// One array per GPU, held from the first use on that GPU until the process ends.  In host code
+// the array's name is only a handle: its address on the current device comes from
+// hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+constexpr size_t kStaticScratchBytes = DETOX_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static void *static_scratch()
+{
+    static std::mutex lock;
+    static void *per_device[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> guard(lock);
+    if (per_device[dev] == nullptr) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            (void)status_of(e != hipSuccess ? e : hipErrorInvalidSymbol);
+            return nullptr;
+        }
+        per_device[dev] = ptr;
+    }
+    return per_device[dev];
+}
+
 extern "C" {
 
 const char *detox_strerror(int status)
@@ -374,10 +401,12 @@ int robust_geomedian_many(const float *X, int64_t count, int64_t d, int64_t ld, 
                                            static_cast<hipStream_t>(stream)));
 }
 
-int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
-               const int32_t *group_rows, int64_t B, const int32_t *vote_perm, int agg, int f,
-               int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
-               int32_t *selected, float *out, void *ws, size_t ws_bytes, void *stream)
+// The whole step on the caller's workspace, or, with ws == nullptr, on this device's copy of
+// the static scratch array (then a need beyond its size is the error).
+static int step_impl(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
+                     const int32_t *group_rows, int64_t B, const int32_t *vote_perm, int agg, int f,
+                     int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
+                     int32_t *selected, float *out, void *ws, size_t ws_bytes, void *stream)
 {
     int rc = check_filter_args(G, n, d, ld, r);
     if (rc) return rc;
@@ -410,6 +439,12 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
     if (agg == DETOX_AGG_GEOMEDIAN && (iters < 0 || !(eps > 0.0))) return DETOX_EINVAL;
     const size_t fbytes = filter_bytes(groups);
     const size_t abytes = aggregator_ws_bytes(B, d);
+    if (ws == nullptr) {
+        if (fbytes + abytes > kStaticScratchBytes) return DETOX_EWORKSPACE;
+        ws = static_scratch();
+        if (ws == nullptr) return DETOX_EDEVICE;
+        ws_bytes = kStaticScratchBytes;
+    }
     if (!ws_ok(ws, ws_bytes, fbytes + abytes)) return DETOX_EWORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -470,6 +505,25 @@ int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
         return status_of(launch_trimmed_mean(rs, f, out, done.median_written ? fw.redo : nullptr, s));
     default: return geomedian_impl(rs, iters, eps, out, aws, fg, s);
     }
+}
+
+int detox_step(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
+               const int32_t *group_rows, int64_t B, const int32_t *vote_perm, int agg, int f,
+               int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
+               int32_t *selected, float *out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (ws == nullptr) return DETOX_EWORKSPACE;
+    return step_impl(G, n, d, ld, r, q, group_rows, B, vote_perm, agg, f, m, iters, eps, winner, Zhat,
+                     ldo, selected, out, ws, ws_bytes, stream);
+}
+
+int detox_step_static(const float *G, int64_t n, int64_t d, int64_t ld, int r, int q,
+                      const int32_t *group_rows, int64_t B, const int32_t *vote_perm, int agg, int f,
+                      int m, int iters, double eps, int32_t *winner, float *Zhat, int64_t ldo,
+                      int32_t *selected, float *out, void *stream)
+{
+    return step_impl(G, n, d, ld, r, q, group_rows, B, vote_perm, agg, f, m, iters, eps, winner, Zhat,
+                     ldo, selected, out, nullptr, 0, stream);
 }
 
 int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, int r,

@@ -72,6 +72,15 @@ def test_argument_validation_happens_on_the_host(dx):
                         p, p, 10, p, p, p, big, None) == EPRECOND                                 # Bulyan on 5 rows, f = 1
     assert L.detox_step(p, 45, 10, 10, 3, 5, None, 16, None, 0, 1, 3, 50, ctypes.c_double(1e-8),
                         p, p, 10, p, p, p, big, None) == EINVAL                                   # B > n/r
+    # the variant on the library's own scratch array: a step that needs more than the array holds
+    # is refused on the host (40 rows for the aggregator: 3 row tiles of Gram partials)
+    header = open(os.path.join(ROOT, "include", "detox.h")).read()
+    assert int(re.search(r"DETOX_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << 20\)", header).group(1)) << 20 < \
+        dx.workspace_bytes("step", 120, 10, 40)
+    assert L.detox_step_static(p, 120, 10, 10, 3, 5, None, 40, None, 2, -1, -1, 50, ctypes.c_double(1e-8),
+                               p, None, 0, p, p, None) == EWS
+    assert L.detox_step_static(p, 45, 10, 10, 3, 5, None, 16, None, 0, 1, 3, 50, ctypes.c_double(1e-8),
+                               p, p, 10, p, p, None) == EINVAL
     for code in range(5):
         assert dx.strerror(code)
 

@@ -1,0 +1,75 @@
+"""GPU check of detox_step_static (the step on the library's own scratch array, for callers that
+cannot allocate): its outputs equal detox_step's bit for bit, on two calls in a row, the second on
+a smaller input, and for every aggregator."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import dev_matrix, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dx():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1907_12205_amd as dx
+    return dx
+
+
+CASES = [dict(B=5, aggregator="multikrum", f=1, m=3), dict(B=15, aggregator="bulyan", f=2),
+         dict(B=5, aggregator="coord_median"), dict(B=7, aggregator="geomedian", iters=20),
+         dict(B=15, aggregator="multikrum", f=2, m=9), dict(B=5, aggregator="trimmed_mean", f=1)]
+
+
+def _both(dx, G, r, q, spec, materialise):
+    import torch
+    from paper_1907_12205_amd.binding import StepBuffers
+    n, d = G.shape
+    kw = dict(f=spec.get("f", -1), m=spec.get("m", -1), iters=spec.get("iters", 50))
+    want = dx.detox_step(G, r, q, spec["B"], spec["aggregator"], materialise=materialise, **kw)
+    got = StepBuffers(n, d, r, spec["B"], G.device, materialise=materialise, workspace=False)
+    got.out.fill_(7.0)
+    before = torch.cuda.memory_allocated()
+    dx.detox_step_static(G, r, q, spec["B"], spec["aggregator"], got, **kw)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    assert host(got.winner).tolist() == host(want.winner).tolist()
+    assert host(got.out).tobytes() == host(want.out).tobytes()
+    if materialise:
+        assert host(got.Zhat).tobytes() == host(want.Zhat).tobytes()
+    if spec["aggregator"] in ("multikrum", "bulyan"):
+        assert host(got.selected).tolist() == host(want.selected).tolist()
+    return got
+
+
+@pytest.mark.parametrize("spec", CASES, ids=lambda s: f"{s['aggregator']}-B{s['B']}")
+def test_static_scratch_step_equals_the_step_with_a_workspace(dx, spec):
+    big = workloads.config(3, d=300_007)
+    Gb = big.matrix()
+    Gb[12] = 7; Gb[13] = 8; Gb[14] = 9                  # a group without majority: the repair path too
+    small = workloads.config(3, d=5_003)
+    Gs = small.matrix()
+    for materialise in (False, True):
+        first = _both(dx, dev_matrix(Gb), 3, 5, spec, materialise)
+        second = _both(dx, dev_matrix(Gs), 3, 5, spec, materialise)       # smaller input, same scratch array
+        kw = {k: v for k, v in spec.items() if k not in ("B", "aggregator")}
+        ref_out, ref_w, _ = oracle.detox_step(Gs, 3, spec["B"], spec["aggregator"], **kw)
+        assert host(second.winner).tolist() == ref_w.tolist()
+        if spec["aggregator"] == "coord_median":
+            assert host(second.out).tobytes() == ref_out.tobytes()
+        else:
+            assert rel_l2(host(second.out), ref_out) <= 1e-5
+        assert host(first.winner)[4] == -1
+
+
+def test_static_scratch_step_refuses_what_does_not_fit(dx):
+    from paper_1907_12205_amd.binding import StepBuffers
+    w = workloads.config(3, d=1000)
+    G = dev_matrix(np.tile(w.matrix(), (3, 1)))          # 135 rows, 45 node groups
+    buf = StepBuffers(135, 1000, 3, 45, G.device, materialise=False, workspace=False)
+    with pytest.raises(dx.DetoxError) as err:
+        dx.detox_step_static(G, 3, 5, 45, "coord_median", buf)
+    assert err.value.code == 3
