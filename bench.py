@@ -1,19 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the DETOX parameter-server step on one MI355X.
 
-Workload (the one the headline metric is quoted on): n = 45 nodes, r = 3, q = 5 Byzantine
-(ALIE attack), d = 11,173,962 fp32 (ResNet-18-sized), synthetic and seeded.  One "step" is one
-pass of the whole hot path over the resident n x d matrix:
+Workload the headline metric is quoted on: n = 45 nodes, r = 3, q = 5 Byzantine (ALIE attack),
+d = 11,173,962 fp32 (ResNet-18-sized), synthetic and seeded.  One "step" is one pass of the whole
+hot path over the resident n x d matrix:
     majority-vote filter -> 15 votes -> 5 block means -> Multi-Krum(f=1, m=3) -> d-vector.
-The same run also times the vanilla comparison (Multi-Krum over all 45 rows, f=5, m=40), the
-dominant kernel on its own (per-kernel HIP events inside the library) and the CPU oracle on the
-host cores.  Prints ONE JSON line on stdout; progress goes to stderr.
+The same run also times: every vanilla aggregator of the workload over all n rows; the other
+aggregators on the same matrix; the two d = 25,000,000 workloads (n = 45 heavy-tailed, n = 105),
+whose matrices are generated on the device with the same shapes and replication; the
+mean-estimation setting; the dominant kernel on its own (HIP events inside the library); a
+stream-read and an fp32-MFMA probe (the measured ceilings beside the published ones); and the CPU
+oracle on the host cores.  Prints ONE JSON line on stdout; progress goes to stderr.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,19 +25,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published peak
+MFMA_F32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published peak
 
 
 def measured_traffic(agg, n, d):
-    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc FETCH_SIZE /
-    WRITE_SIZE for this workload (the committed summary under profiles/), or None."""
-    import re
+    """HBM bytes per launch of the dominant kernel as rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    measured them for this workload (the committed summary under profiles/, which also names the
+    commit it was taken at), or (None, None)."""
     path = os.path.join(ROOT, "profiles", f"detox_step_{agg}__n{n}_d{d}.md")
     try:
-        m = re.search(r"^traffic_bytes_per_launch\[.*\]: (\d+)", open(path).read(), re.M)
-        return int(m.group(1)) if m else None
+        text = open(path).read()
     except OSError:
-        return None
+        return None, None
+    m = re.search(r"^traffic_bytes_per_launch\[.*\]: (\d+)", text, re.M)
+    c = re.search(r"^measured_at_commit: (\S+)", text, re.M)
+    return (int(m.group(1)) if m else None), (c.group(1) if c else None)
 
 
 def log(*a):
@@ -53,6 +60,54 @@ def time_steps(fn, steps, warmup, torch):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     return start.elapsed_time(stop) / steps, wall_ms / steps
+
+
+def traced_kernels(dx, fn, reps, np):
+    """Mean duration (ms) of every kernel of `fn`, from the library's own HIP events on the launch stream."""
+    with dx.trace() as tr:
+        for _ in range(reps):
+            fn()
+        recs = tr.records()
+    per = {}
+    for name, ms in recs:
+        per.setdefault(name, []).append(ms)
+    return {k: float(np.mean(v)) for k, v in per.items()}
+
+
+def probes(dx, torch, G):
+    """Measured ceilings: stream read over the resident matrix's buffer, fp32 MFMA issue rate."""
+    sink = torch.zeros(64, dtype=torch.float32, device=G.device)
+    buf = G._base if G._base is not None else G
+    nbytes = buf.numel() * 4
+    ms, _ = time_steps(lambda: dx.probe_stream_read(buf, sink), 10, 3, torch)
+    flop = dx.probe_mfma_f32(20000, sink)
+    ms_m, _ = time_steps(lambda: dx.probe_mfma_f32(20000, sink), 5, 2, torch)
+    res = {"stream_read_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "stream_read_bytes": nbytes,
+           "mfma_f32_TFLOPs": round(flop / (ms_m * 1e-3) / 1e12, 1)}
+    log(f"[bench] probes: stream read {res['stream_read_GBps']:.0f} GB/s over {nbytes / 1e9:.2f} GB, "
+        f"fp32 MFMA {res['mfma_f32_TFLOPs']:.1f} TFLOP/s")
+    return res
+
+
+class Legs:
+    """Times paths on one resident matrix and records them against their compulsory rows."""
+
+    def __init__(self, n, d, steps, torch, stream_gbs, only=None):
+        self.n, self.d, self.steps, self.torch, self.stream_gbs, self.only = n, d, steps, torch, stream_gbs, only
+        self.rows = []
+
+    def timed(self, name, fn, rows, warmup=2, **extra):
+        if self.only and self.only not in name:
+            return None
+        ms, _ = time_steps(fn, self.steps, warmup, self.torch)
+        gbs = rows * self.d * 4 / (ms * 1e-3) / 1e9
+        rec = {"path": name, "ms_per_step": round(ms, 5),
+               "GBps_aggregated": round(self.n * self.d * 4 / (ms * 1e-3) / 1e9, 1),
+               "rows_moved": rows, "hbm_frac_algorithmic": round(gbs / HBM_PEAK_GBS, 4),
+               "frac_of_measured_stream": round(gbs / self.stream_gbs, 4) if self.stream_gbs else None, **extra}
+        self.rows.append(rec)
+        log(f"[bench] {name}: {ms:.4f} ms/step, {rec['hbm_frac_algorithmic'] * 100:.1f}% of HBM peak over {rows} rows")
+        return rec
 
 
 def mean_estimation_paths(dx, workloads, torch, np, steps, d=100):
@@ -101,6 +156,95 @@ def mean_estimation_paths(dx, workloads, torch, np, steps, d=100):
     return {"workload": f"{w.name}: n={n}, r={r}, q={q}, d={d}, {w.attack}", "paths": res}
 
 
+def device_matrix(torch, n, r, d, byz_rows, kind, seed=20190712):
+    """An n x d matrix with the replication structure of the workloads, generated on the device
+    (timing only; the seeded host generators of `workloads` serve the parity tests): one base
+    vector per node group copied to its members, Byzantine rows overwritten.
+      kind "student_t": base 1e-3 * t(3), Byzantine rows uniform in [-1, 1];
+      kind "normal"   : base N(0, 1e-3), Byzantine rows constant +-100."""
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    G = torch.empty((n, d), dtype=torch.float32, device="cuda:0")
+    for j in range(n // r):
+        z = torch.randn(d, device="cuda:0", generator=g)
+        if kind == "student_t":
+            chi = sum(torch.randn(d, device="cuda:0", generator=g) ** 2 for _ in range(3)) / 3.0
+            z = z / chi.sqrt()
+            z *= 1e-3
+        else:
+            z *= 1e-3 ** 0.5
+        for k in range(r):
+            G[j * r + k].copy_(z)
+        del z
+    for t, i in enumerate(byz_rows):
+        if kind == "student_t":
+            G[i].uniform_(-1.0, 1.0, generator=g)
+        else:
+            G[i].fill_(100.0 if t % 2 == 0 else -100.0)
+    torch.cuda.synchronize()
+    return G
+
+
+def mfma_roofline(n, d, kernel_ms, mfma_tflops):
+    """The Gram kernel against the fp32 matrix-core peak, on the method's own operations:
+    n(n+1)/2 multiply-adds per column (the padded tiles compute more)."""
+    flop = n * (n + 1) / 2 * 2.0 * d
+    achieved = flop / (kernel_ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": "gram_mfma_f32", "achieved": round(achieved, 1), "peak": MFMA_F32_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4),
+            "frac_of_measured_mfma": round(achieved / mfma_tflops, 4) if mfma_tflops else None,
+            "algorithmic_flop_per_launch": flop, "kernel_ms": round(kernel_ms, 5), "traffic": None}
+
+
+def big_workloads(dx, workloads, torch, np, steps, pr, only):
+    """The two d = 25,000,000 workloads: DETOX pipelines and vanilla aggregators, device-generated data."""
+    from paper_1907_12205_amd.binding import StepBuffers
+    res = []
+    d = 25_000_000
+    # ---- n = 45, r = 3, q = 5, heavy-tailed ------------------------------------------------------
+    n, r, q = 45, 3, 5
+    byz = workloads.place_byzantine(workloads.DEFAULT_SEED, n, r, q, 1)
+    G = device_matrix(torch, n, r, d, byz, "student_t")
+    legs = Legs(n, d, steps, torch, pr["stream_read_GBps"], only)
+    out = torch.empty(d, dtype=torch.float32, device=G.device)
+    b15 = StepBuffers(n, d, r, 15, G.device, materialise=False)
+    b5 = StepBuffers(n, d, r, 5, G.device, materialise=False)
+    legs.timed("DETOX Bulyan over the 15 votes, f=1", lambda: dx.detox_step(G, r, q, 15, "bulyan", f=1, buffers=b15), n + 13 + 1)
+    legs.timed("DETOX coord-median, B=5 (one pass)", lambda: dx.detox_step(G, r, q, 5, "coord_median", buffers=b5), n + 1)
+    ws = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
+    legs.timed("vanilla Bulyan over 45 rows, f=5", lambda: dx.robust_bulyan(G, 5, out=out, ws=ws), n + 35 + 1)
+    res.append({"workload": f"cfg4 shape: n={n}, r={r}, q={q}, d={d}, Student-t(3) base, uniform Byzantine rows; "
+                            "generated on the device", "paths": legs.rows})
+    del G, b15, b5, ws, out
+    torch.cuda.empty_cache()
+    # ---- n = 105, r = 5, q = 10 ------------------------------------------------------------------
+    n, r, q = 105, 5, 10
+    byz = workloads.place_byzantine(workloads.DEFAULT_SEED, n, r, q, 2)
+    G = device_matrix(torch, n, r, d, byz, "normal")
+    legs = Legs(n, d, max(steps // 2, 3), torch, pr["stream_read_GBps"], only)
+    out = torch.empty(d, dtype=torch.float32, device=G.device)
+    b7 = StepBuffers(n, d, r, 7, G.device, materialise=False)
+    b21 = StepBuffers(n, d, r, 21, G.device, materialise=False)
+    legs.timed("DETOX geometric median, B=7, 50 iterations", lambda: dx.detox_step(G, r, q, 7, "geomedian", buffers=b7), n + 7 + 7 + 1)
+    legs.timed("DETOX Bulyan over the 21 votes, f=2", lambda: dx.detox_step(G, r, q, 21, "bulyan", f=2, buffers=b21), n + 17 + 1)
+    legs.timed("vanilla coord-median over 105 rows", lambda: dx.robust_coord_median(G, out=out), n + 1)
+    ws = torch.empty(dx.workspace_bytes("multikrum", n, d), dtype=torch.uint8, device=G.device)
+    fn = lambda: dx.robust_multikrum(G, 10, 95, out=out, ws=ws, with_scores=False)
+    rec = legs.timed("vanilla Multi-Krum over 105 rows, f=10, m=95", fn, n + 95 + 1)
+    if rec is not None:
+        km = traced_kernels(dx, fn, 3, np)
+        rec["kernel_ms"] = {k: round(v, 5) for k, v in km.items()}
+        if "gram_mfma_f32" in km:
+            rec["roofline"] = mfma_roofline(n, d, km["gram_mfma_f32"], pr["mfma_f32_TFLOPs"])
+            log(f"[bench] Gram kernel of 105 rows: {km['gram_mfma_f32']:.3f} ms = {rec['roofline']['achieved']:.1f} TFLOP/s on "
+                f"the method's operations, {rec['roofline']['frac'] * 100:.1f}% of the fp32 MFMA peak")
+    res.append({"workload": f"cfg5 shape: n={n}, r={r}, q={q}, d={d}, N(0,1e-3) base, constant +-100 Byzantine rows; "
+                            "generated on the device", "paths": legs.rows})
+    del G
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,10 +252,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload index 1..5 (3 = headline)")
     ap.add_argument("--d", type=int, default=None, help="override the dimension (debugging)")
+    ap.add_argument("--ld", type=int, default=None, help="row stride in elements (default: d rounded up to 64)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-vanilla", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other aggregators' timings")
     ap.add_argument("--no-mean-estimation", action="store_true", help="skip the many-short-rows setting")
+    ap.add_argument("--no-big", action="store_true", help="skip the two d = 25,000,000 workloads")
+    ap.add_argument("--only", default=None, help="time only the paths whose name contains this (profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the parameter-server step on ONE GPU (the step has no "
@@ -131,12 +278,14 @@ def main():
     t0 = time.time()
     w = workloads.config(args.config, d=args.d)
     n, r, q, d = w.n, w.r, w.q, w.d
-    ld = (d + 63) // 64 * 64                       # rows padded to 256 bytes: 16-byte loads everywhere
+    ld = args.ld or (d + 63) // 64 * 64            # rows padded to 256 bytes: 16-byte loads everywhere
     G = w.to_device("cuda:0", ld=ld)
     spec = w.detox[0]
     B, agg = spec["B"], spec["aggregator"]
+    groups = n // r
     log(f"[bench] workload {w.name}: n={n} r={r} q={q} d={d} ld={ld} attack={w.attack} "
         f"({n * d * 4 / 1e9:.3f} GB resident, generated in {time.time() - t0:.1f}s)")
+    pr = probes(dx, torch, G)
 
     # the block means are not written to memory (Zhat = NULL): the fast mode of detox_step
     buf = StepBuffers(n, d, r, B, G.device, materialise=False)
@@ -152,108 +301,109 @@ def main():
         f"{value:.1f} GB/s of gradients aggregated")
 
     # ---- dominant kernel, timed by the library's own HIP events on the launch stream --------
-    with dx.trace() as tr:
-        for _ in range(args.steps):
-            detox_step()
-        recs = tr.records()
-    per_kernel = {}
-    for name, ms in recs:
-        per_kernel.setdefault(name, []).append(ms)
-    kernel_ms = {k: float(np.mean(v)) for k, v in per_kernel.items()}
+    kernel_ms = traced_kernels(dx, detox_step, args.steps, np)
     dominant = max(kernel_ms, key=kernel_ms.get)
     # algorithmic rows per launch: the one-pass filter kernels read every row of G once; the
     # median variant also writes the d-vector
     alg_rows = {"filter_block_mean_gram": n, "filter_block_mean_median": n + 1, "filter": n,
-                "filter_block_mean": n + B}
+                "filter_block_mean": n + B, "filter_votes_gram": n}
     alg_bytes = alg_rows.get(dominant, n) * d * 4
     achieved = alg_bytes / (kernel_ms[dominant] * 1e-3) / 1e9
     log("[bench] per-kernel ms: " + ", ".join(f"{k}={v:.4f}" for k, v in kernel_ms.items()))
+    traffic, traffic_commit = measured_traffic(agg, n, d)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(agg, n, d),
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_measured_at_commit": traffic_commit,
+                "frac_of_measured_stream": round(achieved / pr["stream_read_GBps"], 4),
                 "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": round(kernel_ms[dominant], 5)}
     # compulsory traffic of the whole step: n rows in, B block means, m of them out again, 1 result
-    step_alg_bytes = (n + B + spec.get("m", 0) + 1) * d * 4 if agg == "multikrum" else None
+    step_rows = {"multikrum": n + B + spec.get("m", 0) + 1, "coord_median": n + 1, "trimmed_mean": n + 1,
+                 "geomedian": n + B + B + 1, "bulyan": n + (B - 2 * spec.get("f", 0)) + 1}[agg]
+    step_alg_bytes = step_rows * d * 4
 
-    # ---- vanilla comparison: the same aggregator over all n rows ------------------------------
-    vanilla = None
+    legs = Legs(n, d, max(args.steps // 2, 3), torch, pr["stream_read_GBps"], args.only)
+    out_o = torch.empty(d, dtype=torch.float32, device=G.device)
+
+    # ---- vanilla comparison: every aggregator the workload names, over all n rows -----------------
+    vanilla = []
     if w.vanilla and not args.no_vanilla:
-        v = w.vanilla[0]
-        out_v = torch.empty(d, dtype=torch.float32, device=G.device)
-        if v["aggregator"] == "multikrum":
-            ws_v = torch.empty(dx.workspace_bytes("multikrum", n, d), dtype=torch.uint8, device=G.device)
-            fn = lambda: dx.robust_multikrum(G, v["f"], v["m"], out=out_v, ws=ws_v, with_scores=False)
-            rows = n + v["m"] + 1
-        elif v["aggregator"] == "bulyan":
-            ws_v = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
-            fn = lambda: dx.robust_bulyan(G, v["f"], out=out_v, ws=ws_v)
-            rows = n + (n - 2 * v["f"]) + 1
-        else:
-            fn = lambda: dx.robust_coord_median(G, out=out_v)
-            rows = n + 1
-        ms_v, _ = time_steps(fn, args.steps, args.warmup, torch)
-        with dx.trace() as tr:
-            for _ in range(min(args.steps, 5)):
-                fn()
-            recs = tr.records()
-        vk = {}
-        for name, ms in recs:
-            vk.setdefault(name, []).append(ms)
-        vanilla = {"aggregator": v["aggregator"], **{k: v[k] for k in ("f", "m") if k in v},
+        for v in w.vanilla:
+            if v["aggregator"] == "multikrum":
+                ws_v = torch.empty(dx.workspace_bytes("multikrum", n, d), dtype=torch.uint8, device=G.device)
+                fn = lambda: dx.robust_multikrum(G, v["f"], v["m"], out=out_o, ws=ws_v, with_scores=False)
+                rows = n + v["m"] + 1
+            elif v["aggregator"] == "bulyan":
+                ws_v = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
+                fn = lambda: dx.robust_bulyan(G, v["f"], out=out_o, ws=ws_v)
+                rows = n + (n - 2 * v["f"]) + 1
+            else:
+                fn = lambda: dx.robust_coord_median(G, out=out_o)
+                rows = n + 1
+            ms_v, _ = time_steps(fn, args.steps, args.warmup, torch)
+            vk = traced_kernels(dx, fn, min(args.steps, 5), np)
+            rec = {"aggregator": v["aggregator"], **{k: v[k] for k in ("f", "m") if k in v},
                    "ms_per_step": round(ms_v, 5), "GBps_aggregated": round(in_bytes / (ms_v * 1e-3) / 1e9, 1),
+                   "rows_moved": rows,
                    "hbm_frac_algorithmic": round(rows * d * 4 / (ms_v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                   "kernel_ms": {k: round(float(np.mean(x)), 5) for k, x in vk.items()},
+                   "frac_of_measured_stream": round(rows * d * 4 / (ms_v * 1e-3) / 1e9 / pr["stream_read_GBps"], 4),
+                   "kernel_ms": {k: round(x, 5) for k, x in vk.items()},
                    "detox_speedup": round(ms_v / ms_step, 3)}
-        log(f"[bench] vanilla {v['aggregator']}: {ms_v:.4f} ms/step; DETOX is {ms_v / ms_step:.2f}x faster")
+            if "gram_mfma_f32" in vk:
+                rec["gram_roofline"] = mfma_roofline(n, d, vk["gram_mfma_f32"], pr["mfma_f32_TFLOPs"])
+                rec["gram_hbm_frac"] = round(in_bytes / (vk["gram_mfma_f32"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            vanilla.append(rec)
+            log(f"[bench] vanilla {v['aggregator']}: {ms_v:.4f} ms/step ({rec['hbm_frac_algorithmic'] * 100:.1f}% of HBM peak "
+                f"over {rows} rows); DETOX is {ms_v / ms_step:.2f}x faster")
 
     # ---- the other rows of the hot path on the same resident matrix (reported, not the value) --
-    others = []
     if not args.no_others:
-        def timed(name, fn, rows):
-            ms, _ = time_steps(fn, max(args.steps // 2, 3), 2, torch)
-            others.append({"path": name, "ms_per_step": round(ms, 5),
-                           "GBps_aggregated": round(in_bytes / (ms * 1e-3) / 1e9, 1),
-                           "hbm_frac_algorithmic": round(rows * d * 4 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
-        groups = n // r
-        out_o = torch.empty(d, dtype=torch.float32, device=G.device)
+        timed = legs.timed
         timed("filter only (votes)", lambda: dx.detox_majority_filter(G, r), n)
+        for other in w.detox[1:]:
+            bo = StepBuffers(n, d, r, other["B"], G.device, materialise=False)
+            okw = dict(f=other.get("f", -1), m=other.get("m", -1), iters=other.get("iters", 50), eps=other.get("eps", 1e-8))
+            rows_o = {"coord_median": n + 1, "bulyan": n + other["B"] - 2 * other.get("f", 0) + 1}.get(other["aggregator"], n + 1)
+            timed(f"DETOX {other['aggregator']}, B={other['B']}", lambda: dx.detox_step(G, r, q, other["B"], other["aggregator"], buffers=bo, **okw), rows_o)
         if groups >= 5:
             bm = StepBuffers(n, d, r, 5, G.device, materialise=False)
             timed("DETOX coord-median, B=5 (one pass)", lambda: dx.detox_step(G, r, q, 5, "coord_median", buffers=bm), n + 1)
             timed("DETOX trimmed mean (alpha=1/4), B=5 (one pass)", lambda: dx.detox_step(G, r, q, 5, "trimmed_mean", buffers=bm), n + 1)
-            timed("DETOX geometric median, B=5, 50 iterations", lambda: dx.detox_step(G, r, q, 5, "geomedian", buffers=bm), n + groups + 1)
+            timed("DETOX geometric median, B=5, 50 iterations", lambda: dx.detox_step(G, r, q, 5, "geomedian", buffers=bm), n + 5 + 5 + 1)
         if groups >= 7:
             bb = StepBuffers(n, d, r, groups, G.device, materialise=False)
-            # 9..16 votes: their Gram matrix comes out of the filter pass, so the votes are read once more
-            # only for the trimming (more votes: also once for the Gram matrix)
             timed(f"DETOX Bulyan over the {groups} votes, f=1", lambda: dx.detox_step(G, r, q, groups, "bulyan", f=1, buffers=bb),
-                  n + (0 if 8 < groups <= 16 else groups) + (groups - 2) + 1)
+                  n + (groups - 2) + 1)
         if groups >= 14:
             # the hierarchy the paper deployed (Section 5.2): robust aggregator inside vote groups, mean across
-            gram_rows = 0 if 8 < groups <= 16 else groups   # 9..16 votes: their Gram matrix comes with the filter pass
             ws_h = torch.empty(max(dx.robust_blocks_workspace_bytes(n, d, r, 1), dx.robust_blocks_workspace_bytes(n, d, r, 2)),
                                dtype=torch.uint8, device=G.device)
             timed(f"DETOX A0=Multi-Krum(f=2,m=3) on {groups // 2}+{groups - groups // 2} votes, A1=mean",
-                  lambda: dx.detox_step_robust_blocks(G, r, 2, "multikrum", 2, 3, out=out_o, ws=ws_h), n + gram_rows + 2 * 3 + 2 + 2 + 1)
+                  lambda: dx.detox_step_robust_blocks(G, r, 2, "multikrum", 2, 3, out=out_o, ws=ws_h), n + 2 * 3 + 2 + 2 + 1)
             timed(f"DETOX A0=Bulyan(f=2) on all {groups} votes",
-                  lambda: dx.detox_step_robust_blocks(G, r, 1, "bulyan", 2, out=out_o, ws=ws_h), n + gram_rows + (groups - 4) + 1)
+                  lambda: dx.detox_step_robust_blocks(G, r, 1, "bulyan", 2, out=out_o, ws=ws_h), n + (groups - 4) + 1)
         timed(f"vanilla coord-median over {n} rows", lambda: dx.robust_coord_median(G, out=out_o), n + 1)
         timed(f"vanilla trimmed mean over {n} rows, {n // 4} off each end",
               lambda: dx.robust_trimmed_mean(G, n // 4, out=out_o), n + 1)
         fb = min(q, (n - 3) // 4)
         ws_b = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
         timed(f"vanilla Bulyan over {n} rows, f={fb}", lambda: dx.robust_bulyan(G, fb, out=out_o, ws=ws_b), n + (n - 2 * fb) + 1)
+        if ld != d:
+            # the same step on unpadded rows (ld = d): narrower loads when d is not a multiple of 4
+            Gu = w.to_device("cuda:0")
+            bu = StepBuffers(n, d, r, B, G.device, materialise=False)
+            timed(f"DETOX {agg}, B={B}, rows not padded (ld = d = {d})", lambda: dx.detox_step(Gu, r, q, B, agg, buffers=bu, **kw), step_rows)
+            del Gu
         if groups >= 5:
             # signSGD pairing: one sign bit per coordinate, two levels of coordinate-wise majority vote
             S = torch.from_numpy(workloads.pack_signs(w.matrix()).view(np.int32)).to(G.device)
             ws_s = torch.empty(dx.workspace_bytes("filter", groups, S.shape[1]), dtype=torch.uint8, device=G.device)
             out_s = torch.empty((2, S.shape[1]), dtype=torch.int32, device=G.device)
             timed("DETOX + signSGD majority vote, bit-packed signs, B=5",
-                  lambda: dx.detox_sign_majority(S, d, r, 5, ws=ws_s, out=out_s), (n + groups + 2) / 32)
-        for o in others:
-            log(f"[bench] {o['path']}: {o['ms_per_step']:.4f} ms/step, {o['hbm_frac_algorithmic'] * 100:.1f}% of HBM peak (algorithmic bytes)")
+                  lambda: dx.detox_sign_majority(S, d, r, 5, ws=ws_s, out=out_s), (n + 2) / 32)
+            del S
 
     mean_est = None
-    if not args.no_others and not args.no_mean_estimation:
+    if not args.no_others and not args.no_mean_estimation and not args.only:
         mean_est = mean_estimation_paths(dx, workloads, torch, np, args.steps)
 
     # ---- CPU oracle on the host cores (a reported baseline, not the target) ------------------
@@ -282,6 +432,13 @@ def main():
             t1 = time.perf_counter()
             oracle.multikrum(Gh, w.vanilla[0]["f"], w.vanilla[0]["m"])
             cpu["vanilla_ms_per_step"] = round((time.perf_counter() - t1) * 1e3, 1)
+        del Gh
+
+    big = None
+    if not args.no_big and args.config == 3 and args.d is None:
+        del G, buf
+        torch.cuda.empty_cache()
+        big = big_workloads(dx, workloads, torch, np, max(args.steps // 2, 3), pr, args.only)
 
     line = {
         "metric": "aggregated gradient GB/s and ms/step (DETOX vs vanilla), % HBM roofline",
@@ -290,11 +447,12 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: n={n}, r={r}, q={q}, d={d}, {w.attack}; filter -> {n // r} votes -> "
                                f"{B} block means -> {agg}", "ld": ld, **{k: v for k, v in spec.items() if k != "aggregator"}},
-        "step_hbm_frac_algorithmic": (round(step_alg_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-                                      if step_alg_bytes else None),
+        "step_rows_moved": step_rows,
+        "step_hbm_frac_algorithmic": round(step_alg_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "step_frac_of_measured_stream": round(step_alg_bytes / (ms_step * 1e-3) / 1e9 / pr["stream_read_GBps"], 4),
         "kernel_ms": {k: round(v, 5) for k, v in kernel_ms.items()},
-        "roofline": roofline, "vanilla": vanilla, "other_paths": others, "mean_estimation": mean_est,
-        "cpu_baseline": cpu,
+        "roofline": roofline, "measured_ceilings": pr, "vanilla": vanilla, "other_paths": legs.rows,
+        "other_workloads": big, "mean_estimation": mean_est, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
 

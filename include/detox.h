@@ -291,6 +291,18 @@ int detox_sign_majority(const uint32_t *S, int64_t n, int64_t d, int64_t ldw, in
                         int32_t *winner, uint32_t *out_pos, uint32_t *out_neg, void *ws,
                         size_t ws_bytes, void *stream);
 
+/* Measurement helpers, no part of the method: what this chip reaches on the two resources that
+ * bound the kernels here, with the access pattern / instruction those kernels use.  Both only
+ * enqueue one kernel on `stream`; the caller times it.
+ *   detox_probe_stream_read: reads `bytes` (a multiple of 16 is used) of `buf` (dev, 16-byte
+ *     aligned) once with 16-byte non-temporal loads; `sink` (dev, 4 bytes) is never written in
+ *     practice.  bytes / time = the stream-read rate.
+ *   detox_probe_mfma_f32: `iters` rounds of 32 independent V_MFMA_F32_16X16X4_F32 per wavefront,
+ *     two wavefronts per SIMD on every CU; *flop (host, out, may be NULL) receives the number of
+ *     floating-point operations launched.  flop / time = the fp32 matrix-core rate.          */
+int detox_probe_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
+int detox_probe_mfma_f32(int iters, void *sink, double *flop, void *stream);
+
 /* Per-kernel timing.  While enabled, every kernel the library launches is
  * bracketed by hipEvents on the caller's stream (this adds a few microseconds
  * per launch; leave it off when timing whole steps).  After synchronising the

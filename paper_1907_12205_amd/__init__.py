@@ -7,6 +7,6 @@ library's exports can be checked), calling anything needs one.
 """
 from .binding import (  # noqa: F401
     AGG, DetoxError, OP, detox_block_mean, detox_filter_block_mean, detox_majority_filter,
-    detox_sign_majority, detox_step, detox_step_robust_blocks, detox_step_static, lib, library_path, robust_bulyan, robust_coord_median,
+    detox_sign_majority, detox_step, detox_step_robust_blocks, detox_step_static, lib, library_path, probe_mfma_f32, probe_stream_read, robust_bulyan, robust_coord_median,
     robust_coord_median_many, robust_geomedian, robust_geomedian_many,
     robust_blocks_workspace_bytes, robust_multikrum, robust_pairwise_sqdist, robust_trimmed_mean, strerror, trace, workspace_bytes)

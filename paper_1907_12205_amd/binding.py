@@ -17,7 +17,7 @@ EXPORTS = ["detox_strerror", "detox_last_hip_error", "detox_workspace_bytes",
            "detox_majority_filter", "detox_block_mean", "detox_filter_block_mean",
            "robust_pairwise_sqdist", "robust_multikrum", "robust_bulyan", "robust_coord_median",
            "robust_geomedian", "robust_trimmed_mean", "robust_coord_median_many",
-           "robust_geomedian_many", "detox_step", "detox_step_static", "detox_step_robust_blocks", "detox_sign_majority", "detox_trace_enable",
+           "robust_geomedian_many", "detox_step", "detox_step_static", "detox_step_robust_blocks", "detox_sign_majority", "detox_probe_stream_read", "detox_probe_mfma_f32", "detox_trace_enable",
            "detox_trace_read"]
 
 
@@ -76,6 +76,10 @@ def lib() -> ctypes.CDLL:
         L.detox_step_robust_blocks.restype = i32
         L.detox_sign_majority.argtypes = [vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         L.detox_sign_majority.restype = i32
+        L.detox_probe_stream_read.argtypes = [vp, sz, vp, vp]
+        L.detox_probe_stream_read.restype = i32
+        L.detox_probe_mfma_f32.argtypes = [i32, vp, ctypes.POINTER(dbl), vp]
+        L.detox_probe_mfma_f32.restype = i32
         L.detox_trace_enable.argtypes = [i32]
         L.detox_trace_enable.restype = None
         L.detox_trace_read.argtypes = [ctypes.POINTER(_TraceRecord), i32]
@@ -373,6 +377,19 @@ def detox_sign_majority(S, d: int, r: int, B: int, group_rows=None, vote_perm=No
                                    out[0].data_ptr(), out[1].data_ptr(), _ptr(ws), nb, _stream())
     _check(rc, "detox_sign_majority")
     return out[0], out[1], winner
+
+
+def probe_stream_read(buf, sink):
+    """Enqueues one read of every byte of the device tensor `buf` (the caller times it)."""
+    _check(lib().detox_probe_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream()),
+           "detox_probe_stream_read")
+
+
+def probe_mfma_f32(iters: int, sink) -> float:
+    """Enqueues the fp32 MFMA probe; returns the number of floating-point operations it performs."""
+    flop = ctypes.c_double(0.0)
+    _check(lib().detox_probe_mfma_f32(int(iters), sink.data_ptr(), ctypes.byref(flop), _stream()), "detox_probe_mfma_f32")
+    return float(flop.value)
 
 
 @contextlib.contextmanager

@@ -49,9 +49,7 @@ size_t filter_bytes(int64_t groups) { return round_up(filter_ws_bytes(groups)); 
 // Tiles the filter pass writes when it forms the Gram matrix of 9..16 votes on the side.
 size_t pass_gram_bytes(int64_t count)
 {
-    return count > 8 && count <= kPassGramMaxVotes
-               ? (size_t)kPassGramMaxWaves * 256 * sizeof(float) + (size_t)kMaxCount * sizeof(unsigned long long)
-               : 0;
+    return count > 8 && count <= kPassGramMaxVotes ? (size_t)kPassGramMaxWaves * 256 * sizeof(float) : 0;
 }
 
 // Gram partials + Gram matrix + the count x count scratch of the selection kernels.

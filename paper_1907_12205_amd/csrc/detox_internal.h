@@ -115,9 +115,7 @@ struct FilterParams {
     int32_t *winner;                    // dev, n_votes
     float *out;                         // dev, d: coordinate-wise median / trimmed mean (those modes)
     int trim_g;                         // trimmed-mean mode: values dropped at each end
-    float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats, then kMaxCount
-                                        //   reference keys (kVotesGram)
-    unsigned long long *vote_ref_keys;  // set by launch_filter
+    float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats (kVotesGram)
 };
 struct FilterWs {
     int *redo;

@@ -159,9 +159,6 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
     constexpr int kTileLd = 68;
     __shared__ __attribute__((aligned(16))) float vtile[MODE == kVotesGram ? kBlock / kWave : 1][16][kTileLd];
     [[maybe_unused]] f32x4_t macc = {0.0f, 0.0f, 0.0f, 0.0f};
-    // kVotesGram: the vote subtracted from every vote before the products (rows.h, pick_reference)
-    [[maybe_unused]] int refpos = 0;
-    if constexpr (MODE == kVotesGram) refpos = pick_reference(p.vote_ref_keys, (int)p.n_votes);
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock) sbits[j] = 0ull;
     __syncthreads();
 
@@ -218,13 +215,29 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
                     for (int i = 0; i < VEC; ++i) v[pos][i] = 0.0f;
                 }
             }
+            // Distances do not change when one vector is subtracted from every vote, and the
+            // fp32 products keep them only if the votes are small relative to each other (rows.h,
+            // pick_reference).  Here every lane holds all votes of its columns, so the vector
+            // subtracted is formed on the spot, per coordinate: the median of the medians of the
+            // vote triples (0,1,2), (3,4,5), ... (five triples from 15 votes on, else the first
+            // three).  It lies among the votes unless two votes in each of three (two) triples
+            // are far away, i.e. it withstands five (three) stray votes wherever they sit; it need
+            // not be exact (v_med3_f32 on a NaN falls back to the minimum of the others).
             float rv[VEC];
+            {
+                const bool five = p.n_votes >= 15;   // uniform
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) rv[i] = v[0][i];
+                for (int i = 0; i < VEC; ++i) {
+                    float m[5];
 #pragma unroll
-            for (int pos = 1; pos < kPassGramMaxVotes; ++pos)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) rv[i] = pos == refpos ? v[pos][i] : rv[i];   // uniform
+                    for (int t = 0; t < 5; ++t)
+                        m[t] = __builtin_amdgcn_fmed3f(v[3 * t][i], v[3 * t + 1][i], v[3 * t + 2][i]);
+                    const float lo = fmaxf(fminf(m[0], m[1]), fminf(m[2], m[3]));
+                    const float hi = fminf(fmaxf(m[0], m[1]), fmaxf(m[2], m[3]));
+                    const float c = five ? __builtin_amdgcn_fmed3f(m[4], lo, hi) : __builtin_amdgcn_fmed3f(m[0], m[1], m[2]);
+                    rv[i] = fabsf(c) < INFINITY ? c : 0.0f;
+                }
+            }
             // The tile is private to the wavefront, whose LDS instructions execute in order: the
             // writes of one component are seen by the reads that follow, and those are done
             // before the next component is written (the fences keep the compiler to that order).
@@ -677,14 +690,6 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
     if (done) *done = FilterDone{};
     hipError_t e;
     int grid = 0;
-    if (mode == kVotesGram) {
-        // the winners are not known yet: the reference vote is picked among the per-coordinate
-        // majority values of the node groups, which is what the pass multiplies
-        p.vote_ref_keys = reinterpret_cast<unsigned long long *>(p.vote_gram_partials + (size_t)kPassGramMaxWaves * 256);
-        const RefRows q{p.G, p.d, p.ld, (int)p.n_votes, nullptr, p.r, p.group_rows, nullptr, p.vote_perm, (int)p.n_votes};
-        e = launch_reference_keys(q, p.vote_ref_keys, nullptr, s);
-        if (e != hipSuccess) return e;
-    }
     if (fused) {
         grid = num_compute_units() * (p.n_votes <= 128 ? 4 : 2);   // wanted; trimmed to what is resident
         if (votes_gram && grid * (kBlock / kWave) > kPassGramMaxWaves) grid = kPassGramMaxWaves / (kBlock / kWave);

@@ -503,8 +503,10 @@ MfmaWs carve_mfma(void *partials, int T, int64_t d)
 // Gram matrix of more than 8 logical rows.  run_if (may be null): the kernels that touch the rows
 // run only if *run_if; alt (may be null): tiles left by the filter pass, added up instead of this
 // call's own unless *run_if.
+//   keys (may be null): reference keys over the same logical rows that the caller already has;
+//   otherwise they are computed here.
 hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const float *alt,
-                     int alt_waves, double *Gm, hipStream_t s)
+                     int alt_waves, const unsigned long long *keys, double *Gm, hipStream_t s)
 {
     const int T = (rs.count + 15) / 16;
     if (T < 1 || T > 8) return hipErrorInvalidValue;
@@ -520,18 +522,22 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
     while (flushes > 1 && (size_t)waves * flushes * tiles_for(T) * 256 > mfma_slot_floats(T, rs.d)) --flushes;
     const int64_t tiles_per_wave = (tiles + waves - 1) / waves;
     const int chain_tiles = (int)((tiles_per_wave + flushes - 1) / flushes);
-    hipError_t e = launch_reference_keys(ref_rows_of(rs), w.keys, run_if, s);
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (keys == nullptr) {
+        e = launch_reference_keys(ref_rows_of(rs), w.keys, run_if, s);
+        if (e != hipSuccess) return e;
+        keys = w.keys;
+    }
     const bool aligned = row_vec_width(rs.base, rs.ld) == 4;
     switch (T) {
-    case 1: e = launch_mfma<1>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 2: e = launch_mfma<2>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 3: e = launch_mfma<3>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 4: e = launch_mfma<4>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 5: e = launch_mfma<5>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 6: e = launch_mfma<6>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 7: e = launch_mfma<7>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    default: e = launch_mfma<8>(rs, w.tiles, w.keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 1: e = launch_mfma<1>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 2: e = launch_mfma<2>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 3: e = launch_mfma<3>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 4: e = launch_mfma<4>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 5: e = launch_mfma<5>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 6: e = launch_mfma<6>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 7: e = launch_mfma<7>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    default: e = launch_mfma<8>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
     }
     if (e != hipSuccess) return e;
     const int elems = tiles_for(T) * 256;
@@ -560,7 +566,7 @@ size_t gram_partial_bytes(int64_t count, int64_t d)
 
 hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s)
 {
-    if (rs.count > 8) return gram_mfma(rs, partials, nullptr, nullptr, 0, Gm, s);
+    if (rs.count > 8) return gram_mfma(rs, partials, nullptr, nullptr, 0, nullptr, Gm, s);
     double *pp = static_cast<double *>(partials);
     int grid = 0;
     hipError_t e = launch_small_any(rs, pp, nullptr, &grid, SmallSelect{}, nullptr, s);
@@ -621,7 +627,7 @@ hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float 
         redo == nullptr)
         return hipErrorInvalidValue;
     // the rows are touched only if some vote had no majority: the tiles of the pass are of no use then
-    return gram_mfma(rs, partials, redo, pass_partials, pass_waves, Gm, s);
+    return gram_mfma(rs, partials, redo, pass_partials, pass_waves, nullptr, Gm, s);
 }
 
 hipError_t launch_small_redo(const RowSet &rs, void *partials, const int *redo, double *Gm, int krum_f,

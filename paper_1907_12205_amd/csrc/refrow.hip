@@ -17,6 +17,30 @@ namespace {
 
 constexpr int kRefBlocks = 16;      // runs of kWave columns in the sample
 
+// Per-coordinate majority among the (at most R) members of node group j: the majority-vote scan
+// on the bit patterns; where no value has a majority the result is arbitrary, as in the filter
+// pass.  All loads first, so that they are in flight together (a slot beyond r repeats member 0).
+template <int R>
+__device__ inline float majority_sample(const RefRows &q, int j, int64_t c)
+{
+    uint32_t x[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int kk = k < q.r ? k : 0;   // uniform
+        const int64_t row = q.group_rows ? q.group_rows[(int64_t)j * q.r + kk] : (int64_t)j * q.r + kk;
+        x[k] = __float_as_uint(q.base[row * q.ld + c]);
+    }
+    uint32_t cand = x[0];
+    int cnt = 1;
+#pragma unroll
+    for (int k = 1; k < R; ++k) {
+        const bool in = k < q.r, same = x[k] == cand, empty = cnt == 0;
+        cand = (in && !same && empty) ? x[k] : cand;
+        cnt = in ? ((same || empty) ? cnt + 1 : cnt - 1) : cnt;
+    }
+    return __uint_as_float(cand);
+}
+
 __device__ inline float sample_vote(const RefRows &q, int pos, int64_t c)
 {
     const int j = q.vote_perm ? q.vote_perm[pos] : pos;
@@ -24,20 +48,7 @@ __device__ inline float sample_vote(const RefRows &q, int pos, int64_t c)
         const int32_t w = q.winner[j];
         return w < 0 ? 0.0f : q.base[(int64_t)w * q.ld + c];
     }
-    // per-coordinate majority among the members (majority-vote scan on the bit patterns); where no
-    // value has a majority the result is arbitrary, as in the filter pass
-    uint32_t cand = 0u;
-    int cnt = 0;
-    for (int k = 0; k < q.r; ++k) {
-        const int64_t row = q.group_rows ? q.group_rows[(int64_t)j * q.r + k] : (int64_t)j * q.r + k;
-        const uint32_t x = __float_as_uint(q.base[row * q.ld + c]);
-        if (cnt == 0) {
-            cand = x, cnt = 1;
-        } else {
-            cnt += x == cand ? 1 : -1;
-        }
-    }
-    return __uint_as_float(cand);
+    return q.r <= 3 ? majority_sample<3>(q, j, c) : (q.r <= 5 ? majority_sample<5>(q, j, c) : majority_sample<kMaxR>(q, j, c));
 }
 
 __device__ inline float sample_value(const RefRows &q, int b, int64_t c)
