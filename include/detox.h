@@ -72,7 +72,8 @@ typedef enum {
     DETOX_OP_GEOMEDIAN = 6,
     DETOX_OP_STEP = 7,              /* detox_step: count = n, aux = B                               */
     DETOX_OP_COORD_MEDIAN_MANY = 8, /* robust_coord_median_many (depends on count and d)            */
-    DETOX_OP_GEOMEDIAN_MANY = 9     /* robust_geomedian_many                                        */
+    DETOX_OP_GEOMEDIAN_MANY = 9,    /* robust_geomedian_many                                        */
+    DETOX_OP_STEP_ROBUST_BLOCKS = 10 /* detox_step_robust_blocks: count = n/r (votes), aux = B      */
 } detox_op;
 
 /* Limits of this build. */
@@ -87,9 +88,10 @@ const char *detox_strerror(int status);
 int detox_last_hip_error(void);
 
 /* Bytes of scratch an operation needs (host-only, pure; no HIP call).
- * count = rows of the matrix handed to the operation, d = dimension,
- * aux = B for DETOX_OP_STEP, otherwise ignored.  Returns 0 for operations that
- * need none and for unsupported arguments. */
+ * count = rows of the matrix handed to the operation (DETOX_OP_STEP_ROBUST_BLOCKS: the number
+ * of votes n/r), d = dimension (the Gram-based operations on more than 64 rows need more the
+ * larger d is), aux = B for DETOX_OP_STEP and DETOX_OP_STEP_ROBUST_BLOCKS, otherwise ignored.
+ * Returns 0 for operations that need none and for unsupported arguments. */
 size_t detox_workspace_bytes(int op, int64_t count, int64_t d, int64_t aux);
 
 /* Filtering step (Section 3; Algorithm 1, "Filtering step"):
@@ -213,7 +215,8 @@ int robust_geomedian_many(const float *X, int64_t count, int64_t d, int64_t ld, 
  * the winner rows of G, with the same arithmetic and bit-identical values.  That is the faster
  * mode; pass Zhat only if the means themselves are wanted.
  *   q          number of Byzantine nodes; used only when f < 0 to derive
- *              f = min(q / ((r+1)/2), largest f the aggregator admits for B rows)
+ *              f = q / ((r+1)/2), the Byzantine votes that can survive the filter; if the
+ *              aggregator does not admit that many among B rows: DETOX_EPRECOND
  *   f, m       aggregator parameters; f < 0 and m < 0 mean "derive"
  *              (m = B - f).  DETOX_AGG_TRIMMED_MEAN: f = values dropped at each end
  *              (f < 0: floor(B/4), i.e. alpha = 1/4)
@@ -262,10 +265,11 @@ int detox_step_static(const float *G, int64_t n, int64_t d, int64_t ld, int r, i
  *              selection order) starts at its first vote position floor(b*V/B); Multi-Krum
  *              fills m entries there, Bulyan size-2f
  *   out        dev, d floats
- *   ws         DETOX_OP_STEP bytes with count = n and aux = the largest group size
- *              ceil((n/r)/B).  With 9 <= n/r <= 16 and DETOX_OP_MULTIKRUM bytes for count = n/r
- *              on top of that, the Gram matrix of all votes is formed during the filter pass
- *              and the vote groups cut theirs out of it (one pass less over the winner rows). */
+ *   ws         DETOX_OP_STEP_ROBUST_BLOCKS bytes (count = n/r, aux = B).  With 9 <= n/r <= 16 (and
+ *              16-byte aligned rows) the Gram matrix of all votes is formed during the filter
+ *              pass, on the matrix cores in fp32, and the vote groups cut theirs out of it (one
+ *              pass less over the winner rows); otherwise every group's matrix is formed from
+ *              its rows (fp64 for groups of at most 8 votes).                               */
 int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, int r,
                              const int32_t *group_rows, int64_t B, const int32_t *vote_perm,
                              int a0, int f, int m, int32_t *winner, float *block_out,
@@ -306,8 +310,10 @@ int detox_probe_mfma_f32(int iters, void *sink, double *flop, void *stream);
 /* Per-kernel timing.  While enabled, every kernel the library launches is
  * bracketed by hipEvents on the caller's stream (this adds a few microseconds
  * per launch; leave it off when timing whole steps).  After synchronising the
- * stream, detox_trace_read returns up to `cap` records, oldest first, and
- * clears the log.  Names are static strings.  Not thread-safe.               */
+ * stream(s), detox_trace_read returns up to `cap` records, oldest first, and
+ * clears the log.  Names are static strings.  The log is the library's only
+ * process-wide state; it is guarded by a lock, so tracing from several threads
+ * is safe (their records interleave).                                          */
 typedef struct {
     const char *kernel;
     float ms;

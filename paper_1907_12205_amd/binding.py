@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdetox.so")
 
 OP = dict(filter=0, block_mean=1, pairwise_sqdist=2, multikrum=3, bulyan=4, coord_median=5,
-          geomedian=6, step=7, coord_median_many=8, geomedian_many=9)
+          geomedian=6, step=7, coord_median_many=8, geomedian_many=9, step_robust_blocks=10)
 AGG = dict(multikrum=0, bulyan=1, coord_median=2, geomedian=3, trimmed_mean=4)
 
 EXPORTS = ["detox_strerror", "detox_last_hip_error", "detox_workspace_bytes",
@@ -328,19 +328,13 @@ def detox_step_static(G, r: int, q: int, B: int, aggregator: str, buffers: StepB
     return b
 
 
-def robust_blocks_workspace_bytes(n: int, d: int, r: int, B: int, gram_in_pass: bool = True) -> int:
-    """Workspace of detox_step_robust_blocks; with gram_in_pass (and 9..16 votes) the extra room
-    that lets the filter pass form the Gram matrix of all votes."""
-    groups = n // max(r, 1)
-    largest = -(-groups // max(B, 1))
-    need = workspace_bytes("step", n, d, largest) + 4 * groups + 512
-    if gram_in_pass and 8 < groups <= 16:
-        need += workspace_bytes("multikrum", groups, d)
-    return need
+def robust_blocks_workspace_bytes(n: int, d: int, r: int, B: int) -> int:
+    """Workspace of detox_step_robust_blocks."""
+    return workspace_bytes("step_robust_blocks", n // max(r, 1), d, B)
 
 
 def detox_step_robust_blocks(G, r: int, B: int, a0: str, f: int, m: int = -1, group_rows=None, vote_perm=None,
-                             out=None, ws=None, gram_in_pass: bool = True):
+                             out=None, ws=None):
     """Robust aggregator inside every vote group, mean over the groups.
     Returns (out[d], winner[n/r], block_out[B x d] or None, selected[n/r])."""
     torch = _torch()
@@ -352,7 +346,7 @@ def detox_step_robust_blocks(G, r: int, B: int, a0: str, f: int, m: int = -1, gr
     block_out = torch.empty((B, d), dtype=torch.float32, device=G.device) if B > 1 else None
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=G.device)
-    ws, nb = _ws(ws, robust_blocks_workspace_bytes(n, d, r, B, gram_in_pass), G.device)
+    ws, nb = _ws(ws, robust_blocks_workspace_bytes(n, d, r, B), G.device)
     rc = lib().detox_step_robust_blocks(p, n, d, ld, r, _ptr(gr), B, _ptr(vp), AGG[a0], f, m, _ptr(winner),
                                         _ptr(block_out), d, _ptr(selected), _ptr(out), _ptr(ws), nb, _stream())
     _check(rc, "detox_step_robust_blocks")

@@ -87,19 +87,23 @@ def build(jobs: int = 8, force: bool = True) -> str:
     return LIB
 
 
-EXAMPLE_SRC = os.path.join(HERE, "..", "examples", "detox_step_main.cpp")
-EXAMPLE_BIN = os.path.join(HERE, "..", "examples", "detox_step_main")
+EXAMPLES = ["detox_step_main", "detox_calls_main"]
 
 
-def build_example() -> str:
-    """The C-ABI-only caller under examples/ (HIP runtime + libdetox.so, no Python, no torch)."""
-    cmd = [HIPCC, "-O2", "-std=c++17", "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", EXAMPLE_SRC,
-           "-o", EXAMPLE_BIN, "-L" + HERE, "-ldetox", "-L/opt/rocm/lib", "-lamdhip64",
-           "-Wl,-rpath," + HERE, "-Wl,-rpath,/opt/rocm/lib"]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("building the example failed:\n" + r.stdout + r.stderr)
-    return EXAMPLE_BIN
+def build_example() -> list:
+    """The C-ABI-only callers under examples/ (HIP runtime + libdetox.so, no Python, no torch)."""
+    out = []
+    for name in EXAMPLES:
+        src = os.path.join(HERE, "..", "examples", name + ".cpp")
+        exe = os.path.join(HERE, "..", "examples", name)
+        cmd = [HIPCC, "-O2", "-std=c++17", "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", src,
+               "-o", exe, "-L" + HERE, "-ldetox", "-L/opt/rocm/lib", "-lamdhip64",
+               "-Wl,-rpath," + HERE, "-Wl,-rpath,/opt/rocm/lib"]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"building the example {name} failed:\n" + r.stdout + r.stderr)
+        out.append(exe)
+    return out
 
 
 if __name__ == "__main__":

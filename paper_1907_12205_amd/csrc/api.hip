@@ -1,6 +1,7 @@
 // C ABI of libdetox (declared in include/detox.h): argument validation, workspace carving and
 // the order in which the kernels of one call are enqueued.  No arithmetic of the method lives
 // here; every step runs in the kernels of the other translation units.
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -17,7 +18,8 @@ struct TraceRec {
     const char *name;
     hipEvent_t start, stop;
 };
-bool g_trace_on = false;
+std::atomic<bool> g_trace_on{false};
+std::mutex g_trace_lock;            // guards g_trace
 std::vector<TraceRec> g_trace;
 
 int status_of(hipError_t e)
@@ -60,6 +62,18 @@ size_t aggregator_ws_bytes(int64_t count, int64_t d)
     return round_up(gram_partial_bytes(count, d)) + round_up(c2 * sizeof(double)) * 3 +
            round_up(c2 * sizeof(int32_t)) + round_up((size_t)count * sizeof(double)) * 2 +
            round_up((size_t)count * sizeof(int32_t)) * 2 + round_up(pass_gram_bytes(count));
+}
+
+// detox_step_robust_blocks: filter + row table of the votes + the aggregator of the largest vote
+// group, and with 9..16 votes the aggregator workspace of all votes, whose Gram matrix the filter
+// pass forms on the side and the vote groups cut theirs out of.
+size_t robust_blocks_bytes(int64_t groups, int64_t d, int64_t B)
+{
+    if (groups < 1 || B < 1 || B > groups || d < 1) return 0;
+    const int64_t largest = (groups + B - 1) / B;
+    if (largest > kMaxCount) return 0;
+    return filter_bytes(groups) + round_up((size_t)groups * sizeof(int32_t)) + aggregator_ws_bytes(largest, d) +
+           (pass_gram_bytes(groups) ? aggregator_ws_bytes(groups, d) : 0);
 }
 
 struct AggWs {
@@ -168,20 +182,25 @@ int check_filter_args(const float *G, int64_t n, int64_t d, int64_t ld, int r)
 
 }  // namespace
 
-bool trace_enabled() { return g_trace_on; }
+bool trace_enabled() { return g_trace_on.load(std::memory_order_relaxed); }
 
+// The record list is shared by all threads and guarded by a lock; a TraceScope keeps the lock from
+// its begin to its end, so that the two events of a launch stay paired when several threads trace.
 void trace_begin(const char *name, hipStream_t s)
 {
+    g_trace_lock.lock();
     TraceRec r;
     r.name = name;
-    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
-    (void)hipEventRecord(r.start, s);
+    r.start = r.stop = nullptr;
+    if (hipEventCreate(&r.start) == hipSuccess && hipEventCreate(&r.stop) == hipSuccess)
+        (void)hipEventRecord(r.start, s);
     g_trace.push_back(r);
 }
 
 void trace_end(hipStream_t s)
 {
-    if (!g_trace.empty()) (void)hipEventRecord(g_trace.back().stop, s);
+    if (!g_trace.empty() && g_trace.back().stop != nullptr) (void)hipEventRecord(g_trace.back().stop, s);
+    g_trace_lock.unlock();
 }
 
 int num_compute_units()
@@ -261,6 +280,7 @@ size_t detox_workspace_bytes(int op, int64_t count, int64_t d, int64_t aux)
         if (aux < 1 || aux > kMaxCount) return 0;
         return filter_bytes(count) + aggregator_ws_bytes(aux, d);
     }
+    case DETOX_OP_STEP_ROBUST_BLOCKS: return robust_blocks_bytes(count, d, aux);
     case DETOX_OP_BLOCK_MEAN:
     case DETOX_OP_COORD_MEDIAN: return 0;
     default: return 0;
@@ -349,6 +369,7 @@ int robust_bulyan(const float *X, int64_t count, int64_t d, int64_t ld, int f, f
         return DETOX_EINVAL;
     if (count < 4 * (int64_t)f + 3) return DETOX_EPRECOND;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count, d))) return DETOX_EWORKSPACE;
+    if (hipError_t e = prepare_selection_kernels(); e != hipSuccess) return status_of(e);
     return bulyan_impl(direct_rows(X, count, d, ld), f, out, selected, ws, FusedGram{},
                        static_cast<hipStream_t>(stream));
 }
@@ -376,6 +397,7 @@ int robust_geomedian(const float *X, int64_t count, int64_t d, int64_t ld, int i
     if (!matrix_ok(X, count, d, ld) || !out || count > kMaxCount || iters < 0 || !(eps > 0.0))
         return DETOX_EINVAL;
     if (!ws_ok(ws, ws_bytes, aggregator_ws_bytes(count, d))) return DETOX_EWORKSPACE;
+    if (hipError_t e = prepare_selection_kernels(); e != hipSuccess) return status_of(e);
     return geomedian_impl(direct_rows(X, count, d, ld), iters, eps, out, ws, FusedGram{},
                           static_cast<hipStream_t>(stream));
 }
@@ -422,10 +444,13 @@ static int step_impl(const float *G, int64_t n, int64_t d, int64_t ld, int r, in
         if (!selected) return DETOX_EINVAL;
         if (f < 0) {
             // Byzantine votes that can survive the filter: each needs (r+1)/2 Byzantine members
+            // (Appendix A.1).  If the aggregator cannot take that many among B rows (Appendix B.1:
+            // B >= 2f+3 for Multi-Krum, 4f+3 for Bulyan), the step is refused rather than run with a
+            // smaller f than the votes may need.
             const int64_t survive = q / ((r + 1) / 2);
             const int64_t cap = agg == DETOX_AGG_MULTIKRUM ? (B - 3) / 2 : (B - 3) / 4;
-            if (B < 3) return DETOX_EPRECOND;
-            f = (int)(survive < cap ? survive : cap);
+            if (B < 3 || survive > cap) return DETOX_EPRECOND;
+            f = (int)survive;
         }
         if (agg == DETOX_AGG_MULTIKRUM) {
             if (m < 0) m = (int)B - f;
@@ -444,6 +469,7 @@ static int step_impl(const float *G, int64_t n, int64_t d, int64_t ld, int r, in
         ws_bytes = kStaticScratchBytes;
     }
     if (!ws_ok(ws, ws_bytes, fbytes + abytes)) return DETOX_EWORKSPACE;
+    if (hipError_t pe = prepare_selection_kernels(); pe != hipSuccess) return status_of(pe);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
@@ -545,12 +571,11 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
     }
     const size_t fbytes = filter_bytes(groups);
     const size_t tbytes = round_up((size_t)groups * sizeof(int32_t));
-    const size_t base_bytes = fbytes + tbytes + aggregator_ws_bytes(largest, d);
-    if (!ws_ok(ws, ws_bytes, base_bytes)) return DETOX_EWORKSPACE;
-    // 9..16 votes and room for one more aggregator workspace (of n/r rows): the Gram matrix of all
-    // votes comes out of the filter pass and every vote group cuts its own matrix out of it
-    const size_t all_bytes = pass_gram_bytes(groups) ? aggregator_ws_bytes(groups, d) : 0;
-    const bool in_pass = all_bytes != 0 && ws_bytes >= base_bytes + all_bytes;
+    if (!ws_ok(ws, ws_bytes, robust_blocks_bytes(groups, d, B))) return DETOX_EWORKSPACE;
+    // 9..16 votes: the Gram matrix of all votes comes out of the filter pass and every vote group
+    // cuts its own matrix out of it (what is computed never depends on the size of the workspace)
+    const bool in_pass = pass_gram_bytes(groups) != 0;
+    if (hipError_t pe = prepare_selection_kernels(); pe != hipSuccess) return status_of(pe);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
@@ -635,11 +660,12 @@ int detox_sign_majority(const uint32_t *S, int64_t n, int64_t d, int64_t ldw, in
 
 void detox_trace_enable(int on)
 {
-    g_trace_on = on != 0;
-    if (!g_trace_on) {
+    g_trace_on.store(on != 0);
+    if (on == 0) {
+        std::lock_guard<std::mutex> guard(g_trace_lock);
         for (auto &r : g_trace) {
-            (void)hipEventDestroy(r.start);
-            (void)hipEventDestroy(r.stop);
+            if (r.start) (void)hipEventDestroy(r.start);
+            if (r.stop) (void)hipEventDestroy(r.stop);
         }
         g_trace.clear();
     }
@@ -647,17 +673,18 @@ void detox_trace_enable(int on)
 
 int detox_trace_read(detox_trace_record *records, int cap)
 {
+    std::lock_guard<std::mutex> guard(g_trace_lock);
     int k = 0;
     for (auto &r : g_trace) {
         float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) ms = -1.0f;
+        if (!r.start || !r.stop || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) ms = -1.0f;
         if (records && k < cap) {
             records[k].kernel = r.name;
             records[k].ms = ms;
             ++k;
         }
-        (void)hipEventDestroy(r.start);
-        (void)hipEventDestroy(r.stop);
+        if (r.start) (void)hipEventDestroy(r.start);
+        if (r.stop) (void)hipEventDestroy(r.stop);
     }
     g_trace.clear();
     return k;

@@ -207,6 +207,8 @@ struct SelectScratch {   // all dev, carved from the caller's workspace
     double *scores;      // count
     double *weights;     // count
 };
+// One-time, per-device set-up of the selection kernels (their LDS limits); cheap when done.
+hipError_t prepare_selection_kernels();
 hipError_t launch_sqdist_from_gram(const double *Gm, int64_t count, double *D, hipStream_t s);
 hipError_t launch_multikrum_select(const double *Gm, int64_t count, int f, int m,
                                    const SelectScratch &sc, int32_t *selected, double *scores_out,

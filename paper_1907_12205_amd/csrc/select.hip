@@ -1,6 +1,8 @@
 // The count x count part of the robust aggregators (scores, selections, Weiszfeld weights), run
 // by a single workgroup in fp64 so that no host round trip interrupts the stream, and the two
 // streaming kernels that turn a selection / a weight vector into the output d-vector.
+#include <atomic>
+
 #include "rows.h"
 
 namespace detox {
@@ -424,6 +426,35 @@ hipError_t launch_multikrum_select(const double *Gm, int64_t count, int f, int m
     return hipGetLastError();
 }
 
+namespace {
+size_t bulyan_select_lds(int64_t count)
+{
+    return (size_t)count * ((count - 1) | 1) * sizeof(double) + (size_t)count * count + 16;
+}
+}  // namespace
+
+// gfx950 has 160 KB of LDS per workgroup, but a kernel that wants more than 64 KB of dynamic LDS
+// has to say so first.  Done once per device, for the largest row count, the first time any
+// entry point of the library runs there: never inside a launch sequence that a caller may be
+// capturing into a graph after its first, eager call.
+hipError_t prepare_selection_kernels()
+{
+    static std::atomic<bool> done[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(bulyan_select_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bulyan_select_lds(kMaxCount));
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(weiszfeld_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kMaxCount * kMaxCount * sizeof(double)));
+    if (e != hipSuccess) return e;
+    done[dev].store(true, std::memory_order_release);
+    return hipSuccess;
+}
+
 hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const SelectScratch &sc,
                                 int32_t *selected, hipStream_t s)
 {
@@ -433,13 +464,9 @@ hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const Se
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t lds = (size_t)count * ((count - 1) | 1) * sizeof(double) + (size_t)count * count + 16;
-    if (lds > 64 * 1024) {
-        // gfx950 has 160 KB of LDS per workgroup; more than 64 KB has to be asked for
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(bulyan_select_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    const size_t lds = bulyan_select_lds(count);
+    e = prepare_selection_kernels();   // more than 64 KB of LDS has to be asked for (once per device)
+    if (e != hipSuccess) return e;
     TraceScope t("bulyan_select", s);
     bulyan_select_kernel<<<1, kRowThreads, lds, s>>>((int)count, f, sc, selected);
     return hipGetLastError();
@@ -449,11 +476,8 @@ hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double e
                             double *weights, hipStream_t s)
 {
     const size_t lds = (size_t)count * count * sizeof(double);
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(weiszfeld_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    const hipError_t e = prepare_selection_kernels();
+    if (e != hipSuccess) return e;
     const int threads = (int)((count * kWzLanesPerRow + kWave - 1) / kWave) * kWave;
     TraceScope t("weiszfeld_gram", s);
     weiszfeld_kernel<<<1, threads, lds, s>>>(Gm, (int)count, iters, eps, weights);

@@ -46,6 +46,14 @@ def test_workspace_sizes(dx):
     assert 0 < a and 0 < b
     assert dx.workspace_bytes("multikrum", 129, 1000) == 0          # beyond the build's limit
     assert dx.workspace_bytes("step", 45, 1000, 5) == dx.workspace_bytes("filter", 45, 1000) + a
+    # the hierarchy with a robust aggregator inside vote groups: sized by its own selector, from the
+    # number of votes and of vote groups; 15 votes carry the in-pass Gram workspace on top
+    rb15, rb21 = dx.workspace_bytes("step_robust_blocks", 15, 1000, 2), dx.workspace_bytes("step_robust_blocks", 21, 1000, 3)
+    assert rb15 > dx.workspace_bytes("filter", 15, 1000) + dx.workspace_bytes("multikrum", 8, 1000) + dx.workspace_bytes("multikrum", 15, 1000)
+    assert rb21 > dx.workspace_bytes("filter", 21, 1000) + dx.workspace_bytes("multikrum", 7, 1000)
+    assert rb15 % 256 == 0 and dx.workspace_bytes("step_robust_blocks", 15, 1000, 16) == 0      # more groups than votes
+    # more than 64 rows: the Gram partial sums take more slots the longer the rows are
+    assert dx.workspace_bytes("multikrum", 105, 25_000_000) > dx.workspace_bytes("multikrum", 105, 1000)
 
 
 def test_argument_validation_happens_on_the_host(dx):
@@ -72,6 +80,11 @@ def test_argument_validation_happens_on_the_host(dx):
                         p, p, 10, p, p, p, big, None) == EPRECOND                                 # Bulyan on 5 rows, f = 1
     assert L.detox_step(p, 45, 10, 10, 3, 5, None, 16, None, 0, 1, 3, 50, ctypes.c_double(1e-8),
                         p, p, 10, p, p, p, big, None) == EINVAL                                   # B > n/r
+    assert L.detox_step(p, 45, 10, 10, 3, 5, None, 5, None, 0, -1, -1, 50, ctypes.c_double(1e-8),
+                        p, p, 10, p, p, p, big, None) == EPRECOND      # derived f = 2 needs 7 rows for Multi-Krum
+    assert L.detox_step_robust_blocks(p, 45, 10, 10, 3, None, 2, None, 0, 2, 3, p, p, 10, p, p, p,
+                                      dx.workspace_bytes("step_robust_blocks", 15, 10, 2) - 256, None) == EWS
+    assert L.detox_step_robust_blocks(p, 45, 10, 10, 3, None, 2, None, 0, 3, 3, p, p, 10, p, p, p, big, None) == EPRECOND
     # the variant on the library's own scratch array: a step that needs more than the array holds
     # is refused on the host (40 rows for the aggregator: 3 row tiles of Gram partials)
     header = open(os.path.join(ROOT, "include", "detox.h")).read()

@@ -82,3 +82,42 @@ def test_captured_step_sees_new_inputs(dx):
         assert host(buf.winner).tolist() == ref_w.tolist()
         assert np.linalg.norm(host(buf.out) - ref_out) <= 1e-5 * np.linalg.norm(ref_out)
     assert ref_w[0] == 0
+
+
+@pytest.mark.parametrize("which,count", [("bulyan", 105), ("geomedian", 100), ("multikrum", 128)])
+def test_captured_aggregators_on_many_rows(dx, which, count):
+    """Row counts whose selection kernels need more than 64 KB of LDS (the limit is raised once per
+    device, outside any launch sequence): captured after one eager call, replayed, compared."""
+    import torch
+    X = torch.from_numpy(workloads.distinct_rows(5, count, 20_011, sigma=0.03)).cuda()
+    X[3] += 0.05
+    out = torch.empty(X.shape[1], dtype=torch.float32, device=X.device)
+    ws = torch.empty(dx.workspace_bytes(which, count, X.shape[1]), dtype=torch.uint8, device=X.device)
+    f = 10
+
+    def call():
+        if which == "bulyan":
+            return dx.robust_bulyan(X, f, out=out, ws=ws)[1]
+        if which == "multikrum":
+            return dx.robust_multikrum(X, f, count - f, out=out, ws=ws, with_scores=False)[1]
+        dx.robust_geomedian(X, 30, 1e-8, out=out, ws=ws)
+        return None
+
+    sel = call()
+    torch.cuda.synchronize()
+    want_out = out.clone()
+    want_sel = None if sel is None else sel.clone()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            sel_g = call()
+    for i in range(3):
+        out.zero_()
+        scratch = torch.randn(1 << 16, device=X.device).sum()      # eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert scratch.isfinite()
+        assert torch.equal(out, want_out), f"replay {i}"
+        if want_sel is not None:
+            assert torch.equal(sel_g, want_sel), f"replay {i}"

@@ -94,9 +94,16 @@ def test_step_derives_f_and_m(dx):
     ref_out, _, ref_Zh = oracle.detox_step(G, 3, 15, "bulyan", f=2)
     b = dx.detox_step(Gd, 3, 5, 15, "bulyan")
     assert rel_l2(host(b.out), ref_out) <= TOL
-    ref_out, _, _ = oracle.detox_step(G, 3, 5, "multikrum", f=1, m=4)     # capped by (5-3)/2
-    b = dx.detox_step(Gd, 3, 5, 5, "multikrum")
+    ref_out, _, _ = oracle.detox_step(G, 3, 7, "multikrum", f=2, m=5)     # 7 = 2*2+3 rows: just enough
+    b = dx.detox_step(Gd, 3, 5, 7, "multikrum")
     assert rel_l2(host(b.out), ref_out) <= TOL
+    # 5 rows admit only f = 1 < 2: refused rather than run with a smaller f (Appendix B.1's requirements)
+    with pytest.raises(dx.DetoxError) as err:
+        dx.detox_step(Gd, 3, 5, 5, "multikrum")
+    assert err.value.code == 2
+    with pytest.raises(dx.DetoxError) as err:
+        dx.detox_step(Gd, 3, 5, 7, "bulyan")
+    assert err.value.code == 2
 
 
 def test_step_output_ignores_byzantine_content(dx):
@@ -253,17 +260,16 @@ def test_robust_aggregator_inside_vote_groups(dx, a0, B, f, m):
     rng = np.random.default_rng(B * 10 + f)
     # with and without a group that has no majority (its vote is the zero vector; the Gram matrix
     # formed in the filter pass is then replaced), with and without a vote permutation, aligned
-    # and unaligned rows, and with the smaller workspace that keeps the Gram matrices out of the pass
-    for broken, vote_perm, ld, in_pass in ((True, None, None, True), (True, rng.permutation(15).astype(np.int32), 40064, True),
-                                           (False, None, 40064, True), (False, rng.permutation(15).astype(np.int32), 40064, True),
-                                           (False, None, None, True), (False, None, 40064, False), (True, None, 40064, False)):
+    # rows (Gram matrix of the 15 votes formed in the filter pass) and unaligned ones (formed per group)
+    for broken, vote_perm, ld in ((True, None, None), (True, rng.permutation(15).astype(np.int32), 40064),
+                                  (False, None, 40064), (False, rng.permutation(15).astype(np.int32), 40064),
+                                  (False, None, None), (False, None, 40065), (True, None, 40065)):
         G = w.matrix()
         if broken:
             G[12] = 7; G[13] = 8; G[14] = 9
         ref_out, ref_w, ref_blocks, ref_sels = oracle.detox_step_robust_blocks(G, 3, B, a0, f, m, vote_perm=vote_perm)
         for _ in range(1):
-            out, winner, blocks, selected = dx.detox_step_robust_blocks(dev_matrix(G, ld), 3, B, a0, f, m, vote_perm=vote_perm,
-                                                                        gram_in_pass=in_pass)
+            out, winner, blocks, selected = dx.detox_step_robust_blocks(dev_matrix(G, ld), 3, B, a0, f, m, vote_perm=vote_perm)
             assert host(winner).tolist() == ref_w.tolist()
             sel = host(selected)
             for b, rs in enumerate(ref_sels):
