@@ -120,7 +120,7 @@ struct FusedGram {
     int blocks = 0;
     const int *redo = nullptr;
     bool reduced = false;   // Gm (and the Multi-Krum selection) already produced unless *redo
-    int vote_waves = 0;     // > 0: MFMA tiles of the votes' Gram matrix in AggWs::pass_gram (unless *redo)
+    int vote_waves = 0;     // > 0: MFMA tiles of the rows' Gram matrix in AggWs::pass_gram (unless *redo)
     const double *whole = nullptr;   // non-null: Gram matrix (whole_ld wide) of a row set of which
     int whole_ld = 0, whole_off = 0; //   these rows are the run starting at whole_off
 };
@@ -433,8 +433,11 @@ static int step_impl(const float *G, int64_t n, int64_t d, int64_t ld, int r, in
     const int64_t groups = n / r;
     if (!winner || !out || (Zhat && ldo < d) || B < 1 || B > groups || B > kMaxCount || q < 0)
         return DETOX_EINVAL;
-    // without Zhat the aggregator reads votes (B = n/r) or re-forms the means of few vote groups
-    if (!Zhat && B != groups && (B > 8 || groups > kFusedMaxVotes)) return DETOX_EINVAL;
+    // without Zhat the aggregator reads votes (B = n/r) or re-forms the means of up to 32 vote
+    // groups on the fly (beyond 8 of them only from 16-byte aligned rows)
+    if (!Zhat && B != groups &&
+        (groups > kFusedMaxVotes || B > kMeansOnTheFlyMaxRows || (B > 8 && row_vec_width(G, ld) != 4)))
+        return DETOX_EINVAL;
     if (agg < DETOX_AGG_MULTIKRUM || agg > DETOX_AGG_TRIMMED_MEAN) return DETOX_EINVAL;
     if (agg == DETOX_AGG_TRIMMED_MEAN) {
         if (f < 0) f = (int)(B / 4);   // alpha = 1/4 (Theorem 3, part 3)
@@ -483,10 +486,6 @@ static int step_impl(const float *G, int64_t n, int64_t d, int64_t ld, int r, in
     // kernel needs them (that is the faster way on this chip).
     FilterWant want = agg == DETOX_AGG_COORD_MEDIAN ? FilterWant::kMedian
                       : (agg == DETOX_AGG_TRIMMED_MEAN ? FilterWant::kTrimmed : FilterWant::kGram);
-    if (Zhat == nullptr && (B > 8 || groups > kFusedMaxVotes)) {   // B = n/r: the rows are the votes
-        const bool gram_based = agg == DETOX_AGG_MULTIKRUM || agg == DETOX_AGG_BULYAN || agg == DETOX_AGG_GEOMEDIAN;
-        want = gram_based && aw.pass_gram != nullptr ? FilterWant::kVotesGram : FilterWant::kVotes;
-    }
     FilterDone done;
     // what the finalize kernel can do on the side when the Gram matrix comes with the pass
     SmallSelect tail{nullptr, 0, 0, 0, (int)B, aw.Gm, f, agg == DETOX_AGG_MULTIKRUM ? m : 0, aw.sc.scores, selected};
@@ -518,7 +517,7 @@ static int step_impl(const float *G, int64_t n, int64_t d, int64_t ld, int r, in
     fg.blocks = done.gram_blocks;
     fg.redo = fw.redo;
     fg.reduced = done.gram_reduced;
-    fg.vote_waves = done.vote_gram_waves;
+    fg.vote_waves = done.pass_gram_waves;
     switch (agg) {
     case DETOX_AGG_MULTIKRUM: return multikrum_impl(rs, f, m, out, selected, nullptr, aws, fg, s);
     case DETOX_AGG_BULYAN: return bulyan_impl(rs, f, out, selected, aws, fg, s);
@@ -586,7 +585,7 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
                    fw.flags, fw.flag_partials, fw.gram_partials, fw.redo, winner, nullptr, 0,
                    in_pass ? all.pass_gram : nullptr};
     FilterDone done;
-    hipError_t e = launch_filter(p, in_pass ? FilterWant::kVotesGram : FilterWant::kVotes, nullptr, &done, s);
+    hipError_t e = launch_filter(p, in_pass ? FilterWant::kGram : FilterWant::kVotes, nullptr, &done, s);
     if (e != hipSuccess) return status_of(e);
     // row table of the votes in vote order: winner itself, or winner o vote_perm
     const int32_t *table = winner;
@@ -597,9 +596,9 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
         table = t;
     }
     FusedGram fg;
-    if (done.vote_gram_waves > 0) {
+    if (done.pass_gram_waves > 0) {
         const RowSet votes{G, d, ld, (int)n, (int)groups, table, nullptr, nullptr, 0};
-        e = launch_gram_after_pass(votes, all.partials, all.pass_gram, done.vote_gram_waves, fw.redo, all.Gm, s);
+        e = launch_gram_after_pass(votes, all.partials, all.pass_gram, done.pass_gram_waves, fw.redo, all.Gm, s);
         if (e != hipSuccess) return status_of(e);
         fg.whole = all.Gm;
         fg.whole_ld = (int)groups;

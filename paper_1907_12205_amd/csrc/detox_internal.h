@@ -14,6 +14,7 @@ constexpr int kMaxCount = 128;         // rows per robust aggregation
 constexpr int kFusedMaxVotes = 1024;   // node groups the persistent filter kernel handles
 constexpr int kFusedMaxGrid = 2048;    // its largest grid (sizes the per-workgroup slots)
 constexpr int kPassGramMaxVotes = 16;  // votes whose Gram matrix the filter pass can form on the side
+constexpr int kMeansOnTheFlyMaxRows = 32;  // block means later kernels re-form from the winner rows instead of reading them
 constexpr int kPassGramMaxWaves = 4096;  // wavefront tiles it may write (sizes the workspace)
 constexpr int kRowParMaxD = 2048;      // widest rows the row-parallel filter / block mean take
 constexpr int kManyGeomedianMaxD = 128;       // widest rows of the streaming Weiszfeld kernels
@@ -115,7 +116,7 @@ struct FilterParams {
     int32_t *winner;                    // dev, n_votes
     float *out;                         // dev, d: coordinate-wise median / trimmed mean (those modes)
     int trim_g;                         // trimmed-mean mode: values dropped at each end
-    float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats (kVotesGram)
+    float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats (Gram matrix of 9..16 votes)
 };
 struct FilterWs {
     int *redo;
@@ -127,26 +128,25 @@ FilterWs carve_filter_ws(void *ws, int64_t n_votes);
 // What one pass over G should produce besides winner[] and *redo.
 enum class FilterWant {
     kVotes,    // nothing else
-    kVotesGram,  // every vote its own block (B = n_votes <= kPassGramMaxVotes): the Gram matrix of the
-               //   votes as per-wavefront MFMA tiles in vote_gram_partials; degrades to kVotes
     kMeans,    // block means in Zhat (must be non-null)
-    kGram,     // block means (in Zhat if non-null) and, when B <= 8, the Gram matrix of the means
+    kGram,     // block means (in Zhat if non-null) and their Gram matrix: fp64 partial sums for
+               //   B <= 8; for 9 .. kPassGramMaxVotes votes, each its own block (Zhat null, 16-byte
+               //   aligned rows, vote_gram_partials non-null): fp32 MFMA tiles per wavefront there
     kMedian,   // block means (in Zhat if non-null) and, when B <= 8, their coordinate-wise median
     kTrimmed   // the same with the coordinate-wise trimmed mean (FilterParams::trim_g per end)
 };
+// Where the extra cannot be had, the pass degrades to kMeans (Zhat non-null) or to kVotes (Zhat
+// null: later kernels read the winner rows and re-form the means they need).
 struct FilterDone {
     bool means_exact = false;     // Zhat already holds the exact block means (no fix-up of blocks
                                   //   with a vote without majority is needed)
-    int gram_blocks = 0;          // > 0: Gram partial slots written (kGram honoured)
+    int gram_blocks = 0;          // > 0: fp64 Gram partial slots written (B <= 8)
     bool gram_reduced = false;    // the finalize kernel already produced Gm (and, if asked, the
                                   //   Multi-Krum selection) unless *redo
     bool median_written = false;  // kMedian / kTrimmed honoured: `out` holds the result unless *redo
-    int vote_gram_waves = 0;      // > 0: kVotesGram honoured, that many wavefront tiles written (valid
-                                  //   unless *redo)
+    int pass_gram_waves = 0;      // > 0: that many wavefronts wrote MFMA Gram tiles (valid unless *redo)
 };
 struct SmallSelect;               // small_select.h: what the finalize kernel should go on to do
-// kGram / kMedian with B > 8 (or more than kFusedMaxVotes groups) degrade to kMeans; then Zhat
-// must be non-null (hipErrorInvalidValue otherwise).
 //   tail (may be null): with kGram honoured, the finalize kernel also reduces the Gram partials
 //   into tail->Gm and, if tail->krum_m > 0, runs Multi-Krum's scoring and selection, all skipped
 //   when *redo gets set.
@@ -179,7 +179,7 @@ hipError_t launch_many_geomedian(const float *X, int64_t count, int64_t d, int64
 size_t gram_partial_bytes(int64_t count, int64_t d);
 // Gram matrix Gm[a][b] = <x_a, x_b> of the logical rows (count x count doubles, full, symmetric).
 hipError_t launch_gram(const RowSet &rs, void *partials, double *Gm, hipStream_t s);
-// count <= 16 rows whose Gram tiles the filter pass has written (pass_waves wavefront tiles in
+// 9 .. kPassGramMaxVotes rows whose Gram tiles the filter pass has written (pass_waves wavefront tiles in
 // pass_partials, valid unless *redo): adds them up into Gm; if *redo, the matrix is first formed
 // again from the rows (one more launch, which does nothing otherwise).
 hipError_t launch_gram_after_pass(const RowSet &rs, void *partials, const float *pass_partials,

@@ -652,8 +652,8 @@ FilterWs carve_filter_ws(void *ws, int64_t n_votes)
 hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tail, FilterDone *done,
                          hipStream_t s)
 {
-    const bool mean = want != FilterWant::kVotes && want != FilterWant::kVotesGram;
     if (row_parallel(p.d, p.n_votes)) {
+        const bool mean = want != FilterWant::kVotes;
         if (mean && p.Zhat == nullptr) return hipErrorInvalidValue;
         if (done) {
             *done = FilterDone{};
@@ -675,18 +675,21 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
     // few vote groups.  A pure filter is the same kernel with every group its own block.
     const bool fused = p.n_votes <= kFusedMaxVotes;
     int mode = kFilterOnly, nb = 0;
-    const bool votes_gram = want == FilterWant::kVotesGram && fused && p.B == p.n_votes &&
-                            p.n_votes <= kPassGramMaxVotes && vec == 4 && p.vote_gram_partials != nullptr;
-    if (want == FilterWant::kVotesGram) {
-        if (votes_gram) mode = kVotesGram;
-    } else if (mean) {
+    if (want != FilterWant::kVotes) {
         mode = kMeans;
         if (fused && p.B <= 8 && want == FilterWant::kGram) mode = kGram, nb = (int)p.B;
         if (fused && p.B <= 8 && want == FilterWant::kMedian) mode = kMedian, nb = (int)p.B;
         if (fused && p.B <= 8 && want == FilterWant::kTrimmed) mode = kTrimmedMean, nb = (int)p.B;
+        // 9 .. 16 votes, each its own block and none wanted in memory: their Gram matrix on the side
+        if (fused && want == FilterWant::kGram && p.B == p.n_votes && p.B > 8 && p.B <= kPassGramMaxVotes &&
+            p.Zhat == nullptr && vec == 4 && p.vote_gram_partials != nullptr)
+            mode = kVotesGram;
+        // nothing on the side: plain block means if they are wanted in memory, else the votes
+        // alone (later kernels read the winner rows and re-form the means they need)
+        if (mode == kMeans && p.Zhat == nullptr) mode = kFilterOnly;
     }
-    // without a register mode the means must go to memory
-    if (mode == kMeans && p.Zhat == nullptr) return hipErrorInvalidValue;
+    const bool mean = mode == kMeans;
+    const bool votes_gram = mode == kVotesGram;
     if (done) *done = FilterDone{};
     hipError_t e;
     int grid = 0;
@@ -734,7 +737,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
             done->gram_blocks = mode == kGram ? grid : 0;
             done->gram_reduced = mode == kGram && tail != nullptr;
             done->median_written = mode == kMedian || mode == kTrimmedMean;
-            done->vote_gram_waves = mode == kVotesGram ? grid * (kBlock / kWave) : 0;
+            done->pass_gram_waves = mode == kVotesGram ? grid * (kBlock / kWave) : 0;
         }
     } else {
         filter_finalize_kernel<<<(unsigned)((p.n_votes + 255) / 256), 256, 0, s>>>(

@@ -162,8 +162,9 @@ hipError_t launch_nv(const RowSet &rs, const int32_t *rows, int beta, float *out
                      unsigned chunks, hipStream_t s)
 {
     if (rs.means()) {
-        // block means formed on the fly: only offered for the few rows of a hierarchical step
-        if constexpr (N <= 8)
+        // block means formed on the fly: offered for the row counts a hierarchical step can have
+        // without writing its block means to memory
+        if constexpr (N <= kMeansOnTheFlyMaxRows)
             order_stat_kernel<N, VEC, MODE, true><<<chunks, kBlock, 0, s>>>(rs, rows, beta, out, run_if);
         else
             return hipErrorInvalidValue;

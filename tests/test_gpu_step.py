@@ -332,3 +332,39 @@ def test_step_over_15_votes_with_a_common_offset(dx, aggregator, k):
         spec.update(f=2)
     _run(dx, w, spec, G=G, ld=(d + 63) // 64 * 64, materialise=False)
     _run(dx, w, spec, G=G, materialise=False, vote_perm=rng.permutation(15).astype(np.int32))
+
+
+WIDE = [dict(aggregator="multikrum", f=2, m=5), dict(aggregator="bulyan", f=1), dict(aggregator="coord_median"),
+        dict(aggregator="geomedian", iters=20), dict(aggregator="trimmed_mean", f=-1)]
+
+
+@pytest.mark.parametrize("spec", WIDE, ids=lambda s: s["aggregator"])
+@pytest.mark.parametrize("n,r,B", [(105, 5, 9), (105, 5, 10), (105, 5, 16), (105, 5, 17), (105, 5, 20), (105, 5, 21),
+                                   (45, 3, 9), (45, 3, 12), (96, 3, 32), (96, 3, 31)])
+def test_step_with_9_to_32_vote_groups_and_no_block_means_in_memory(dx, spec, n, r, B):
+    """Algorithm 2 with any number of vote groups up to 32 while the block means stay out of memory
+    (Zhat = NULL): the pass only votes, later kernels (Gram matrix, order statistics, averages)
+    re-form the means from the winner rows.  With a group without
+    majority (repair path), a Byzantine vote that survives, a vote permutation, and once with the
+    means written out as well."""
+    import torch
+    groups = n // r
+    d = 40_003
+    rng = np.random.default_rng(1000 * n + B)
+    base = (rng.standard_normal((groups, d)) * 0.05 + 0.5).astype(np.float32)
+    w = workloads.Workload("wide", n, r, 4, d, base, {})
+    spec = dict(spec, B=B)
+    if spec["aggregator"] == "trimmed_mean":
+        spec["f"] = B // 4
+    ld = (d + 63) // 64 * 64
+    for broken in (False, True):
+        G = np.repeat(base, r, axis=0)
+        G[0] = 3.0                                       # outvoted (r >= 3)
+        G[r * 2] = G[r * 2 + 1] = -2.0                   # two colluding members: a Byzantine vote (majority only if r = 3)
+        if broken:
+            for k in range(r):
+                G[r * 5 + k] = float(k)                  # group 5: all members differ
+        vote_perm = rng.permutation(groups).astype(np.int32)
+        _run(dx, w, spec, G=G, ld=ld, materialise=False)
+        _run(dx, w, spec, G=G, ld=ld, materialise=False, vote_perm=vote_perm)
+    _run(dx, w, spec, G=G, ld=ld, materialise=True, vote_perm=vote_perm)
