@@ -395,12 +395,15 @@ def main():
             del Gu
         if groups >= 5:
             # signSGD pairing: one sign bit per coordinate, two levels of coordinate-wise majority vote
-            S = torch.from_numpy(workloads.pack_signs(w.matrix()).view(np.int32)).to(G.device)
+            Sh = workloads.pack_signs(w.matrix(), pad_words=4)       # rows 16-byte aligned: 16-byte loads in the filter
+            Sbuf = torch.zeros((n, Sh.strides[0] // 4), dtype=torch.int32, device=G.device)
+            S = Sbuf[:, : Sh.shape[1]]
+            S.copy_(torch.from_numpy(np.ascontiguousarray(Sh).view(np.int32)))
             ws_s = torch.empty(dx.workspace_bytes("filter", groups, S.shape[1]), dtype=torch.uint8, device=G.device)
             out_s = torch.empty((2, S.shape[1]), dtype=torch.int32, device=G.device)
             timed("DETOX + signSGD majority vote, bit-packed signs, B=5",
                   lambda: dx.detox_sign_majority(S, d, r, 5, ws=ws_s, out=out_s), (n + 2) / 32)
-            del S
+            del S, Sbuf
 
     mean_est = None
     if not args.no_others and not args.no_mean_estimation and not args.only:

@@ -647,13 +647,17 @@ int detox_sign_majority(const uint32_t *S, int64_t n, int64_t d, int64_t ldw, in
     if (!ws_ok(ws, ws_bytes, filter_bytes(groups))) return DETOX_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
-    // the filter compares bit patterns, so the packed words go through it as they are
-    FilterParams p{reinterpret_cast<const float *>(S), words, ldw, r, group_rows, nullptr, groups,
-                   groups, nullptr, 0, fw.flags, fw.flag_partials, fw.gram_partials, fw.redo,
-                   winner, nullptr, 0};
-    hipError_t e = launch_filter(p, FilterWant::kVotes, nullptr, nullptr, s);
+    // The filter compares bit patterns, so the packed words go through it as they are; where it
+    // can (16-byte aligned rows and outputs) the same pass takes both vote levels from the
+    // per-coordinate majority bits, and the stand-alone vote runs only if some group had no majority.
+    FilterParams p{reinterpret_cast<const float *>(S), words, ldw, r, group_rows, vote_perm, groups,
+                   B, nullptr, 0, fw.flags, fw.flag_partials, fw.gram_partials, fw.redo,
+                   winner, nullptr, 0, nullptr, out_pos, out_neg, d};
+    FilterDone done;
+    hipError_t e = launch_filter(p, FilterWant::kSignVote, nullptr, &done, s);
     if (e == hipSuccess)
-        e = launch_sign_vote(S, d, ldw, winner, vote_perm, (int)groups, (int)B, out_pos, out_neg, s);
+        e = launch_sign_vote(S, d, ldw, winner, vote_perm, (int)groups, (int)B, out_pos, out_neg,
+                             done.sign_written ? fw.redo : nullptr, s);
     return status_of(e);
 }
 

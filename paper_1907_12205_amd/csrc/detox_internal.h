@@ -117,6 +117,8 @@ struct FilterParams {
     float *out;                         // dev, d: coordinate-wise median / trimmed mean (those modes)
     int trim_g;                         // trimmed-mean mode: values dropped at each end
     float *vote_gram_partials;          // dev or null: kPassGramMaxWaves x 256 floats (Gram matrix of 9..16 votes)
+    uint32_t *sign_pos, *sign_neg;      // dev, kSignVote: the two result masks (d = words of 32 coordinates)
+    int64_t sign_d;                     //   number of coordinates (the unused bits of the last word stay clear)
 };
 struct FilterWs {
     int *redo;
@@ -133,7 +135,10 @@ enum class FilterWant {
                //   B <= 8; for 9 .. kPassGramMaxVotes votes, each its own block (Zhat null, 16-byte
                //   aligned rows, vote_gram_partials non-null): fp32 MFMA tiles per wavefront there
     kMedian,   // block means (in Zhat if non-null) and, when B <= 8, their coordinate-wise median
-    kTrimmed   // the same with the coordinate-wise trimmed mean (FilterParams::trim_g per end)
+    kTrimmed,  // the same with the coordinate-wise trimmed mean (FilterParams::trim_g per end)
+    kSignVote  // the rows are bit-packed signs: two levels of coordinate-wise majority vote over the
+               //   per-coordinate majority bits of the node groups, written to sign_pos / sign_neg
+               //   (16-byte aligned rows and outputs, at most 255 votes per group and 255 groups)
 };
 // Where the extra cannot be had, the pass degrades to kMeans (Zhat non-null) or to kVotes (Zhat
 // null: later kernels read the winner rows and re-form the means they need).
@@ -145,6 +150,7 @@ struct FilterDone {
                                   //   Multi-Krum selection) unless *redo
     bool median_written = false;  // kMedian / kTrimmed honoured: `out` holds the result unless *redo
     int pass_gram_waves = 0;      // > 0: that many wavefronts wrote MFMA Gram tiles (valid unless *redo)
+    bool sign_written = false;    // kSignVote honoured: the masks hold the result unless *redo
 };
 struct SmallSelect;               // small_select.h: what the finalize kernel should go on to do
 //   tail (may be null): with kGram honoured, the finalize kernel also reduces the Gram partials
@@ -238,8 +244,9 @@ hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *sc
 
 // ---- signvote.hip ----------------------------------------------------------
 // Two levels of coordinate-wise majority vote over bit-packed sign rows read through winner[].
+//   run_if (dev, may be null): skip unless *run_if.
 hipError_t launch_sign_vote(const uint32_t *S, int64_t d, int64_t ldw, const int32_t *winner,
                             const int32_t *vote_perm, int n_votes, int B, uint32_t *out_pos,
-                            uint32_t *out_neg, hipStream_t s);
+                            uint32_t *out_neg, const int *run_if, hipStream_t s);
 
 }  // namespace detox

@@ -20,6 +20,7 @@
 
 #include "rows.h"
 #include "small_select.h"
+#include "signplanes.h"
 #include "sortnet.h"
 
 namespace detox {
@@ -135,6 +136,10 @@ __device__ inline int32_t winner_from_bits(unsigned long long bits, const int32_
 //   kMedian     : + block means kept in registers (NB = B <= 8), their coordinate-wise median
 //                 written to `out` (the whole DETOX-median step in one pass over G); Zhat
 //                 written only if non-null.
+//   kSignVote   : the rows are bit-packed signs (Section 5.2, setup 4: DETOX paired with signSGD;
+//                 VEC = 4 words = 128 coordinates per lane): + both levels of the coordinate-wise
+//                 majority vote on bit-sliced counters, from the per-coordinate majority bits of
+//                 the node groups; the two result masks are written directly.
 //   kVotesGram  : every vote its own block, at most 16 votes (VEC = 4 only): + the Gram matrix
 //                 of the votes on the matrix cores.  Each lane holds the per-coordinate majority
 //                 values of all votes for its four columns; they go through a small LDS tile
@@ -143,12 +148,12 @@ __device__ inline int32_t winner_from_bits(unsigned long long bits, const int32_
 //                 l/16), and every wavefront leaves its 16x16 fp32 accumulator tile in
 //                 vote_gram_partials in the layout of the stand-alone Gram kernel.
 // ---------------------------------------------------------------------------------------
-enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3, kTrimmedMean = 4, kVotesGram = 5 };
+enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3, kTrimmedMean = 4, kVotesGram = 5, kSignVote = 6 };
 
 template <int R, int VEC, int NB, int MODE>
 __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
 {
-    constexpr bool MEAN = MODE != kFilterOnly && MODE != kVotesGram;
+    constexpr bool MEAN = MODE != kFilterOnly && MODE != kVotesGram && MODE != kSignVote;
     constexpr bool REGS = MODE == kGram || MODE == kMedian || MODE == kTrimmedMean;   // means of all blocks in registers
     constexpr int NP = MODE == kGram ? NB * (NB + 1) / 2 : 1;
     static_assert(!REGS || NB > 0, "register modes need the block count at compile time");
@@ -199,6 +204,58 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
                     store_floats<VEC>(p.Zhat + b * p.ldo + col, valid, acc);
             }
         };
+        if constexpr (MODE == kSignVote) {
+            // counts of +1 and -1 verdicts of the vote groups, per coordinate, as bit planes
+            uint32_t plus[VEC][kPlanes], minus[VEC][kPlanes];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+#pragma unroll
+                for (int k = 0; k < kPlanes; ++k) plus[i][k] = minus[i][k] = 0u;
+            for (int64_t b = 0; b < p.B; ++b) {
+                const int64_t lo = (b * p.n_votes) / p.B, hi = ((b + 1) * p.n_votes) / p.B;
+                uint32_t ones[VEC][kPlanes];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+#pragma unroll
+                    for (int k = 0; k < kPlanes; ++k) ones[i][k] = 0u;
+                for (int64_t pos = lo; pos < hi; ++pos) {
+                    const int64_t j = p.vote_perm ? p.vote_perm[pos] : pos;
+                    uint32_t x[R][VEC];
+                    const unsigned long long wave_bits = load_group<R, VEC>(p, j, col, valid, full, x);
+                    if (wave_bits != 0ull && lane == 0) atomicOr(&sbits[j], wave_bits);   // LDS, integer
+                    // the vote's bits wherever the group has a majority vector (else: redone later)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) planes_add(ones[i], bitwise_majority<R, VEC>(x, i));
+                }
+                const int votes = (int)(hi - lo);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    planes_add(plus[i], planes_gt_const(ones[i], votes / 2));
+                    planes_add(minus[i], planes_lt_const(ones[i], (votes + 1) / 2));
+                }
+            }
+            uint32_t pm[VEC], mm[VEC];
+            const int64_t words = p.d;   // the matrix handed to this mode is n x words
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                pm[i] = planes_gt(plus[i], minus[i]);
+                mm[i] = planes_gt(minus[i], plus[i]);
+                if (col + i == words - 1 && (p.sign_d & 31) != 0) {
+                    const uint32_t keep = (1u << (p.sign_d & 31)) - 1u;
+                    pm[i] &= keep;
+                    mm[i] &= keep;
+                }
+            }
+            if (valid == VEC) {
+                *reinterpret_cast<u32x4_t *>(p.sign_pos + col) = u32x4_t{pm[0], pm[1], pm[2], pm[3]};
+                *reinterpret_cast<u32x4_t *>(p.sign_neg + col) = u32x4_t{mm[0], mm[1], mm[2], mm[3]};
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+                    if (i < valid) p.sign_pos[col + i] = pm[i], p.sign_neg[col + i] = mm[i];
+            }
+            continue;
+        }
         if constexpr (MODE == kVotesGram) {
             static_assert(MODE != kVotesGram || VEC == 4, "the tile feed is written for four columns per lane");
             float v[kPassGramMaxVotes][VEC];
@@ -533,6 +590,12 @@ hipError_t launch_fused_rvn(const FilterParams &p, int mode, int *grid, int64_t 
             else
                 return hipErrorInvalidValue;
         }
+        if (mode == kSignVote) {
+            if constexpr (VEC == 4)
+                return launch_fused_mode<R, VEC, 0, kSignVote>(p, "filter_sign_vote", grid, chunks, s);
+            else
+                return hipErrorInvalidValue;
+        }
         if (mode == kMeans)
             return launch_fused_mode<R, VEC, 0, kMeans>(p, "filter_block_mean", grid, chunks, s);
         return launch_fused_mode<R, VEC, 0, kFilterOnly>(p, "filter", grid, chunks, s);
@@ -684,6 +747,12 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         if (fused && want == FilterWant::kGram && p.B == p.n_votes && p.B > 8 && p.B <= kPassGramMaxVotes &&
             p.Zhat == nullptr && vec == 4 && p.vote_gram_partials != nullptr)
             mode = kVotesGram;
+        // packed signs: both vote levels in the pass (else: votes only, the caller votes afterwards)
+        if (want == FilterWant::kSignVote)
+            mode = fused && vec == 4 && p.sign_pos != nullptr && p.sign_neg != nullptr &&
+                           row_vec_width(p.sign_pos, 4) == 4 && row_vec_width(p.sign_neg, 4) == 4
+                       ? kSignVote
+                       : kFilterOnly;
         // nothing on the side: plain block means if they are wanted in memory, else the votes
         // alone (later kernels read the winner rows and re-form the means they need)
         if (mode == kMeans && p.Zhat == nullptr) mode = kFilterOnly;
@@ -738,6 +807,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
             done->gram_reduced = mode == kGram && tail != nullptr;
             done->median_written = mode == kMedian || mode == kTrimmedMean;
             done->pass_gram_waves = mode == kVotesGram ? grid * (kBlock / kWave) : 0;
+            done->sign_written = mode == kSignVote;
         }
     } else {
         filter_finalize_kernel<<<(unsigned)((p.n_votes + 255) / 256), 256, 0, s>>>(

@@ -4,60 +4,10 @@
 // bit-sliced counters: a count per coordinate is held as a few words ("planes"), one bit of the
 // count per plane, and adding a vote, comparing a count with a threshold or two counts with each
 // other are a handful of bitwise operations for 32 coordinates at once.
-#include "detox_internal.h"
+#include "signplanes.h"
 
 namespace detox {
 namespace {
-
-constexpr int kPlanes = 8;   // counts up to 255
-
-__device__ inline void planes_add(uint32_t (&c)[kPlanes], uint32_t x)
-{
-#pragma unroll
-    for (int k = 0; k < kPlanes; ++k) {
-        const uint32_t carry = c[k] & x;
-        c[k] ^= x;
-        x = carry;
-    }
-}
-
-// bit set where count > t
-__device__ inline uint32_t planes_gt_const(const uint32_t (&c)[kPlanes], int t)
-{
-    uint32_t gt = 0u, eq = ~0u;
-#pragma unroll
-    for (int k = kPlanes - 1; k >= 0; --k) {
-        const uint32_t tk = ((t >> k) & 1) ? ~0u : 0u;
-        gt |= eq & c[k] & ~tk;
-        eq &= ~(c[k] ^ tk);
-    }
-    return gt;
-}
-
-// bit set where count < t
-__device__ inline uint32_t planes_lt_const(const uint32_t (&c)[kPlanes], int t)
-{
-    uint32_t lt = 0u, eq = ~0u;
-#pragma unroll
-    for (int k = kPlanes - 1; k >= 0; --k) {
-        const uint32_t tk = ((t >> k) & 1) ? ~0u : 0u;
-        lt |= eq & ~c[k] & tk;
-        eq &= ~(c[k] ^ tk);
-    }
-    return lt;
-}
-
-// bit set where a > b
-__device__ inline uint32_t planes_gt(const uint32_t (&a)[kPlanes], const uint32_t (&b)[kPlanes])
-{
-    uint32_t gt = 0u, eq = ~0u;
-#pragma unroll
-    for (int k = kPlanes - 1; k >= 0; --k) {
-        gt |= eq & a[k] & ~b[k];
-        eq &= ~(a[k] ^ b[k]);
-    }
-    return gt;
-}
 
 // One thread per word (32 coordinates).  Vote group b: ones = number of its votes (with a
 // majority) whose bit is set; its verdict is +1 where 2*ones > valid, -1 where 2*ones < valid.
@@ -67,8 +17,9 @@ __global__ __launch_bounds__(kBlock) void sign_vote_kernel(const uint32_t *S, in
                                                            const int32_t *winner,
                                                            const int32_t *vote_perm, int n_votes,
                                                            int B, uint32_t *out_pos,
-                                                           uint32_t *out_neg)
+                                                           uint32_t *out_neg, const int *run_if)
 {
+    if (run_if && *run_if == 0) return;   // uniform: the filter pass has written the result already
     const int64_t col = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (col >= words) return;
     uint32_t plus[kPlanes], minus[kPlanes];
@@ -103,12 +54,12 @@ __global__ __launch_bounds__(kBlock) void sign_vote_kernel(const uint32_t *S, in
 
 hipError_t launch_sign_vote(const uint32_t *S, int64_t d, int64_t ldw, const int32_t *winner,
                             const int32_t *vote_perm, int n_votes, int B, uint32_t *out_pos,
-                            uint32_t *out_neg, hipStream_t s)
+                            uint32_t *out_neg, const int *run_if, hipStream_t s)
 {
     const int64_t words = (d + 31) / 32;
-    TraceScope t("sign_vote", s);
+    TraceScope t(run_if ? "sign_vote_if_redo" : "sign_vote", s);
     sign_vote_kernel<<<(unsigned)((words + kBlock - 1) / kBlock), kBlock, 0, s>>>(
-        S, words, ldw, d, winner, vote_perm, n_votes, B, out_pos, out_neg);
+        S, words, ldw, d, winner, vote_perm, n_votes, B, out_pos, out_neg, run_if);
     return hipGetLastError();
 }
 

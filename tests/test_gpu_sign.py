@@ -58,3 +58,30 @@ def test_sign_majority_with_abstaining_and_byzantine_votes(dx):
     for B in (5, 15, 1, 4):
         ref = _run(dx, S, w.d, 3, B)
     assert (ref == 0).sum() >= 0
+
+
+@pytest.mark.parametrize("r", [1, 2, 3, 4, 5, 7, 11])
+def test_sign_majority_in_the_filter_pass(dx, r):
+    """Rows padded to a multiple of four words: the filter pass itself takes both vote levels from
+    the per-coordinate majority bits of the node groups (one data-touching launch); with a group
+    without majority the stand-alone vote repairs the result.  Every group size, even ones too."""
+    groups, d = 12, 40_037
+    rng = np.random.default_rng(r)
+    base = rng.standard_normal((groups, d)).astype(np.float32)
+    X = np.repeat(base, r, axis=0)
+    if r >= 3:
+        X[0] = -1.0                                   # outvoted
+        X[r * 4] = 1.0
+    for broken in (False, True):
+        if broken and r >= 2:
+            for k in range(r):                        # group 7: all members differ somewhere
+                X[r * 7 + k, k * 100: k * 100 + 50] *= -1.0
+        S = workloads.pack_signs(X, pad_words=4)
+        ldw = S.strides[0] // 4
+        assert ldw % 4 == 0
+        for B, vp in ((3, None), (12, None), (5, rng.permutation(groups).astype(np.int32)), (1, None)):
+            _run(dx, np.ascontiguousarray(S), d, r, B, vote_perm=vp, ldw=ldw)
+        with dx.trace() as tr:
+            _run(dx, np.ascontiguousarray(S), d, r, 4, ldw=ldw)
+            names = [k for k, _ in tr.records()]
+        assert "filter_sign_vote" in names and "sign_vote_if_redo" in names

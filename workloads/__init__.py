@@ -231,12 +231,15 @@ def integer_rows(seed: int, count: int, d: int, lo: int = -8, hi: int = 8):
     return _rng(seed, _S_BASE).integers(lo, hi + 1, size=(count, d)).astype(np.float32)
 
 
-def pack_signs(X):
+def pack_signs(X, pad_words: int = 1):
     """Bit-pack the signs of a float matrix for the signSGD pairing (input preparation only):
-    bit (c % 32) of word (c // 32) set <=> X[i, c] >= 0; unused bits of the last word are zero."""
+    bit (c % 32) of word (c // 32) set <=> X[i, c] >= 0; unused bits of the last word are zero.
+    pad_words: the row stride is rounded up to a multiple of it (4: rows stay 16-byte aligned);
+    the result is the n x ceil(d/32) view of that buffer."""
     n, d = X.shape
     words = (d + 31) // 32
-    out = np.empty((n, words), dtype=np.uint32)
+    ldw = (words + pad_words - 1) // pad_words * pad_words
+    out = np.zeros((n, ldw), dtype=np.uint32)[:, :words]
     for i in range(n):
         bits = np.zeros(words * 32, dtype=np.uint8)
         bits[:d] = X[i] >= 0
