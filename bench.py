@@ -27,6 +27,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published peak
 MFMA_F32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published peak
 
 
 def measured_traffic(agg, n, d):
@@ -185,15 +186,26 @@ def device_matrix(torch, n, r, d, byz_rows, kind, seed=20190712):
     return G
 
 
-def mfma_roofline(n, d, kernel_ms, mfma_tflops):
-    """The Gram kernel against the fp32 matrix-core peak, on the method's own operations:
-    n(n+1)/2 multiply-adds per column (the padded tiles compute more)."""
+def gram_roofline(n, d, kernel_ms, pr):
+    """The Gram kernel of more than 8 rows.  It reads the rows once (4 n d bytes) and does the
+    method's n(n+1)/2 fp32 multiply-adds per column as six bf16 matrix instructions per 16x16 tile
+    and 32 columns (operands cut into three bf16 pieces): reported against the HBM peak, with the
+    rate on the method's own operations beside the fp32 matrix-core peak it no longer depends on,
+    and the bf16 operations actually issued (padded tiles included) against the bf16 peak."""
     flop = n * (n + 1) / 2 * 2.0 * d
-    achieved = flop / (kernel_ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": "gram_mfma_f32", "achieved": round(achieved, 1), "peak": MFMA_F32_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4),
-            "frac_of_measured_mfma": round(achieved / mfma_tflops, 4) if mfma_tflops else None,
-            "algorithmic_flop_per_launch": flop, "kernel_ms": round(kernel_ms, 5), "traffic": None}
+    tiles = (n + 15) // 16
+    issued = 6.0 * (tiles * (tiles + 1) / 2) * 256 * 2.0 * d
+    sec = kernel_ms * 1e-3
+    gbs = 4.0 * n * d / sec / 1e9
+    return {"bound": "hbm", "kernel": "gram_mfma_bf16x3", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "frac_of_measured_stream": round(gbs / pr["stream_read_GBps"], 4) if pr.get("stream_read_GBps") else None,
+            "method_fp32_TFLOPs": round(flop / sec / 1e12, 1),
+            "method_fp32_vs_fp32_mfma_peak": round(flop / sec / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+            "issued_bf16_TFLOPs": round(issued / sec / 1e12, 1),
+            "issued_bf16_vs_bf16_mfma_peak": round(issued / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "algorithmic_flop_per_launch": flop, "algorithmic_bytes_per_launch": 4.0 * n * d,
+            "kernel_ms": round(kernel_ms, 5), "traffic": None}
 
 
 def big_workloads(dx, workloads, torch, np, steps, pr, only):
@@ -234,10 +246,11 @@ def big_workloads(dx, workloads, torch, np, steps, pr, only):
     if rec is not None:
         km = traced_kernels(dx, fn, 3, np)
         rec["kernel_ms"] = {k: round(v, 5) for k, v in km.items()}
-        if "gram_mfma_f32" in km:
-            rec["roofline"] = mfma_roofline(n, d, km["gram_mfma_f32"], pr["mfma_f32_TFLOPs"])
-            log(f"[bench] Gram kernel of 105 rows: {km['gram_mfma_f32']:.3f} ms = {rec['roofline']['achieved']:.1f} TFLOP/s on "
-                f"the method's operations, {rec['roofline']['frac'] * 100:.1f}% of the fp32 MFMA peak")
+        if "gram_mfma_bf16x3" in km:
+            rec["roofline"] = gram_roofline(n, d, km["gram_mfma_bf16x3"], pr)
+            log(f"[bench] Gram kernel of 105 rows: {km['gram_mfma_bf16x3']:.3f} ms = {rec['roofline']['achieved']:.0f} GB/s "
+                f"({rec['roofline']['frac'] * 100:.1f}% of HBM peak), {rec['roofline']['method_fp32_TFLOPs']:.1f} TFLOP/s on the "
+                f"method's fp32 operations ({rec['roofline']['method_fp32_vs_fp32_mfma_peak'] * 100:.0f}% of the fp32 MFMA peak)")
     res.append({"workload": f"cfg5 shape: n={n}, r={r}, q={q}, d={d}, N(0,1e-3) base, constant +-100 Byzantine rows; "
                             "generated on the device", "paths": legs.rows})
     del G
@@ -348,9 +361,8 @@ def main():
                    "frac_of_measured_stream": round(rows * d * 4 / (ms_v * 1e-3) / 1e9 / pr["stream_read_GBps"], 4),
                    "kernel_ms": {k: round(x, 5) for k, x in vk.items()},
                    "detox_speedup": round(ms_v / ms_step, 3)}
-            if "gram_mfma_f32" in vk:
-                rec["gram_roofline"] = mfma_roofline(n, d, vk["gram_mfma_f32"], pr["mfma_f32_TFLOPs"])
-                rec["gram_hbm_frac"] = round(in_bytes / (vk["gram_mfma_f32"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            if "gram_mfma_bf16x3" in vk:
+                rec["gram_roofline"] = gram_roofline(n, d, vk["gram_mfma_bf16x3"], pr)
             vanilla.append(rec)
             log(f"[bench] vanilla {v['aggregator']}: {ms_v:.4f} ms/step ({rec['hbm_frac_algorithmic'] * 100:.1f}% of HBM peak "
                 f"over {rows} rows); DETOX is {ms_v / ms_step:.2f}x faster")

@@ -10,6 +10,8 @@
 // counter shows to be the last) adds them in a fixed order in fp64.  No floating-point atomics:
 // results repeat bit for bit, and rows
 // that are bit-identical produce bit-identical Gram entries (same products, same order).
+#include <utility>
+
 #include "rows.h"
 #include "small_select.h"
 
@@ -17,16 +19,21 @@ namespace detox {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kMaxGramWaves = 4096;   // upper bound used to size the workspace
 
 __host__ __device__ constexpr int tiles_for(int T) { return T * (T + 1) / 2; }
 
-// Workgroups (of 4 wavefronts) per CU for the MFMA kernel: what its LDS tiles and registers let
-// stay resident (the kernel's launch bounds hold the register count to these numbers).
-constexpr int mfma_blocks_per_cu(int T) { return T <= 2 ? 4 : (T <= 3 ? 3 : 2); }
+// Workgroups (of 4 wavefronts) per CU of the two matrix-core kernels: what their LDS tiles and
+// registers let stay resident (the kernels' launch bounds hold the register count to these numbers).
+constexpr int direct_blocks_per_cu(int T) { return T <= 1 ? 6 : (T <= 2 ? 4 : (T <= 3 ? 5 : (T <= 4 ? 4 : 2))); }
+constexpr int staged_blocks_per_cu(int T) { return T <= 2 ? 4 : (T <= 3 ? 3 : (T <= 4 ? 2 : 1)); }
 // Bound on the wavefront partials (sizes the workspace; assumes at most 256 CUs, more are clamped).
-constexpr int mfma_max_waves(int T) { return 256 * mfma_blocks_per_cu(T) * (kBlock / kWave); }
+constexpr int mfma_max_waves(int T) { return 256 * direct_blocks_per_cu(T) * (kBlock / kWave); }
 
 // ---------------------------------------------------------------------------------------
 // count <= 8: fp64 on the vector ALUs
@@ -129,35 +136,39 @@ __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double 
 }
 
 // ---------------------------------------------------------------------------------------
-// count > 8: fp32 MFMA.  V_MFMA_F32_16X16X4_F32 takes A (16x4) with lane l holding
-// A[l%16][l/16] and B (4x16) with lane l holding B[l/16][l%16]; for a Gram tile both operands
-// are slices of X in the same layout, so one register per row tile feeds both sides.  The
-// accumulator of tile (ti, tj) holds C[4*(l/16)+v][l%16] in component v of lane l.
+// count > 8: the products on the bf16 matrix instructions (sixteen times the rate of the fp32
+// one).  Every fp32 operand is cut into three bf16 pieces, x = h + m + l exactly (h = x rounded to
+// bf16, m = the rest rounded to bf16, l = what is then left: 8 + 8 + 8 significant bits), and x*y
+// is taken as (m*m' + h*l' + l*h' + h*m' + m*h') + h*h'; the three terms left out are below 2^-24
+// of |x*y|.  Products of bf16 values are exact in fp32.  V_MFMA_F32_16X16X32_BF16 truncates when it
+// adds into its accumulator, so the six instructions of 32 columns run small terms first into a
+// fresh accumulator (only the last addition rounds at the size of the result) and that sum is
+// added to the running total by an ordinary rounded fp32 addition: the totals carry no bias that
+// grows with d (an accumulator fed by the instruction alone loses about half a unit in the last
+// place per instruction, all in one direction).
 //
-// A wavefront works on tiles of 64 (or 32) columns of all (padded) rows.  It fetches a tile with
-// loads that are contiguous along the rows (16 lanes x 16 bytes = one 256-byte segment of a row,
-// four rows per instruction, non-temporal), parks it in an LDS tile of its own and reads the MFMA
-// operands back from there: lane (i, kk) takes 16 bytes of row 16t+i at columns 16s+4kk, whose
-// four components serve four successive MFMA steps (the summation index may be assigned to
-// columns in any order as long as both operands agree).  The loads of the next tile are issued
-// before the current one is consumed.  The reference row's segment is read from the same LDS
-// tile and subtracted from every operand before the products (rows.h, pick_reference).
+// The instruction takes, per lane, 8 consecutive summation indices of one row for either operand
+// in the same arrangement (lane l: row l%16, indices 8*(l/16) ..), so for a Gram tile one set of
+// registers per row tile feeds both sides; which columns those indices stand for is free as long
+// as both operands agree.  The accumulator of tile (ti, tj) holds C[4*(l/16)+v][l%16] in
+// component v of lane l.  Before the cut, the reference row's values at the same columns are
+// subtracted (rows.h, pick_reference).
+//
+// Two kernels feed these products.  gram_direct_kernel (16-byte aligned plain rows, up to 7 row
+// tiles) has its loads write the tile straight into LDS.  gram_staged_kernel (everything else:
+// block means formed on the fly, unaligned rows, 8 row tiles, the ragged shapes) fetches a tile
+// into registers with loads that are contiguous along the rows, parks it in LDS and reads the
+// operands back from there.  Either way every wavefront owns a strided share of the column tiles
+// and one LDS tile, and issues the loads of its next tile before it multiplies the current one.
 // ---------------------------------------------------------------------------------------
-constexpr int kChainCols = 2048;   // products an MFMA accumulator takes in before it is emptied
+constexpr int kStagedCols = 64, kStagedPitch = kStagedCols + 4;   // floats between LDS rows: the 16-byte reads of 16 rows hit 64 banks
 
-// Columns per tile: 64 (one 256-byte segment of every row per tile, four rows per load
-// instruction) while the kernel is bound by memory; 32 and then 16 (eight and sixteen rows per
-// instruction) from five and seven row tiles on, where the matrix cores are the bound and the
-// registers are needed for accumulators.
-constexpr int tile_cols(int T) { return T <= 4 ? 64 : (T <= 6 ? 32 : 16); }
-constexpr int tile_pitch(int T) { return tile_cols(T) + 4; }   // floats between LDS rows: the 16-byte reads of 16 rows hit 64 banks
-
-// Geometry of a tile of COLS columns: a load instruction covers RPI rows (COLS/4 lanes x 16 bytes
-// each), a lane fetches NP pieces per tile: piece g is 16 bytes of logical row RPI*g + lane/LPR at
-// column 4*(lane%LPR) of the tile.
+// Geometry of a staged tile: a load instruction covers RPI rows (16 lanes x 16 bytes each), a
+// lane fetches NP pieces per tile: piece g is 16 bytes of logical row RPI*g + lane/LPR at column
+// 4*(lane%LPR) of the tile.
 template <int T>
 struct TileGeo {
-    static constexpr int COLS = tile_cols(T), PITCH = tile_pitch(T);
+    static constexpr int COLS = kStagedCols, PITCH = kStagedPitch;
     static constexpr int LPR = COLS / 4, RPI = kWave / LPR, NP = 16 * T / RPI;
 };
 
@@ -222,37 +233,103 @@ __device__ inline void tile_park(const f32x4 (&buf)[TileGeo<T>::NP], unsigned lo
     __builtin_amdgcn_wave_barrier();
 }
 
-// Accumulates the products of the parked tile.  rd: this lane's operand position for row tile 0,
-// s = 0; ref: the reference row's position for s = 0 (a row of zeros: nothing is subtracted).
-template <int T>
-__device__ inline void tile_products(const float *rd, const float *ref, f32x4 (&acc)[tiles_for(T)])
+struct SplitOperand {
+    bf16x8 h, m, l;
+};
+
+__device__ __forceinline__ void split_pair(float x0, float x1, uint32_t &h, uint32_t &m, uint32_t &l)
 {
-    using G = TileGeo<T>;
+    h = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x0, x1}, bf16x2));
+    const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xffff0000u);
+    m = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{r0, r1}, bf16x2));
+    const float s0 = r0 - __uint_as_float(m << 16), s1 = r1 - __uint_as_float(m & 0xffff0000u);
+    l = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{s0, s1}, bf16x2));
+}
+
+__device__ __forceinline__ SplitOperand split_operand(const f32x4 &a, const f32x4 &b)
+{
+    uint32_t h[4], m[4], l[4];
+    split_pair(a[0], a[1], h[0], m[0], l[0]);
+    split_pair(a[2], a[3], h[1], m[1], l[1]);
+    split_pair(b[0], b[1], h[2], m[2], l[2]);
+    split_pair(b[2], b[3], h[3], m[3], l[3]);
+    SplitOperand o;
+    o.h = __builtin_bit_cast(bf16x8, (u32x4{h[0], h[1], h[2], h[3]}));
+    o.m = __builtin_bit_cast(bf16x8, (u32x4{m[0], m[1], m[2], m[3]}));
+    o.l = __builtin_bit_cast(bf16x8, (u32x4{l[0], l[1], l[2], l[3]}));
+    return o;
+}
+
+// Operands of all row tiles for columns 32*S .. 32*S+31 of the parked tile, reference row taken off.
+template <int T, int S>
+__device__ __forceinline__ void read_split(const float *rd, const float *ref, SplitOperand (&a)[T])
+{
+    const f32x4 c0 = *reinterpret_cast<const f32x4 *>(ref + 32 * S);
+    const f32x4 c1 = *reinterpret_cast<const f32x4 *>(ref + 32 * S + 4);
 #pragma unroll
-    for (int s = 0; s < G::COLS / 16; ++s) {
-        const f32x4 c = *reinterpret_cast<const f32x4 *>(ref + 16 * s);
-        f32x4 a[T];
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-            a[t] = *reinterpret_cast<const f32x4 *>(rd + t * 16 * G::PITCH + 16 * s) - c;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            int tile = 0;
-#pragma unroll
-            for (int ti = 0; ti < T; ++ti)
-#pragma unroll
-                for (int tj = ti; tj < T; ++tj, ++tile)
-                    acc[tile] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti][e], a[tj][e], acc[tile], 0, 0, 0);
-        }
+    for (int t = 0; t < T; ++t)
+        a[t] = split_operand(*reinterpret_cast<const f32x4 *>(rd + t * 16 * kStagedPitch + 32 * S) - c0,
+                             *reinterpret_cast<const f32x4 *>(rd + t * 16 * kStagedPitch + 32 * S + 4) - c1);
+}
+
+// Pair number p of the upper triangle of the T x T tile grid, row by row.
+constexpr int pair_ti(int T, int p)
+{
+    int ti = 0;
+    while (p >= T - ti) p -= T - ti, ++ti;
+    return ti;
+}
+constexpr int pair_tj(int T, int p)
+{
+    int ti = 0;
+    while (p >= T - ti) p -= T - ti, ++ti;
+    return ti + p;
+}
+
+// TERM 0: h*h', 1: h*m', 2: m*h', 3: h*l', 4: l*h', 5: m*m'.
+template <int T, int P, int TERM>
+__device__ __forceinline__ f32x4 split_mfma(const SplitOperand (&a)[T], const f32x4 &c)
+{
+    constexpr int ti = pair_ti(T, P), tj = pair_tj(T, P);
+    bf16x8 x, y;
+    if constexpr (TERM == 0 || TERM == 1 || TERM == 3) x = a[ti].h;
+    if constexpr (TERM == 2 || TERM == 5) x = a[ti].m;
+    if constexpr (TERM == 4) x = a[ti].l;
+    if constexpr (TERM == 0 || TERM == 2 || TERM == 4) y = a[tj].h;
+    if constexpr (TERM == 1 || TERM == 5) y = a[tj].m;
+    if constexpr (TERM == 3) y = a[tj].l;
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, c, 0, 0, 0);
+}
+
+// A few pairs side by side, so that successive instructions do not wait for one another.
+template <int T, int BASE, int... Ps>
+__device__ __forceinline__ void split_pair_group(const SplitOperand (&a)[T], f32x4 (&acc)[tiles_for(T)],
+                                                 std::integer_sequence<int, Ps...>)
+{
+    f32x4 tmp[sizeof...(Ps)];
+    ((tmp[Ps] = split_mfma<T, BASE + Ps, 5>(a, f32x4{0.0f, 0.0f, 0.0f, 0.0f})), ...);
+    ((tmp[Ps] = split_mfma<T, BASE + Ps, 3>(a, tmp[Ps])), ...);
+    ((tmp[Ps] = split_mfma<T, BASE + Ps, 4>(a, tmp[Ps])), ...);
+    ((tmp[Ps] = split_mfma<T, BASE + Ps, 1>(a, tmp[Ps])), ...);
+    ((tmp[Ps] = split_mfma<T, BASE + Ps, 2>(a, tmp[Ps])), ...);
+    ((tmp[Ps] = split_mfma<T, BASE + Ps, 0>(a, tmp[Ps])), ...);
+    ((acc[BASE + Ps] += tmp[Ps]), ...);
+}
+
+template <int T, int BASE = 0>
+__device__ __forceinline__ void split_products(const SplitOperand (&a)[T], f32x4 (&acc)[tiles_for(T)])
+{
+    constexpr int NT = tiles_for(T);
+    if constexpr (BASE < NT) {
+        constexpr int n = NT - BASE < 4 ? NT - BASE : 4;
+        split_pair_group<T, BASE>(a, acc, std::make_integer_sequence<int, n>{});
+        split_products<T, BASE + 4>(a, acc);
     }
 }
 
-// ref_keys (may be null: no centring): the keys the reference row is picked from.
-//   chain_tiles, flushes: T >= 5 only (see below).
 template <int T, bool ALIGNED, bool MEANS>
-__global__ __launch_bounds__(kBlock, (T <= 3 ? 3 : 2)) void gram_mfma_kernel(
-    RowSet rs, float *partials, const unsigned long long *ref_keys, const int *run_if, int chain_tiles,
-    int flushes)
+__global__ __launch_bounds__(kBlock, staged_blocks_per_cu(T) > 3 ? 3 : staged_blocks_per_cu(T)) void gram_staged_kernel(
+    RowSet rs, float *partials, const unsigned long long *ref_keys, const int *run_if)
 {
     if (run_if && *run_if == 0) return;   // uniform
     using G = TileGeo<T>;
@@ -289,41 +366,19 @@ __global__ __launch_bounds__(kBlock, (T <= 3 ? 3 : 2)) void gram_mfma_kernel(
 
     float *tile = lds_tiles + (size_t)wv * (16 * T * G::PITCH);
     float *wr = tile + (lane / G::LPR) * G::PITCH + 4 * (lane % G::LPR);
-    const float *rd = tile + (lane & 15) * G::PITCH + 4 * (lane >> 4);
-    const float *ref = lds_zeros + 4 * (lane >> 4);
-    if (ref_keys != nullptr) ref = tile + pick_reference(ref_keys, count) * G::PITCH + 4 * (lane >> 4);
+    const float *rd = tile + (lane & 15) * G::PITCH + 8 * (lane >> 4);
+    const float *ref = lds_zeros + 8 * (lane >> 4);
+    if (ref_keys != nullptr) ref = tile + pick_reference(ref_keys, count) * G::PITCH + 8 * (lane >> 4);
 
-    // The matrix cores add the products of an instruction to the accumulator with a few guard
-    // bits and no more, which shows as a small bias that grows with the number of products an
-    // accumulator takes in (about 1.6e-10 of the sum per product).  So the accumulators are
-    // emptied now and then.  Up to four row tiles: every kChainCols columns, with ordinary rounded
-    // additions, into a second set of registers.  From five row tiles on, where registers are
-    // short: every chain_tiles tiles into one more slot of the partial sums, `flushes` slots per
-    // wavefront in all (slot f of wavefront w is number f * waves + w; all of them are written).
-    constexpr bool kRegisterTotals = T <= 4;
     f32x4 acc[NT];
-    f32x4 total[kRegisterTotals ? NT : 1];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int t = 0; t < (kRegisterTotals ? NT : 1); ++t) total[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    if constexpr (kRegisterTotals) chain_tiles = kChainCols / G::COLS;
-    int flushed = 0;
-    auto empty_accumulators = [&]() {
-        if constexpr (kRegisterTotals) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t) total[t] += acc[t];
-        } else {
-            // C[4*(l/16)+v][l%16] of tile t at [t][v][l]
-            float *out = partials + ((int64_t)flushed * waves + wave) * (NT * 256) + lane;
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) out[t * 256 + v * 64] = acc[t][v];
-            ++flushed;
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    auto products = [&]() {
+        SplitOperand a[T];
+        read_split<T, 0>(rd, ref, a);
+        split_products<T>(a, acc);
+        read_split<T, 1>(rd, ref, a);
+        split_products<T>(a, acc);
     };
 
     // fetch, park, fetch the next tile, multiply the parked one while those loads are in flight
@@ -331,33 +386,177 @@ __global__ __launch_bounds__(kBlock, (T <= 3 ? 3 : 2)) void gram_mfma_kernel(
     const int64_t lane_col = 4 * (lane % G::LPR);
     f32x4 buf[G::NP];
     int64_t step = wave;
-    int chain = 0;
     if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
     while (step < full_tiles) {
         tile_park<T>(buf, zero, wr);
         step += waves;
         if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
-        tile_products<T>(rd, ref, acc);
-        if (++chain == chain_tiles && (kRegisterTotals || flushed + 1 < flushes)) {   // uniform
-            chain = 0;
-            empty_accumulators();
-        }
+        products();
     }
-    // the ragged last tile (d % COLS columns) goes to one wavefront
+    // the ragged last tile (d % 64 columns) goes to one wavefront
     if ((d % G::COLS) != 0 && wave == full_tiles % waves) {
         tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, full_tiles * G::COLS + lane_col, true, buf);
         tile_park<T>(buf, zero, wr);
-        tile_products<T>(rd, ref, acc);
+        products();
     }
-    if constexpr (kRegisterTotals) {
-        float *out = partials + wave * (int64_t)(NT * 256) + lane;
+    // C[4*(l/16)+v][l%16] of tile t at [t][v][l]
+    float *out = partials + wave * (int64_t)(NT * 256) + lane;
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) out[t * 256 + v * 64] = total[t][v] + acc[t][v];
-    } else {
-        do empty_accumulators(); while (flushed < flushes);   // the rest of the slots get zeros
+        for (int v = 0; v < 4; ++v) out[t * 256 + v * 64] = acc[t][v];
+}
+
+// ---------------------------------------------------------------------------------------
+// 16-byte aligned plain rows: tiles of 32 columns that the loads write straight into LDS.  No
+// registers hold a tile in flight, which leaves room for more wavefronts per SIMD (two even next
+// to the 112 accumulator registers of 7 row tiles), one cutting operands while another's matrix
+// instructions run or its loads are under way.  A load instruction moves 8 rows x 128 bytes; lane l's 16 bytes land at byte 16*l of the instruction's 1 KiB block, whatever
+// address it fetched from, so the lanes fetch the eight 16-byte pieces of their row in an order
+// that is rotated from row to row (piece c of row r sits at position c ^ ((r/2) % 8)): the sixteen
+// lanes that then read the same piece of sixteen rows for the matrix instruction hit sixteen
+// different groups of banks.
+// ---------------------------------------------------------------------------------------
+constexpr int kDirectCols = 32;
+constexpr int kDirectMaxTiles = 7;   // with eight row tiles the workgroup's LDS passes 64 KiB
+
+typedef __attribute__((address_space(1))) const void *GlobalPtr;
+typedef __attribute__((address_space(3))) void *LdsPtr;
+
+template <int T>
+__global__ __launch_bounds__(kBlock, direct_blocks_per_cu(T)) void gram_direct_kernel(RowSet rs, float *partials,
+                                                                const unsigned long long *ref_keys,
+                                                                const int *run_if)
+{
+    if (run_if && *run_if == 0) return;   // uniform
+    constexpr int NT = tiles_for(T), kRows = 16 * T, kInst = 2 * T;
+    constexpr int kTileBytes = kRows * kDirectCols * 4;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_tiles[(kBlock / kWave) * kTileBytes];
+    __shared__ int64_t lds_rows[kRows];
+    __shared__ __attribute__((aligned(16))) float lds_zeros[kDirectCols];
+    __shared__ int lds_any_zero;
+    const int count = rs.count;
+    const int64_t d = rs.d;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + wv;
+    const int64_t waves = (int64_t)gridDim.x * (kBlock / kWave);
+
+    // padded rows repeat the last row (their entries are never reported); a row that stands for
+    // the zero vector is fetched from row 0 and replaced by zeros when the operands are read
+    if (threadIdx.x == 0) lds_any_zero = 0;
+    if (threadIdx.x < kDirectCols) lds_zeros[threadIdx.x] = 0.0f;
+    __syncthreads();
+    if ((int)threadIdx.x < kRows) {
+        int64_t row = (int)threadIdx.x < count ? (int)threadIdx.x : count - 1;
+        if (rs.index) row = rs.index[row];
+        if (row < 0) lds_any_zero = 1;
+        lds_rows[threadIdx.x] = row < 0 ? -1 : row * rs.ld;
     }
+    __syncthreads();
+    const int i = lane & 15, kk = lane >> 4;
+    unsigned zmask = 0u;   // bit t: row 16t + i is the zero vector
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+        if (lds_rows[16 * t + i] < 0) zmask |= 1u << t;
+    const bool any_zero = lds_any_zero != 0;   // uniform
+    // the reference row (-1: none, also when it is the zero vector: nothing to take off then)
+    int p = ref_keys != nullptr ? pick_reference(ref_keys, count) : -1;
+    if (p >= 0 && lds_rows[p] < 0) p = -1;
+    __syncthreads();
+    if ((int)threadIdx.x < kRows && lds_rows[threadIdx.x] < 0) lds_rows[threadIdx.x] = 0;
+    __syncthreads();
+
+    unsigned char *tile = lds_tiles + (size_t)wv * kTileBytes;
+    // loads: instruction g, lane l: row 8g + l/8, piece (l%8) ^ ((4*(g%2) + l/16) % 8) of its 8
+    const int load_row = lane >> 3;
+    const int piece_even = (lane & 7) ^ (lane >> 4);
+    // operands: lane (i, kk) takes pieces 2kk and 2kk+1 of row 16t + i
+    const int sw = (i >> 1) & 7;
+    const unsigned char *rd0 = tile + i * 128 + ((2 * kk) ^ sw) * 16;
+    const unsigned char *rd1 = tile + i * 128 + ((2 * kk + 1) ^ sw) * 16;
+    const unsigned char *ref0 = reinterpret_cast<const unsigned char *>(lds_zeros) + 32 * kk;
+    const unsigned char *ref1 = ref0 + 16;
+    if (p >= 0) {
+        const int psw = (p >> 1) & 7;
+        ref0 = tile + p * 128 + ((2 * kk) ^ psw) * 16;
+        ref1 = tile + p * 128 + ((2 * kk + 1) ^ psw) * 16;
+    }
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // all of a tile's loads; nothing waits for them here
+    auto issue_loads = [&](int64_t col0) {
+#pragma unroll
+        for (int g = 0; g < kInst; ++g) {
+            const int piece = (g & 1) ? (piece_even ^ 4) : piece_even;
+            const float *src = rs.base + lds_rows[8 * g + load_row] + col0 + 4 * piece;
+            __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(tile + g * 1024), 16, 0, 2 /* non-temporal */);
+        }
+    };
+    // The tile's raw operands into registers.  Both waits are explicit: for the loads that fill
+    // the tile before the first read, and for the reads before the caller lets the next tile's
+    // loads overwrite it.
+    auto read_raw = [&](f32x4 (&x0)[T], f32x4 (&x1)[T], f32x4 &c0, f32x4 &c1) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        c0 = *reinterpret_cast<const f32x4 *>(ref0);
+        c1 = *reinterpret_cast<const f32x4 *>(ref1);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            x0[t] = *reinterpret_cast<const f32x4 *>(rd0 + t * 2048);
+            x1[t] = *reinterpret_cast<const f32x4 *>(rd1 + t * 2048);
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto multiply = [&](f32x4 (&x0)[T], f32x4 (&x1)[T], const f32x4 &c0, const f32x4 &c1) {
+        if (any_zero) {   // uniform, rare
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+                if ((zmask >> t) & 1u) x0[t] = x1[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+        SplitOperand a[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) a[t] = split_operand(x0[t] - c0, x1[t] - c1);
+        split_products<T>(a, acc);
+    };
+
+    const int64_t full_tiles = d / kDirectCols;
+    int64_t step = wave;
+    if (step < full_tiles) issue_loads(step * kDirectCols);
+    while (step < full_tiles) {
+        f32x4 x0[T], x1[T], c0, c1;
+        read_raw(x0, x1, c0, c1);
+        step += waves;
+        if (step < full_tiles) issue_loads(step * kDirectCols);
+        multiply(x0, x1, c0, c1);
+    }
+    // the ragged last tile (d % 32 columns) goes to one wavefront, through registers
+    if ((d % kDirectCols) != 0 && wave == full_tiles % waves) {
+#pragma unroll
+        for (int g = 0; g < kInst; ++g) {
+            const int piece = (g & 1) ? (piece_even ^ 4) : piece_even;
+            const int64_t col = full_tiles * kDirectCols + 4 * piece;
+            const float *q = rs.base + lds_rows[8 * g + load_row] + col;
+            const f32x4 v = f32x4{col + 0 < d ? q[0] : 0.0f, col + 1 < d ? q[1] : 0.0f,
+                                  col + 2 < d ? q[2] : 0.0f, col + 3 < d ? q[3] : 0.0f};
+            *reinterpret_cast<f32x4 *>(tile + g * 1024 + lane * 16) = v;
+        }
+        f32x4 x0[T], x1[T], c0, c1;
+        read_raw(x0, x1, c0, c1);
+        multiply(x0, x1, c0, c1);
+    }
+    // C[4*(l/16)+v][l%16] of tile t at [t][v][l]
+    float *out = partials + wave * (int64_t)(NT * 256) + lane;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) out[t * 256 + v * 64] = acc[t][v];
 }
 
 // Adds the per-wavefront tiles in fp64, in two fixed-order levels: kReduceSlices contiguous
@@ -448,54 +647,46 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
     }
 }
 
+// direct: the rows are plain (no block means) and 16-byte aligned, and T <= kDirectMaxTiles.
 template <int T>
 hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long long *keys, int grid,
-                       bool aligned, const int *run_if, int chain_tiles, int flushes, hipStream_t s)
+                       bool aligned, bool direct, const int *run_if, hipStream_t s)
 {
-    TraceScope t(run_if ? "gram_mfma_f32_if_redo" : "gram_mfma_f32", s);
+    TraceScope t(run_if ? "gram_mfma_bf16x3_if_redo" : "gram_mfma_bf16x3", s);
     if (rs.means()) {
         // block means formed on the fly: offered for the row counts a hierarchical step can have
         if constexpr (T <= 2) {
             if (!aligned) return hipErrorInvalidValue;
-            gram_mfma_kernel<T, true, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if, chain_tiles, flushes);
+            gram_staged_kernel<T, true, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
         } else {
             return hipErrorInvalidValue;
         }
+    } else if (direct) {
+        if constexpr (T <= kDirectMaxTiles)
+            gram_direct_kernel<T><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+        else
+            return hipErrorInvalidValue;
     } else if (aligned) {
-        gram_mfma_kernel<T, true, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if, chain_tiles, flushes);
+        gram_staged_kernel<T, true, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
     } else {
-        gram_mfma_kernel<T, false, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if, chain_tiles, flushes);
+        gram_staged_kernel<T, false, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
     }
     return hipGetLastError();
 }
 
-// Slots of partial sums a wavefront writes (see the kernel): one, or from five row tiles on as
-// many as keep the chain of products behind one accumulator near kLongChainCols columns.
-constexpr int kLongChainCols = 4096, kMaxFlushes = 8;
-int flushes_for(int T, int64_t d, int waves)
-{
-    if (T <= 4) return 1;
-    const int64_t per_wave = (d + waves - 1) / waves;
-    const int64_t f = (per_wave + kLongChainCols - 1) / kLongChainCols;
-    return f < 1 ? 1 : (f > kMaxFlushes ? kMaxFlushes : (int)f);
-}
-
-// Workspace of the MFMA path: the slots of partial sums (room for the largest grid), the slice
-// sums of the first reduction level, the reference keys.
+// Workspace of the matrix-core path: one tile set of partial sums per wavefront (room for the
+// largest grid), the slice sums of the first reduction level, the reference keys.
 struct MfmaWs {
     float *tiles;
     double *slices;
     unsigned long long *keys;
 };
-size_t mfma_slot_floats(int T, int64_t d)
-{
-    return (size_t)mfma_max_waves(T) * (size_t)flushes_for(T, d, mfma_max_waves(T)) * (size_t)tiles_for(T) * 256;
-}
-MfmaWs carve_mfma(void *partials, int T, int64_t d)
+size_t mfma_slot_floats(int T) { return (size_t)mfma_max_waves(T) * (size_t)tiles_for(T) * 256; }
+MfmaWs carve_mfma(void *partials, int T)
 {
     MfmaWs w;
     w.tiles = static_cast<float *>(partials);
-    w.slices = reinterpret_cast<double *>(w.tiles + mfma_slot_floats(T, d));
+    w.slices = reinterpret_cast<double *>(w.tiles + mfma_slot_floats(T));
     w.keys = reinterpret_cast<unsigned long long *>(w.slices + (size_t)kReduceSlices * tiles_for(T) * 256);
     return w;
 }
@@ -510,41 +701,38 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
 {
     const int T = (rs.count + 15) / 16;
     if (T < 1 || T > 8) return hipErrorInvalidValue;
-    const MfmaWs w = carve_mfma(partials, T, rs.d);
-    int grid = num_compute_units() * mfma_blocks_per_cu(T);
+    const MfmaWs w = carve_mfma(partials, T);
+    const bool aligned = row_vec_width(rs.base, rs.ld) == 4;
+    const bool direct = aligned && !rs.means() && T <= kDirectMaxTiles;
+    int grid = num_compute_units() * (direct ? direct_blocks_per_cu(T) : staged_blocks_per_cu(T));
     if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
-    const int64_t tiles = (rs.d + tile_cols(T) - 1) / tile_cols(T);
+    const int cols = direct ? kDirectCols : kStagedCols;
+    const int64_t tiles = (rs.d + cols - 1) / cols;
     const int64_t need = (tiles + kBlock / kWave - 1) / (kBlock / kWave);
     if (grid > need) grid = (int)need;
     const int waves = grid * (kBlock / kWave);
-    // never more slots than the workspace was sized for (its bound assumes the largest grid)
-    int flushes = flushes_for(T, rs.d, waves);
-    while (flushes > 1 && (size_t)waves * flushes * tiles_for(T) * 256 > mfma_slot_floats(T, rs.d)) --flushes;
-    const int64_t tiles_per_wave = (tiles + waves - 1) / waves;
-    const int chain_tiles = (int)((tiles_per_wave + flushes - 1) / flushes);
     hipError_t e = hipSuccess;
     if (keys == nullptr) {
         e = launch_reference_keys(ref_rows_of(rs), w.keys, run_if, s);
         if (e != hipSuccess) return e;
         keys = w.keys;
     }
-    const bool aligned = row_vec_width(rs.base, rs.ld) == 4;
     switch (T) {
-    case 1: e = launch_mfma<1>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 2: e = launch_mfma<2>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 3: e = launch_mfma<3>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 4: e = launch_mfma<4>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 5: e = launch_mfma<5>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 6: e = launch_mfma<6>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    case 7: e = launch_mfma<7>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
-    default: e = launch_mfma<8>(rs, w.tiles, keys, grid, aligned, run_if, chain_tiles, flushes, s); break;
+    case 1: e = launch_mfma<1>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    case 2: e = launch_mfma<2>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    case 3: e = launch_mfma<3>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    case 4: e = launch_mfma<4>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    case 5: e = launch_mfma<5>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    case 6: e = launch_mfma<6>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    case 7: e = launch_mfma<7>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    default: e = launch_mfma<8>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
     }
     if (e != hipSuccess) return e;
     const int elems = tiles_for(T) * 256;
     {
         TraceScope t("gram_reduce", s);
         gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
-            w.tiles, waves * flushes, elems, w.slices, alt, alt_waves, run_if);
+            w.tiles, waves, elems, w.slices, alt, alt_waves, run_if);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -559,7 +747,8 @@ size_t gram_partial_bytes(int64_t count, int64_t d)
 {
     if (count <= 8) return (size_t)kMaxGramWaves * (size_t)(count * (count + 1) / 2) * sizeof(double);
     const int T = (int)((count + 15) / 16);
-    return mfma_slot_floats(T, d) * sizeof(float) +
+    (void)d;
+    return mfma_slot_floats(T) * sizeof(float) +
            (size_t)kReduceSlices * (size_t)tiles_for(T) * 256 * sizeof(double) +
            (size_t)kMaxCount * sizeof(unsigned long long);
 }

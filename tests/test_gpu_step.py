@@ -310,7 +310,7 @@ def test_gram_of_the_votes_formed_in_the_filter_pass(dx, groups, r, aggregator):
         dx.detox_step(dev_matrix(G, (d + 3) // 4 * 4), r, 2, groups, aggregator, f=spec.get("f", -1),
                       m=spec.get("m", -1), materialise=False)
         names = [n for n, _ in tr.records()]
-    assert "filter_votes_gram" in names and "gram_mfma_f32" not in names
+    assert "filter_votes_gram" in names and "gram_mfma_bf16x3" not in names
 
 
 @pytest.mark.parametrize("k", [10, 100, 1000])
@@ -368,3 +368,32 @@ def test_step_with_9_to_32_vote_groups_and_no_block_means_in_memory(dx, spec, n,
         _run(dx, w, spec, G=G, ld=ld, materialise=False)
         _run(dx, w, spec, G=G, ld=ld, materialise=False, vote_perm=vote_perm)
     _run(dx, w, spec, G=G, ld=ld, materialise=True, vote_perm=vote_perm)
+
+
+@pytest.mark.parametrize("aggregator", ["multikrum", "bulyan", "geomedian"])
+@pytest.mark.parametrize("groups", [45, 70, 100])
+@pytest.mark.parametrize("broken", [1, 2])
+def test_step_over_many_votes_some_without_majority(dx, aggregator, groups, broken):
+    """More than 32 votes as one block each (B = n/r), votes kept out of memory: the Gram matrix is
+    formed over the winner rows, where a vote without majority stands for the zero vector.  broken = 1:
+    a few such votes; broken = 2: two thirds of them, so that the row the Gram kernel centres on
+    is itself a zero vector."""
+    r, d = 3, 20_011
+    rng = np.random.default_rng(groups + broken)
+    base = (rng.standard_normal((groups, d)) * 0.05 + 0.5).astype(np.float32)
+    G = np.repeat(base, r, axis=0)
+    bad = [1, 7, groups - 1] if broken == 1 else [g for g in range(groups) if g % 3 != 0]
+    for g in bad:
+        for k in range(r):
+            G[r * g + k] += float(k + 1)                 # all members differ
+    G[r * 3] = 9.0                                        # outvoted
+    w = workloads.Workload("many", groups * r, r, 4, d, base, {})
+    spec = dict(aggregator=aggregator, B=groups)
+    if aggregator == "multikrum":
+        spec.update(f=4, m=groups - 6)
+    if aggregator == "bulyan":
+        spec.update(f=4)
+    if aggregator == "geomedian":
+        spec.update(iters=20)
+    _run(dx, w, spec, G=G, ld=(d + 63) // 64 * 64, materialise=False)
+    _run(dx, w, spec, G=G, materialise=False, vote_perm=rng.permutation(groups).astype(np.int32))
