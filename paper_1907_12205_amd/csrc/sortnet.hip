@@ -118,41 +118,45 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
 #pragma unroll
             for (int v = 0; v < VEC; ++v)
                 top[((i - h - 1) * kBlock + threadIdx.x) * VEC + v] = val[i][v];
+        // The window is [lo, lo+beta) with lo_min <= lo <= lo_max.  The values at lo_max ..
+        // lo_min+beta-1 lie in every such window; of the pair (c, c+beta), lo_min <= c < lo_max,
+        // exactly one does: the upper one if the window slid past c, else the lower one.  So the
+        // sum is taken as it is decided: the fixed part, then one value per candidate (fp64; at
+        // most 128 fp32 terms, so the order of the additions stays below 1e-13 of the sum).
         const int lo_min = h - beta + 1 > 0 ? h - beta + 1 : 0;
-        const int dropped = N - beta;                         // values outside the window
+        const int lo_max = h < N - beta ? h : N - beta;
         float med[VEC];
-        int lo[VEC];
+        double sum[VEC];
+        bool sliding[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             med[v] = N % 2 == 1 ? val[N / 2][v] : (val[N / 2 - 1][v] + val[N / 2][v]) * 0.5f;
-            lo[v] = lo_min;
+            sum[v] = 0.0;
+            sliding[v] = true;
+        }
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+            if (c >= lo_max && c < lo_min + beta) {           // uniform: inside every window
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) sum[v] += (double)val[c][v];
+            }
         }
 #pragma unroll
         for (int c = 0; c <= h; ++c) {
-            if (c >= lo_min && c + beta < N) {                // uniform: a real candidate
+            if (c >= lo_min && c < lo_max) {                  // uniform: a real candidate
                 const int e = c + beta - (h + 1);             // in [0, kTop)
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     const float enter = top[(e * kBlock + threadIdx.x) * VEC + v];
                     const float dl = fabsf(val[c][v] - med[v]);
                     const float dr = fabsf(enter - med[v]);
-                    if (dr < dl && lo[v] == c) lo[v] = c + 1;
+                    sliding[v] = sliding[v] && dr < dl;
+                    sum[v] += (double)(sliding[v] ? enter : val[c][v]);
                 }
             }
         }
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            double s = 0.0;
-#pragma unroll
-            for (int c = 0; c < N; ++c) {
-                if (c >= dropped && c < beta) {               // uniform: inside every window
-                    s += (double)val[c][v];
-                } else if (c >= lo[v] && c < lo[v] + beta) {
-                    s += (double)val[c][v];
-                }
-            }
-            o[v] = (float)(s / (double)beta);
-        }
+        for (int v = 0; v < VEC; ++v) o[v] = (float)(sum[v] / (double)beta);
     }
     store_floats<VEC>(out + col, valid, o);
 }

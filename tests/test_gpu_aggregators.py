@@ -40,7 +40,7 @@ def test_coord_median_integer_ties(dx):
     assert host(dx.robust_coord_median(dev_matrix(X))).tobytes() == oracle.coord_median(X).tobytes()
 
 
-SQDIST_COUNTS = [1, 2, 5, 7, 8, 9, 15, 16, 17, 33, 45, 64, 105, 128]
+SQDIST_COUNTS = [1, 2, 5, 7, 8, 9, 15, 16, 17, 32, 33, 45, 48, 64, 70, 83, 96, 105, 112, 113, 128]
 
 
 @pytest.mark.parametrize("count", SQDIST_COUNTS)
