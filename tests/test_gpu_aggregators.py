@@ -55,6 +55,17 @@ def test_pairwise_sqdist(dx, count):
         assert np.abs(D - ref).max() <= tol * ref.max() + 1e-300, (count, ld, off)
 
 
+@pytest.mark.parametrize("count", [9, 33, 105, 128])
+@pytest.mark.parametrize("d", [1, 3, 31, 32, 33, 63, 64, 65, 97])
+def test_pairwise_sqdist_on_very_short_rows(dx, count, d):
+    """Fewer columns than one tile of the matrix-core kernels, and just around one and two tiles."""
+    X = workloads.distinct_rows(count + d, count, d, sigma=0.03, mean=0.5)
+    ref = oracle.pairwise_sqdist(X)
+    for ld in (None, (d + 63) // 64 * 64):
+        D = host(dx.robust_pairwise_sqdist(dev_matrix(X, ld, 0)))
+        assert np.abs(D - ref).max() <= 2e-6 * ref.max() + 1e-300, (count, d, ld)
+
+
 @pytest.mark.parametrize("count", [6, 15, 45, 105])
 def test_identical_rows_give_exact_zero_and_equal_distances(dx, count):
     r = 3
