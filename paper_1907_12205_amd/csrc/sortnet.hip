@@ -90,7 +90,9 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
             double s = 0.0;
 #pragma unroll
             for (int c = 0; c < N; ++c)
-                if (c >= beta && c < N - beta) s += (double)key_value(k[c][v]);
+                if (c >= beta && c < N - beta) {              // uniform
+                    s += (double)key_value(k[c][v]);
+                }
             o[v] = (float)(s / (double)(N - 2 * beta));
         }
     } else if constexpr (!TRIM) {
@@ -137,6 +139,7 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
 #pragma unroll
         for (int c = 0; c < N; ++c) {
             if (c >= lo_max && c < lo_min + beta) {           // uniform: inside every window
+                asm volatile("" ::: "memory");                // a real branch, not a select per value
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) sum[v] += (double)val[c][v];
             }
@@ -144,6 +147,7 @@ __global__ __launch_bounds__(kBlock) void order_stat_kernel(RowSet rs, const int
 #pragma unroll
         for (int c = 0; c <= h; ++c) {
             if (c >= lo_min && c < lo_max) {                  // uniform: a real candidate
+                asm volatile("" ::: "memory");
                 const int e = c + beta - (h + 1);             // in [0, kTop)
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
