@@ -400,7 +400,7 @@ def main():
         ws_b = torch.empty(dx.workspace_bytes("bulyan", n, d), dtype=torch.uint8, device=G.device)
         timed(f"vanilla Bulyan over {n} rows, f={fb}", lambda: dx.robust_bulyan(G, fb, out=out_o, ws=ws_b), n + (n - 2 * fb) + 1)
         if ld != d:
-            # the same step on unpadded rows (ld = d): narrower loads when d is not a multiple of 4
+            # the same step on unpadded rows (ld = d): rows off the 16-byte grid when d is not a multiple of 4
             Gu = w.to_device("cuda:0")
             bu = StepBuffers(n, d, r, B, G.device, materialise=False)
             timed(f"DETOX {agg}, B={B}, rows not padded (ld = d = {d})", lambda: dx.detox_step(Gu, r, q, B, agg, buffers=bu, **kw), step_rows)

@@ -18,9 +18,11 @@
  *
  * Conventions for every entry point
  *   - Matrices are fp32, row-major, one gradient per row; `ld` is the distance
- *     between rows in elements (ld >= d).  The fast paths need the base
- *     pointer 16-byte aligned and ld % 4 == 0; any other ld >= d works through
- *     narrower loads.  Element (i, c) is at base[i*ld + c]; indices are 64-bit.
+ *     between rows in elements (ld >= d).  Any ld >= d runs at full width (rows
+ *     that start off a 16-byte boundary cost a few per cent); only the Gram
+ *     matrix of more than 8 rows takes a slower kernel unless the base pointer
+ *     is 16-byte aligned and ld % 4 == 0.  Element (i, c) is at base[i*ld + c];
+ *     indices are 64-bit.
  *   - Pointers marked "dev" are device (HBM) addresses owned by the caller;
  *     nothing is copied to or from the host.  Inputs are never written;
  *     outputs must not overlap inputs.
@@ -265,8 +267,8 @@ int detox_step_static(const float *G, int64_t n, int64_t d, int64_t ld, int r, i
  *              selection order) starts at its first vote position floor(b*V/B); Multi-Krum
  *              fills m entries there, Bulyan size-2f
  *   out        dev, d floats
- *   ws         DETOX_OP_STEP_ROBUST_BLOCKS bytes (count = n/r, aux = B).  With 9 <= n/r <= 16 (and
- *              16-byte aligned rows) the Gram matrix of all votes is formed during the filter
+ *   ws         DETOX_OP_STEP_ROBUST_BLOCKS bytes (count = n/r, aux = B).  With 9 <= n/r <= 16
+ *              the Gram matrix of all votes is formed during the filter
  *              pass, on the matrix cores in fp32, and the vote groups cut theirs out of it (one
  *              pass less over the winner rows); otherwise every group's matrix is formed from
  *              its rows (fp64 for groups of at most 8 votes).                               */

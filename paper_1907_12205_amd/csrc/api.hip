@@ -434,10 +434,8 @@ static int step_impl(const float *G, int64_t n, int64_t d, int64_t ld, int r, in
     if (!winner || !out || (Zhat && ldo < d) || B < 1 || B > groups || B > kMaxCount || q < 0)
         return DETOX_EINVAL;
     // without Zhat the aggregator reads votes (B = n/r) or re-forms the means of up to 32 vote
-    // groups on the fly (beyond 8 of them only from 16-byte aligned rows)
-    if (!Zhat && B != groups &&
-        (groups > kFusedMaxVotes || B > kMeansOnTheFlyMaxRows || (B > 8 && row_vec_width(G, ld) != 4)))
-        return DETOX_EINVAL;
+    // groups on the fly
+    if (!Zhat && B != groups && (groups > kFusedMaxVotes || B > kMeansOnTheFlyMaxRows)) return DETOX_EINVAL;
     if (agg < DETOX_AGG_MULTIKRUM || agg > DETOX_AGG_TRIMMED_MEAN) return DETOX_EINVAL;
     if (agg == DETOX_AGG_TRIMMED_MEAN) {
         if (f < 0) f = (int)(B / 4);   // alpha = 1/4 (Theorem 3, part 3)
@@ -648,7 +646,7 @@ int detox_sign_majority(const uint32_t *S, int64_t n, int64_t d, int64_t ldw, in
     hipStream_t s = static_cast<hipStream_t>(stream);
     const FilterWs fw = carve_filter_ws(ws, groups);
     // The filter compares bit patterns, so the packed words go through it as they are; where it
-    // can (16-byte aligned rows and outputs) the same pass takes both vote levels from the
+    // can (up to 1024 node groups) the same pass takes both vote levels from the
     // per-coordinate majority bits, and the stand-alone vote runs only if some group had no majority.
     FilterParams p{reinterpret_cast<const float *>(S), words, ldw, r, group_rows, vote_perm, groups,
                    B, nullptr, 0, fw.flags, fw.flag_partials, fw.gram_partials, fw.redo,

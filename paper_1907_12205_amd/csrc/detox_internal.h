@@ -44,13 +44,14 @@ struct TraceScope {
 
 int num_compute_units();  // of the current device (cached)
 
-// Widest vector (4, 2 or 1 fp32) every row of a matrix can be accessed with.
-inline int row_vec_width(const void *base, int64_t ld)
+// The streaming kernels take four fp32 columns per lane with one 16-byte access whatever the
+// alignment of the rows (rows.h: the access is declared with the alignment of its components,
+// which this target serves at full width; a row that starts off a 16-byte boundary costs one
+// more cache line per wavefront and instruction).  Only the loads that write LDS directly (the
+// Gram kernel of more than 8 rows) ask for this:
+inline bool rows_16_byte_aligned(const void *base, int64_t ld)
 {
-    const uintptr_t a = reinterpret_cast<uintptr_t>(base);
-    if (a % 16 == 0 && ld % 4 == 0) return 4;
-    if (a % 8 == 0 && ld % 2 == 0) return 2;
-    return 1;
+    return reinterpret_cast<uintptr_t>(base) % 16 == 0 && ld % 4 == 0;
 }
 
 // A set of logical rows handed to an aggregator (see rows.h for the device side).
@@ -132,13 +133,13 @@ enum class FilterWant {
     kVotes,    // nothing else
     kMeans,    // block means in Zhat (must be non-null)
     kGram,     // block means (in Zhat if non-null) and their Gram matrix: fp64 partial sums for
-               //   B <= 8; for 9 .. kPassGramMaxVotes votes, each its own block (Zhat null, 16-byte
-               //   aligned rows, vote_gram_partials non-null): fp32 MFMA tiles per wavefront there
+               //   B <= 8; for 9 .. kPassGramMaxVotes votes, each its own block (Zhat null,
+               //   vote_gram_partials non-null): fp32 MFMA tiles per wavefront there
     kMedian,   // block means (in Zhat if non-null) and, when B <= 8, their coordinate-wise median
     kTrimmed,  // the same with the coordinate-wise trimmed mean (FilterParams::trim_g per end)
     kSignVote  // the rows are bit-packed signs: two levels of coordinate-wise majority vote over the
                //   per-coordinate majority bits of the node groups, written to sign_pos / sign_neg
-               //   (16-byte aligned rows and outputs, at most 255 votes per group and 255 groups)
+               //   (at most 255 votes per group and 255 groups)
 };
 // Where the extra cannot be had, the pass degrades to kMeans (Zhat non-null) or to kVotes (Zhat
 // null: later kernels read the winner rows and re-form the means they need).

@@ -247,8 +247,8 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
                 }
             }
             if (valid == VEC) {
-                *reinterpret_cast<u32x4_t *>(p.sign_pos + col) = u32x4_t{pm[0], pm[1], pm[2], pm[3]};
-                *reinterpret_cast<u32x4_t *>(p.sign_neg + col) = u32x4_t{mm[0], mm[1], mm[2], mm[3]};
+                *reinterpret_cast<u32x4_any_t *>(p.sign_pos + col) = u32x4_t{pm[0], pm[1], pm[2], pm[3]};
+                *reinterpret_cast<u32x4_any_t *>(p.sign_neg + col) = u32x4_t{mm[0], mm[1], mm[2], mm[3]};
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i)
@@ -645,14 +645,9 @@ template <int R>
 hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int mode, int nb, int *grid,
                     int64_t chunks, int vec, hipStream_t s)
 {
-    if (fused) {
-        if (vec == 4) return launch_fused_rv<R, 4>(p, mode, nb, grid, chunks, s);
-        if (vec == 2) return launch_fused_rv<R, 2>(p, mode, nb, grid, chunks, s);
-        return launch_fused_rv<R, 1>(p, mode, nb, grid, chunks, s);
-    }
-    if (vec == 4) return launch_general_rv<R, 4>(p, mean, s);
-    if (vec == 2) return launch_general_rv<R, 2>(p, mean, s);
-    return launch_general_rv<R, 1>(p, mean, s);
+    if (vec != 4) return hipErrorInvalidValue;
+    if (fused) return launch_fused_rv<R, 4>(p, mode, nb, grid, chunks, s);
+    return launch_general_rv<R, 4>(p, mean, s);
 }
 
 }  // namespace
@@ -724,15 +719,7 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         }
         return launch_filter_rows(p, mean, s);
     }
-    int vec = row_vec_width(p.G, p.ld);
-    if (p.Zhat) {
-        const int vo = row_vec_width(p.Zhat, p.ldo);
-        vec = vo < vec ? vo : vec;
-    }
-    if (want == FilterWant::kMedian || want == FilterWant::kTrimmed) {
-        const int vo = row_vec_width(p.out, 4);
-        vec = vo < vec ? vo : vec;
-    }
+    constexpr int vec = 4;   // columns per lane
     const int64_t chunks = (p.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     // The persistent kernel serves the paper's regime: up to kFusedMaxVotes node groups cut into
     // few vote groups.  A pure filter is the same kernel with every group its own block.
@@ -745,14 +732,11 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         if (fused && p.B <= 8 && want == FilterWant::kTrimmed) mode = kTrimmedMean, nb = (int)p.B;
         // 9 .. 16 votes, each its own block and none wanted in memory: their Gram matrix on the side
         if (fused && want == FilterWant::kGram && p.B == p.n_votes && p.B > 8 && p.B <= kPassGramMaxVotes &&
-            p.Zhat == nullptr && vec == 4 && p.vote_gram_partials != nullptr)
+            p.Zhat == nullptr && p.vote_gram_partials != nullptr)
             mode = kVotesGram;
         // packed signs: both vote levels in the pass (else: votes only, the caller votes afterwards)
         if (want == FilterWant::kSignVote)
-            mode = fused && vec == 4 && p.sign_pos != nullptr && p.sign_neg != nullptr &&
-                           row_vec_width(p.sign_pos, 4) == 4 && row_vec_width(p.sign_neg, 4) == 4
-                       ? kSignVote
-                       : kFilterOnly;
+            mode = fused && p.sign_pos != nullptr && p.sign_neg != nullptr ? kSignVote : kFilterOnly;
         // nothing on the side: plain block means if they are wanted in memory, else the votes
         // alone (later kernels read the winner rows and re-form the means they need)
         if (mode == kMeans && p.Zhat == nullptr) mode = kFilterOnly;
@@ -822,9 +806,7 @@ hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_
 {
     if (!copy && !only_bad && row_parallel(d, n_votes))
         return launch_block_mean_rows(G, d, ld, winner, n_votes, B, vote_perm, Zhat, ldo, s);
-    int vec = row_vec_width(G, ld);
-    const int vo = row_vec_width(Zhat, ldo);
-    vec = vo < vec ? vo : vec;
+    constexpr int vec = 4;   // columns per lane
     const int64_t chunks = (d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     const int64_t cap = only_bad ? 512 : 4096;
     const dim3 grid((unsigned)(chunks < cap ? chunks : cap), (unsigned)B);
@@ -839,12 +821,7 @@ hipError_t launch_block_mean(const float *G, int64_t d, int64_t ld, const int32_
             block_mean_kernel<V, false><<<grid, kBlock, 0, s>>>(G, d, ld, winner, n_votes, B,    \
                                                                 vote_perm, Zhat, ldo, ob);       \
     } while (0)
-    if (vec == 4)
-        DETOX_BM(4);
-    else if (vec == 2)
-        DETOX_BM(2);
-    else
-        DETOX_BM(1);
+    DETOX_BM(4);
 #undef DETOX_BM
     return hipGetLastError();
 }

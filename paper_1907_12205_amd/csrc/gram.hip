@@ -615,12 +615,8 @@ hipError_t launch_small(const RowSet &rs, double *partials, int grid, int vec, c
         else                                                                                      \
             gram_small_kernel<C, V, false><<<grid, kBlock, 0, s>>>(rs, partials, run_if, tail, arrived);         \
     } while (0)
-    if (vec == 4)
-        DETOX_GS(4);
-    else if (vec == 2)
-        DETOX_GS(2);
-    else
-        DETOX_GS(1);
+    if (vec != 4) return hipErrorInvalidValue;
+    DETOX_GS(4);
 #undef DETOX_GS
     return hipGetLastError();
 }
@@ -628,7 +624,7 @@ hipError_t launch_small(const RowSet &rs, double *partials, int grid, int vec, c
 hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int *grid_out,
                             const SmallSelect &tail, unsigned *arrived, hipStream_t s)
 {
-    const int vec = row_vec_width(rs.base, rs.ld);
+    constexpr int vec = 4;   // columns per lane
     const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     int grid = num_compute_units() * 8;
     if (grid > kMaxGramWaves) grid = kMaxGramWaves;
@@ -656,7 +652,6 @@ hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long lo
     if (rs.means()) {
         // block means formed on the fly: offered for the row counts a hierarchical step can have
         if constexpr (T <= 2) {
-            if (!aligned) return hipErrorInvalidValue;
             gram_staged_kernel<T, true, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
         } else {
             return hipErrorInvalidValue;
@@ -702,7 +697,7 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
     const int T = (rs.count + 15) / 16;
     if (T < 1 || T > 8) return hipErrorInvalidValue;
     const MfmaWs w = carve_mfma(partials, T);
-    const bool aligned = row_vec_width(rs.base, rs.ld) == 4;
+    const bool aligned = rows_16_byte_aligned(rs.base, rs.ld);
     const bool direct = aligned && !rs.means() && T <= kDirectMaxTiles;
     int grid = num_compute_units() * (direct ? direct_blocks_per_cu(T) : staged_blocks_per_cu(T));
     if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);

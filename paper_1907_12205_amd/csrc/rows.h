@@ -20,6 +20,13 @@ namespace detox {
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+// The same vectors in memory that is only known to be aligned like its fp32 components: rows of
+// any leading dimension are read and written with them (one 16-byte instruction per lane; the
+// hardware serves global accesses of any alignment).
+typedef u32x4_t u32x4_any_t __attribute__((aligned(4)));
+typedef u32x2_t u32x2_any_t __attribute__((aligned(4)));
+typedef float f32x4_any_t __attribute__((ext_vector_type(4), aligned(4)));
+typedef float f32x2_any_t __attribute__((ext_vector_type(2), aligned(4)));
 
 // Loads `valid` (<= VEC) fp32 words starting at p as raw bits (non-temporal: every input byte is
 // used once); the rest read as zero.  Never touches memory beyond p + valid.
@@ -30,11 +37,11 @@ __device__ inline void load_words(const float *p, int valid, uint32_t (&w)[VEC])
 {
     if (valid == VEC) {
         if constexpr (VEC == 4) {
-            const u32x4_t *q = reinterpret_cast<const u32x4_t *>(p);
+            const u32x4_any_t *q = reinterpret_cast<const u32x4_any_t *>(p);
             const u32x4_t t = NT ? __builtin_nontemporal_load(q) : *q;
             w[0] = t.x, w[1] = t.y, w[2] = t.z, w[3] = t.w;
         } else if constexpr (VEC == 2) {
-            const u32x2_t *q = reinterpret_cast<const u32x2_t *>(p);
+            const u32x2_any_t *q = reinterpret_cast<const u32x2_any_t *>(p);
             const u32x2_t t = NT ? __builtin_nontemporal_load(q) : *q;
             w[0] = t.x, w[1] = t.y;
         } else {
@@ -62,9 +69,9 @@ __device__ inline void store_floats(float *p, int valid, const float (&v)[VEC])
 {
     if (valid == VEC) {
         if constexpr (VEC == 4)
-            *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<f32x4_any_t *>(p) = f32x4_any_t{v[0], v[1], v[2], v[3]};
         else if constexpr (VEC == 2)
-            *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+            *reinterpret_cast<f32x2_any_t *>(p) = f32x2_any_t{v[0], v[1]};
         else
             p[0] = v[0];
     } else {

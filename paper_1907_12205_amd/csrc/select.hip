@@ -359,9 +359,7 @@ template <bool WEIGHTED>
 hipError_t launch_combine(const RowSet &rs, const int32_t *rows, const double *weights, int m,
                           float *out, hipStream_t s)
 {
-    int vec = row_vec_width(rs.base, rs.ld);
-    const int vo = row_vec_width(out, 4);
-    vec = vo < vec ? vo : vec;
+    constexpr int vec = 4;   // columns per lane
     const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     TraceScope t(WEIGHTED ? "weighted_sum" : "rows_mean", s);
 #define DETOX_CR(V)                                                                               \
@@ -371,12 +369,7 @@ hipError_t launch_combine(const RowSet &rs, const int32_t *rows, const double *w
         else                                                                                      \
             combine_rows_kernel<V, WEIGHTED, false><<<(unsigned)chunks, kBlock, 0, s>>>(rs, rows, weights, m, out); \
     } while (0)
-    if (vec == 4)
-        DETOX_CR(4);
-    else if (vec == 2)
-        DETOX_CR(2);
-    else
-        DETOX_CR(1);
+    DETOX_CR(4);
 #undef DETOX_CR
     return hipGetLastError();
 }

@@ -304,9 +304,7 @@ hipError_t order_stat(int mode, int n, RowSet rs, const int32_t *rows, int32_t *
         phys = identity_table();
         if (!phys) return hipErrorInvalidDeviceFunction;
     }
-    int vec = row_vec_width(rs.base, rs.ld);
-    const int vo = row_vec_width(out, 4);
-    vec = vo < vec ? vo : vec;
+    const int vec = 4;   // columns per lane, before the kernels' own register budget cuts it
     switch ((n - 1) % kSortnetParts) {
     case 0: return order_stat_part0(mode, n, rs, phys, beta, out, run_if, vec, s);
     case 1: return order_stat_part1(mode, n, rs, phys, beta, out, run_if, vec, s);

@@ -259,8 +259,8 @@ def test_robust_aggregator_inside_vote_groups(dx, a0, B, f, m):
     w = workloads.config(3, d=40009)
     rng = np.random.default_rng(B * 10 + f)
     # with and without a group that has no majority (its vote is the zero vector; the Gram matrix
-    # formed in the filter pass is then replaced), with and without a vote permutation, aligned
-    # rows (Gram matrix of the 15 votes formed in the filter pass) and unaligned ones (formed per group)
+    # formed in the filter pass is then replaced), with and without a vote permutation, on rows
+    # that start on 16-byte boundaries and on rows that do not
     for broken, vote_perm, ld in ((True, None, None), (True, rng.permutation(15).astype(np.int32), 40064),
                                   (False, None, 40064), (False, rng.permutation(15).astype(np.int32), 40064),
                                   (False, None, None), (False, None, 40065), (True, None, 40065)):
@@ -368,6 +368,9 @@ def test_step_with_9_to_32_vote_groups_and_no_block_means_in_memory(dx, spec, n,
         _run(dx, w, spec, G=G, ld=ld, materialise=False)
         _run(dx, w, spec, G=G, ld=ld, materialise=False, vote_perm=vote_perm)
     _run(dx, w, spec, G=G, ld=ld, materialise=True, vote_perm=vote_perm)
+    # rows off the 16-byte grid (ld = d odd, and ld = 2 mod 4)
+    _run(dx, w, spec, G=G, materialise=False, vote_perm=vote_perm)
+    _run(dx, w, spec, G=G, ld=d + 3, materialise=False)
 
 
 @pytest.mark.parametrize("aggregator", ["multikrum", "bulyan", "geomedian"])
