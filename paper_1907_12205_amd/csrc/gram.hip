@@ -175,7 +175,7 @@ struct TileGeo {
 // Fetches this lane's pieces of the tile whose first column is col - 4*(lane%LPR).  rows: LDS
 // table with, for every padded logical row, the element offset in rs.base of the row behind it
 // (a zero or padded row: some valid row); with MEANS, the logical row itself.
-template <int T, bool ALIGNED, bool MEANS>
+template <int T, bool MEANS>
 __device__ inline void tile_fetch(const RowSet &rs, const int64_t *rows, int64_t col, bool guarded,
                                   f32x4 (&buf)[TileGeo<T>::NP])
 {
@@ -197,10 +197,7 @@ __device__ inline void tile_fetch(const RowSet &rs, const int64_t *rows, int64_t
         } else {
             const float *q = rs.base + rows[G::RPI * g + sub] + col;
             if (!guarded) {
-                if constexpr (ALIGNED)
-                    buf[g] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(q));
-                else
-                    buf[g] = f32x4{q[0], q[1], q[2], q[3]};
+                buf[g] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_any_t *>(q));
             } else {
                 const int64_t d = rs.d;
                 buf[g] = f32x4{col + 0 < d ? q[0] : 0.0f, col + 1 < d ? q[1] : 0.0f,
@@ -327,7 +324,7 @@ __device__ __forceinline__ void split_products(const SplitOperand (&a)[T], f32x4
     }
 }
 
-template <int T, bool ALIGNED, bool MEANS>
+template <int T, bool MEANS>
 __global__ __launch_bounds__(kBlock, staged_blocks_per_cu(T) > 3 ? 3 : staged_blocks_per_cu(T)) void gram_staged_kernel(
     RowSet rs, float *partials, const unsigned long long *ref_keys, const int *run_if)
 {
@@ -386,16 +383,16 @@ __global__ __launch_bounds__(kBlock, staged_blocks_per_cu(T) > 3 ? 3 : staged_bl
     const int64_t lane_col = 4 * (lane % G::LPR);
     f32x4 buf[G::NP];
     int64_t step = wave;
-    if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
+    if (step < full_tiles) tile_fetch<T, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
     while (step < full_tiles) {
         tile_park<T>(buf, zero, wr);
         step += waves;
-        if (step < full_tiles) tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
+        if (step < full_tiles) tile_fetch<T, MEANS>(rs, lds_rows, step * G::COLS + lane_col, false, buf);
         products();
     }
     // the ragged last tile (d % 64 columns) goes to one wavefront
     if ((d % G::COLS) != 0 && wave == full_tiles % waves) {
-        tile_fetch<T, ALIGNED, MEANS>(rs, lds_rows, full_tiles * G::COLS + lane_col, true, buf);
+        tile_fetch<T, MEANS>(rs, lds_rows, full_tiles * G::COLS + lane_col, true, buf);
         tile_park<T>(buf, zero, wr);
         products();
     }
@@ -646,13 +643,13 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
 // direct: the rows are plain (no block means) and 16-byte aligned, and T <= kDirectMaxTiles.
 template <int T>
 hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long long *keys, int grid,
-                       bool aligned, bool direct, const int *run_if, hipStream_t s)
+                       bool direct, const int *run_if, hipStream_t s)
 {
     TraceScope t(run_if ? "gram_mfma_bf16x3_if_redo" : "gram_mfma_bf16x3", s);
     if (rs.means()) {
         // block means formed on the fly: offered for the row counts a hierarchical step can have
         if constexpr (T <= 2) {
-            gram_staged_kernel<T, true, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+            gram_staged_kernel<T, true><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
         } else {
             return hipErrorInvalidValue;
         }
@@ -661,10 +658,8 @@ hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long lo
             gram_direct_kernel<T><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
         else
             return hipErrorInvalidValue;
-    } else if (aligned) {
-        gram_staged_kernel<T, true, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
     } else {
-        gram_staged_kernel<T, false, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
+        gram_staged_kernel<T, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
     }
     return hipGetLastError();
 }
@@ -697,8 +692,7 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
     const int T = (rs.count + 15) / 16;
     if (T < 1 || T > 8) return hipErrorInvalidValue;
     const MfmaWs w = carve_mfma(partials, T);
-    const bool aligned = rows_16_byte_aligned(rs.base, rs.ld);
-    const bool direct = aligned && !rs.means() && T <= kDirectMaxTiles;
+    const bool direct = rows_16_byte_aligned(rs.base, rs.ld) && !rs.means() && T <= kDirectMaxTiles;
     int grid = num_compute_units() * (direct ? direct_blocks_per_cu(T) : staged_blocks_per_cu(T));
     if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
     const int cols = direct ? kDirectCols : kStagedCols;
@@ -713,14 +707,14 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
         keys = w.keys;
     }
     switch (T) {
-    case 1: e = launch_mfma<1>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
-    case 2: e = launch_mfma<2>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
-    case 3: e = launch_mfma<3>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
-    case 4: e = launch_mfma<4>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
-    case 5: e = launch_mfma<5>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
-    case 6: e = launch_mfma<6>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
-    case 7: e = launch_mfma<7>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
-    default: e = launch_mfma<8>(rs, w.tiles, keys, grid, aligned, direct, run_if, s); break;
+    case 1: e = launch_mfma<1>(rs, w.tiles, keys, grid, direct, run_if, s); break;
+    case 2: e = launch_mfma<2>(rs, w.tiles, keys, grid, direct, run_if, s); break;
+    case 3: e = launch_mfma<3>(rs, w.tiles, keys, grid, direct, run_if, s); break;
+    case 4: e = launch_mfma<4>(rs, w.tiles, keys, grid, direct, run_if, s); break;
+    case 5: e = launch_mfma<5>(rs, w.tiles, keys, grid, direct, run_if, s); break;
+    case 6: e = launch_mfma<6>(rs, w.tiles, keys, grid, direct, run_if, s); break;
+    case 7: e = launch_mfma<7>(rs, w.tiles, keys, grid, direct, run_if, s); break;
+    default: e = launch_mfma<8>(rs, w.tiles, keys, grid, direct, run_if, s); break;
     }
     if (e != hipSuccess) return e;
     const int elems = tiles_for(T) * 256;
