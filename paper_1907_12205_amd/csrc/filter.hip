@@ -643,9 +643,8 @@ hipError_t launch_general_rv(const FilterParams &p, bool mean, hipStream_t s)
 
 template <int R>
 hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int mode, int nb, int *grid,
-                    int64_t chunks, int vec, hipStream_t s)
+                    int64_t chunks, hipStream_t s)
 {
-    if (vec != 4) return hipErrorInvalidValue;
     if (fused) return launch_fused_rv<R, 4>(p, mode, nb, grid, chunks, s);
     return launch_general_rv<R, 4>(p, mean, s);
 }
@@ -660,9 +659,9 @@ hipError_t launch_r(const FilterParams &p, bool mean, bool fused, int mode, int 
 #define DETOX_FR_FN2(r) filter_launch_r##r
 #define DETOX_FR_FN(r) DETOX_FR_FN2(r)
 hipError_t DETOX_FR_FN(DETOX_FILTER_R)(const FilterParams &p, bool mean, bool fused, int mode, int nb,
-                                       int *grid, int64_t chunks, int vec, hipStream_t s)
+                                       int *grid, int64_t chunks, hipStream_t s)
 {
-    return launch_r<DETOX_FILTER_R>(p, mean, fused, mode, nb, grid, chunks, vec, s);
+    return launch_r<DETOX_FILTER_R>(p, mean, fused, mode, nb, grid, chunks, s);
 }
 
 }  // namespace detox
@@ -671,7 +670,7 @@ hipError_t DETOX_FR_FN(DETOX_FILTER_R)(const FilterParams &p, bool mean, bool fu
 
 #define DETOX_DECL_FR(r)                                                                           \
     hipError_t filter_launch_r##r(const FilterParams &p, bool mean, bool fused, int mode, int nb,   \
-                                  int *grid, int64_t chunks, int vec, hipStream_t s);
+                                  int *grid, int64_t chunks, hipStream_t s);
 DETOX_DECL_FR(1) DETOX_DECL_FR(2) DETOX_DECL_FR(3) DETOX_DECL_FR(4) DETOX_DECL_FR(5) DETOX_DECL_FR(6)
 DETOX_DECL_FR(7) DETOX_DECL_FR(8) DETOX_DECL_FR(9) DETOX_DECL_FR(10) DETOX_DECL_FR(11)
 #undef DETOX_DECL_FR
@@ -759,17 +758,17 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         if (e != hipSuccess) return e;
     }
     switch (p.r) {
-    case 1: e = filter_launch_r1(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 2: e = filter_launch_r2(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 3: e = filter_launch_r3(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 4: e = filter_launch_r4(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 5: e = filter_launch_r5(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 6: e = filter_launch_r6(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 7: e = filter_launch_r7(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 8: e = filter_launch_r8(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 9: e = filter_launch_r9(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 10: e = filter_launch_r10(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
-    case 11: e = filter_launch_r11(p, mean, fused, mode, nb, &grid, chunks, vec, s); break;
+    case 1: e = filter_launch_r1(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 2: e = filter_launch_r2(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 3: e = filter_launch_r3(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 4: e = filter_launch_r4(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 5: e = filter_launch_r5(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 6: e = filter_launch_r6(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 7: e = filter_launch_r7(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 8: e = filter_launch_r8(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 9: e = filter_launch_r9(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 10: e = filter_launch_r10(p, mean, fused, mode, nb, &grid, chunks, s); break;
+    case 11: e = filter_launch_r11(p, mean, fused, mode, nb, &grid, chunks, s); break;
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

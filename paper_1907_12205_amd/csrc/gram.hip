@@ -601,7 +601,7 @@ __global__ void gram_mfma_reduce2_kernel(const double *slices, int T, int count,
 }
 
 template <int C>
-hipError_t launch_small(const RowSet &rs, double *partials, int grid, int vec, const int *run_if,
+hipError_t launch_small(const RowSet &rs, double *partials, int grid, const int *run_if,
                         const SmallSelect &tail, unsigned *arrived, hipStream_t s)
 {
     TraceScope t(run_if ? "gram_select_if_redo" : "gram_f64", s);
@@ -612,7 +612,6 @@ hipError_t launch_small(const RowSet &rs, double *partials, int grid, int vec, c
         else                                                                                      \
             gram_small_kernel<C, V, false><<<grid, kBlock, 0, s>>>(rs, partials, run_if, tail, arrived);         \
     } while (0)
-    if (vec != 4) return hipErrorInvalidValue;
     DETOX_GS(4);
 #undef DETOX_GS
     return hipGetLastError();
@@ -628,14 +627,14 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
     if (grid > chunks) grid = (int)chunks;
     *grid_out = grid;
     switch (rs.count) {
-    case 1: return launch_small<1>(rs, pp, grid, vec, run_if, tail, arrived, s);
-    case 2: return launch_small<2>(rs, pp, grid, vec, run_if, tail, arrived, s);
-    case 3: return launch_small<3>(rs, pp, grid, vec, run_if, tail, arrived, s);
-    case 4: return launch_small<4>(rs, pp, grid, vec, run_if, tail, arrived, s);
-    case 5: return launch_small<5>(rs, pp, grid, vec, run_if, tail, arrived, s);
-    case 6: return launch_small<6>(rs, pp, grid, vec, run_if, tail, arrived, s);
-    case 7: return launch_small<7>(rs, pp, grid, vec, run_if, tail, arrived, s);
-    case 8: return launch_small<8>(rs, pp, grid, vec, run_if, tail, arrived, s);
+    case 1: return launch_small<1>(rs, pp, grid, run_if, tail, arrived, s);
+    case 2: return launch_small<2>(rs, pp, grid, run_if, tail, arrived, s);
+    case 3: return launch_small<3>(rs, pp, grid, run_if, tail, arrived, s);
+    case 4: return launch_small<4>(rs, pp, grid, run_if, tail, arrived, s);
+    case 5: return launch_small<5>(rs, pp, grid, run_if, tail, arrived, s);
+    case 6: return launch_small<6>(rs, pp, grid, run_if, tail, arrived, s);
+    case 7: return launch_small<7>(rs, pp, grid, run_if, tail, arrived, s);
+    case 8: return launch_small<8>(rs, pp, grid, run_if, tail, arrived, s);
     default: return hipErrorInvalidValue;
     }
 }
