@@ -30,10 +30,13 @@ __host__ __device__ constexpr int tiles_for(int T) { return T * (T + 1) / 2; }
 
 // Workgroups (of 4 wavefronts) per CU of the two matrix-core kernels: what their LDS tiles and
 // registers let stay resident (the kernels' launch bounds hold the register count to these numbers).
-constexpr int direct_blocks_per_cu(int T) { return T <= 1 ? 6 : (T <= 2 ? 4 : (T <= 3 ? 5 : (T <= 4 ? 4 : 2))); }
+constexpr int direct_blocks_per_cu(int T) { return T <= 1 ? 6 : (T <= 2 ? 4 : (T <= 3 ? 5 : (T <= 4 ? 4 : (T <= 7 ? 2 : 4)))); }
+// Wavefronts per workgroup of the direct kernel: two with eight row tiles, so that the workgroup's
+// LDS (and with it every address its loads hand to the LDS unit) stays below 64 KiB.
+constexpr int direct_waves_per_block(int T) { return T <= 7 ? kBlock / kWave : 2; }
 constexpr int staged_blocks_per_cu(int T) { return T <= 2 ? 4 : (T <= 3 ? 3 : (T <= 4 ? 2 : 1)); }
 // Bound on the wavefront partials (sizes the workspace; assumes at most 256 CUs, more are clamped).
-constexpr int mfma_max_waves(int T) { return 256 * direct_blocks_per_cu(T) * (kBlock / kWave); }
+constexpr int mfma_max_waves(int T) { return 256 * direct_blocks_per_cu(T) * direct_waves_per_block(T); }
 
 // ---------------------------------------------------------------------------------------
 // count <= 8: fp64 on the vector ALUs
@@ -154,9 +157,9 @@ __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double 
 // component v of lane l.  Before the cut, the reference row's values at the same columns are
 // subtracted (rows.h, pick_reference).
 //
-// Two kernels feed these products.  gram_direct_kernel (16-byte aligned plain rows, up to 7 row
-// tiles) has its loads write the tile straight into LDS.  gram_staged_kernel (everything else:
-// block means formed on the fly, unaligned rows, 8 row tiles, the ragged shapes) fetches a tile
+// Two kernels feed these products.  gram_direct_kernel (16-byte aligned plain rows) has its loads
+// write the tile straight into LDS.  gram_staged_kernel (everything else: block means formed on
+// the fly, rows off the 16-byte grid) fetches a tile
 // into registers with loads that are contiguous along the rows, parks it in LDS and reads the
 // operands back from there.  Either way every wavefront owns a strided share of the column tiles
 // and one LDS tile, and issues the loads of its next tile before it multiplies the current one.
@@ -415,20 +418,22 @@ __global__ __launch_bounds__(kBlock, staged_blocks_per_cu(T) > 3 ? 3 : staged_bl
 // different groups of banks.
 // ---------------------------------------------------------------------------------------
 constexpr int kDirectCols = 32;
-constexpr int kDirectMaxTiles = 7;   // with eight row tiles the workgroup's LDS passes 64 KiB
 
 typedef __attribute__((address_space(1))) const void *GlobalPtr;
 typedef __attribute__((address_space(3))) void *LdsPtr;
 
 template <int T>
-__global__ __launch_bounds__(kBlock, direct_blocks_per_cu(T)) void gram_direct_kernel(RowSet rs, float *partials,
+__global__ __launch_bounds__(kWave * direct_waves_per_block(T),
+                             direct_blocks_per_cu(T) * direct_waves_per_block(T) / 4) void gram_direct_kernel(RowSet rs, float *partials,
                                                                 const unsigned long long *ref_keys,
                                                                 const int *run_if)
 {
     if (run_if && *run_if == 0) return;   // uniform
     constexpr int NT = tiles_for(T), kRows = 16 * T, kInst = 2 * T;
     constexpr int kTileBytes = kRows * kDirectCols * 4;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_tiles[(kBlock / kWave) * kTileBytes];
+    constexpr int kWaves = direct_waves_per_block(T);
+    static_assert(kWave * kWaves >= kRows, "one thread per row sets up the row table");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_tiles[kWaves * kTileBytes];
     __shared__ int64_t lds_rows[kRows];
     __shared__ __attribute__((aligned(16))) float lds_zeros[kDirectCols];
     __shared__ int lds_any_zero;
@@ -436,8 +441,8 @@ __global__ __launch_bounds__(kBlock, direct_blocks_per_cu(T)) void gram_direct_k
     const int64_t d = rs.d;
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + wv;
-    const int64_t waves = (int64_t)gridDim.x * (kBlock / kWave);
+    const int64_t wave = (int64_t)blockIdx.x * kWaves + wv;
+    const int64_t waves = (int64_t)gridDim.x * kWaves;
 
     // padded rows repeat the last row (their entries are never reported); a row that stands for
     // the zero vector is fetched from row 0 and replaced by zeros when the operands are read
@@ -639,7 +644,7 @@ hipError_t launch_small_any(const RowSet &rs, double *pp, const int *run_if, int
     }
 }
 
-// direct: the rows are plain (no block means) and 16-byte aligned, and T <= kDirectMaxTiles.
+// direct: the rows are plain (no block means) and 16-byte aligned.
 template <int T>
 hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long long *keys, int grid,
                        bool direct, const int *run_if, hipStream_t s)
@@ -653,10 +658,7 @@ hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long lo
             return hipErrorInvalidValue;
         }
     } else if (direct) {
-        if constexpr (T <= kDirectMaxTiles)
-            gram_direct_kernel<T><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
-        else
-            return hipErrorInvalidValue;
+        gram_direct_kernel<T><<<grid, kWave * direct_waves_per_block(T), 0, s>>>(rs, partials, keys, run_if);
     } else {
         gram_staged_kernel<T, false><<<grid, kBlock, 0, s>>>(rs, partials, keys, run_if);
     }
@@ -691,14 +693,15 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
     const int T = (rs.count + 15) / 16;
     if (T < 1 || T > 8) return hipErrorInvalidValue;
     const MfmaWs w = carve_mfma(partials, T);
-    const bool direct = rows_16_byte_aligned(rs.base, rs.ld) && !rs.means() && T <= kDirectMaxTiles;
+    const bool direct = rows_16_byte_aligned(rs.base, rs.ld) && !rs.means();
     int grid = num_compute_units() * (direct ? direct_blocks_per_cu(T) : staged_blocks_per_cu(T));
-    if (grid * (kBlock / kWave) > mfma_max_waves(T)) grid = mfma_max_waves(T) / (kBlock / kWave);
+    const int wpb = direct ? direct_waves_per_block(T) : kBlock / kWave;   // wavefronts per workgroup
+    if (grid * wpb > mfma_max_waves(T)) grid = mfma_max_waves(T) / wpb;
     const int cols = direct ? kDirectCols : kStagedCols;
     const int64_t tiles = (rs.d + cols - 1) / cols;
-    const int64_t need = (tiles + kBlock / kWave - 1) / (kBlock / kWave);
+    const int64_t need = (tiles + wpb - 1) / wpb;
     if (grid > need) grid = (int)need;
-    const int waves = grid * (kBlock / kWave);
+    const int waves = grid * wpb;
     hipError_t e = hipSuccess;
     if (keys == nullptr) {
         e = launch_reference_keys(ref_rows_of(rs), w.keys, run_if, s);
