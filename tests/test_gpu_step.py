@@ -234,6 +234,10 @@ def test_tiny_dimensions(dx, d):
     D = oracle.pairwise_sqdist(G)
     scores = oracle.krum_scores(D, 5)
     assert np.allclose(np.sort(scores[host(sel)]), np.sort(scores[ref_sel]), rtol=1e-5, atol=1e-12)
+    # ... and that what is valid holds: 40 different rows, and the output is their mean
+    picked = host(sel)
+    assert len(set(picked.tolist())) == 40 and picked.min() >= 0 and picked.max() < G.shape[0]
+    assert rel_l2(host(out), G[picked].astype(np.float64).sum(axis=0) / 40.0) <= TOL
     assert host(dx.robust_coord_median(Gd)).tobytes() == oracle.coord_median(G).tobytes()
 
 
