@@ -3,9 +3,10 @@
 // Section 4, "Improved speed") and of the Gram-space Weiszfeld iteration.
 //
 //   count <= 8 : fp64 FMAs on the vector ALUs, all pairs held in registers per thread.
-//   count  > 8 : fp32 MFMA 16x16x4 tiles (upper triangle of the tile grid), one accumulator set
-//                per wavefront over a strided share of the columns.
-// Either way every workgroup / wavefront writes its partial sums to the workspace and a second
+//   count  > 8 : bf16 MFMA 16x16x32 tiles on fp32 operands cut into three bf16 pieces (upper
+//                triangle of the tile grid), one accumulator set per wavefront over a strided
+//                share of the columns, added up within the workgroup at the end.
+// Either way every workgroup writes its partial sums to the workspace and a second
 // kernel (or, in the conditional repeat of a small Gram matrix, the workgroup that an integer
 // counter shows to be the last) adds them in a fixed order in fp64.  No floating-point atomics:
 // results repeat bit for bit, and rows
@@ -35,8 +36,9 @@ constexpr int direct_blocks_per_cu(int T) { return T <= 1 ? 6 : (T <= 2 ? 4 : (T
 // LDS (and with it every address its loads hand to the LDS unit) stays below 64 KiB.
 constexpr int direct_waves_per_block(int T) { return T <= 7 ? kBlock / kWave : 2; }
 constexpr int staged_blocks_per_cu(int T) { return T <= 2 ? 4 : (T <= 3 ? 3 : (T <= 4 ? 2 : 1)); }
-// Bound on the wavefront partials (sizes the workspace; assumes at most 256 CUs, more are clamped).
-constexpr int mfma_max_waves(int T) { return 256 * direct_blocks_per_cu(T) * direct_waves_per_block(T); }
+// Bound on the workgroups, each of which leaves one set of partial tiles (sizes the workspace;
+// assumes at most 256 CUs, more are clamped).
+constexpr int mfma_max_blocks(int T) { return 256 * direct_blocks_per_cu(T); }
 
 // ---------------------------------------------------------------------------------------
 // count <= 8: fp64 on the vector ALUs
@@ -327,6 +329,43 @@ __device__ __forceinline__ void split_products(const SplitOperand (&a)[T], f32x4
     }
 }
 
+
+// Adds the accumulators of a workgroup's WAVES wavefronts (a power of two) into those of
+// wavefront 0, pairwise in a fixed order (wavefront w takes in w + WAVES/2, then w + WAVES/4, ..),
+// through LDS that nothing else uses any more, in as many portions of tiles as its size asks for.
+// Every thread of the workgroup calls it.
+template <int NT, int WAVES, int LDS_FLOATS>
+__device__ __forceinline__ void add_up_workgroup(f32x4 (&acc)[NT], float *lds, int wv, int lane)
+{
+    if constexpr (WAVES > 1) {
+        constexpr int kFit = LDS_FLOATS / ((WAVES / 2) * 256);   // tiles per portion at the widest level
+        constexpr int CH = kFit < NT ? kFit : NT;
+        static_assert(CH >= 1, "room for one tile per sending wavefront");
+#pragma unroll
+        for (int half = WAVES / 2; half >= 1; half >>= 1) {
+#pragma unroll
+            for (int t0 = 0; t0 < NT; t0 += CH) {
+                __syncthreads();
+                if (wv >= half && wv < 2 * half) {
+                    float *slot = lds + (wv - half) * (CH * 256) + lane;
+#pragma unroll
+                    for (int t = t0; t < NT && t < t0 + CH; ++t)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) slot[(t - t0) * 256 + v * 64] = acc[t][v];
+                }
+                __syncthreads();
+                if (wv < half) {
+                    const float *slot = lds + wv * (CH * 256) + lane;
+#pragma unroll
+                    for (int t = t0; t < NT && t < t0 + CH; ++t)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[t][v] += slot[(t - t0) * 256 + v * 64];
+                }
+            }
+        }
+    }
+}
+
 template <int T, bool MEANS>
 __global__ __launch_bounds__(kBlock, staged_blocks_per_cu(T) > 3 ? 3 : staged_blocks_per_cu(T)) void gram_staged_kernel(
     RowSet rs, float *partials, const unsigned long long *ref_keys, const int *run_if)
@@ -399,8 +438,10 @@ __global__ __launch_bounds__(kBlock, staged_blocks_per_cu(T) > 3 ? 3 : staged_bl
         tile_park<T>(buf, zero, wr);
         products();
     }
+    add_up_workgroup<NT, kBlock / kWave, (kBlock / kWave) * 16 * T * G::PITCH>(acc, lds_tiles, wv, lane);
+    if (wv != 0) return;
     // C[4*(l/16)+v][l%16] of tile t at [t][v][l]
-    float *out = partials + wave * (int64_t)(NT * 256) + lane;
+    float *out = partials + blockIdx.x * (int64_t)(NT * 256) + lane;
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -553,16 +594,18 @@ __global__ __launch_bounds__(kWave * direct_waves_per_block(T),
         read_raw(x0, x1, c0, c1);
         multiply(x0, x1, c0, c1);
     }
+    add_up_workgroup<NT, kWaves, kWaves * kTileBytes / 4>(acc, reinterpret_cast<float *>(lds_tiles), wv, lane);
+    if (wv != 0) return;
     // C[4*(l/16)+v][l%16] of tile t at [t][v][l]
-    float *out = partials + wave * (int64_t)(NT * 256) + lane;
+    float *out = partials + blockIdx.x * (int64_t)(NT * 256) + lane;
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) out[t * 256 + v * 64] = acc[t][v];
 }
 
-// Adds the per-wavefront tiles in fp64, in two fixed-order levels: kReduceSlices contiguous
-// ranges of wavefronts are summed side by side (threads run along the tile elements, so every
+// Adds the tile sets in the workspace (one per workgroup, or per wavefront of the filter pass) in
+// fp64, in two fixed-order levels: kReduceSlices contiguous ranges of them are summed side by side (threads run along the tile elements, so every
 // load is coalesced), then the slice sums are added in slice order and scattered into the matrix.
 constexpr int kReduceSlices = 32;
 
@@ -665,14 +708,14 @@ hipError_t launch_mfma(const RowSet &rs, float *partials, const unsigned long lo
     return hipGetLastError();
 }
 
-// Workspace of the matrix-core path: one tile set of partial sums per wavefront (room for the
+// Workspace of the matrix-core path: one tile set of partial sums per workgroup (room for the
 // largest grid), the slice sums of the first reduction level, the reference keys.
 struct MfmaWs {
     float *tiles;
     double *slices;
     unsigned long long *keys;
 };
-size_t mfma_slot_floats(int T) { return (size_t)mfma_max_waves(T) * (size_t)tiles_for(T) * 256; }
+size_t mfma_slot_floats(int T) { return (size_t)mfma_max_blocks(T) * (size_t)tiles_for(T) * 256; }
 MfmaWs carve_mfma(void *partials, int T)
 {
     MfmaWs w;
@@ -696,12 +739,11 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
     const bool direct = rows_16_byte_aligned(rs.base, rs.ld) && !rs.means();
     int grid = num_compute_units() * (direct ? direct_blocks_per_cu(T) : staged_blocks_per_cu(T));
     const int wpb = direct ? direct_waves_per_block(T) : kBlock / kWave;   // wavefronts per workgroup
-    if (grid * wpb > mfma_max_waves(T)) grid = mfma_max_waves(T) / wpb;
+    if (grid > mfma_max_blocks(T)) grid = mfma_max_blocks(T);
     const int cols = direct ? kDirectCols : kStagedCols;
     const int64_t tiles = (rs.d + cols - 1) / cols;
     const int64_t need = (tiles + wpb - 1) / wpb;
     if (grid > need) grid = (int)need;
-    const int waves = grid * wpb;
     hipError_t e = hipSuccess;
     if (keys == nullptr) {
         e = launch_reference_keys(ref_rows_of(rs), w.keys, run_if, s);
@@ -723,7 +765,7 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
     {
         TraceScope t("gram_reduce", s);
         gram_mfma_reduce1_kernel<<<dim3((elems + kBlock - 1) / kBlock, kReduceSlices), kBlock, 0, s>>>(
-            w.tiles, waves, elems, w.slices, alt, alt_waves, run_if);
+            w.tiles, grid, elems, w.slices, alt, alt_waves, run_if);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -297,19 +297,15 @@ __global__ __launch_bounds__(kWzGramThreads) void weiszfeld_kernel(const double 
 
 // WEIGHTED = false: out = fp32( (sum_i (double) row[rows[i]]) / m ), logical rows in list order.
 // WEIGHTED = true : out = fp32( sum_j weights[j] * (double) row[j] ) over all logical rows.
+// One thread's VEC columns from col on (valid of them exist; full: the whole chunk of the
+// workgroup exists, uniform).
 template <int VEC, bool WEIGHTED, bool MEANS>
-__global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const int32_t *rows,
-                                                              const double *weights, int m,
-                                                              float *out)
+__device__ __forceinline__ void combine_columns(const RowSet &rs, const int32_t *rows, const double *weights, int m,
+                                                int64_t col, int valid, bool full, float (&o)[VEC])
 {
-    const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
-    const int64_t left = rs.d - col;
-    if (left <= 0) return;
-    const int valid = left >= VEC ? VEC : (int)left;
     double acc[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.0;
-    const bool full = ((int64_t)blockIdx.x + 1) * kBlock * VEC <= rs.d;   // uniform
     auto logical_row = [&](int k) {
         int b = k;
         if constexpr (!WEIGHTED) {
@@ -349,10 +345,130 @@ __global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const i
             add_row(k, x);
         }
     }
-    float o[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) o[i] = WEIGHTED ? (float)acc[i] : (float)(acc[i] / (double)m);
+}
+
+template <int VEC, bool WEIGHTED, bool MEANS>
+__global__ __launch_bounds__(kBlock) void combine_rows_kernel(RowSet rs, const int32_t *rows,
+                                                              const double *weights, int m,
+                                                              float *out)
+{
+    const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+    const int64_t left = rs.d - col;
+    if (left <= 0) return;
+    const int valid = left >= VEC ? VEC : (int)left;
+    const bool full = ((int64_t)blockIdx.x + 1) * kBlock * VEC <= rs.d;   // uniform
+    float o[VEC];
+    combine_columns<VEC, WEIGHTED, MEANS>(rs, rows, weights, m, col, valid, full, o);
     store_floats<VEC>(out + col, valid, o);
+}
+
+// The same with BURST adjacent chunks per workgroup, whose results stay in registers until all of
+// them are there and are stored together.  Launched so that every workgroup of the grid is
+// resident at once: they all read, then they all write, and the chip's memory sees one stretch of
+// reads and one of writes instead of writes scattered among the reads.
+// chunk0: first chunk of this launch; chunks: one past its last.
+// Of a workgroup's BURST results per thread the first burst_in_registers(BURST) wait in registers,
+// the others in LDS (every thread reads back only what it wrote itself).
+constexpr int burst_in_registers(int burst) { return burst <= 4 ? burst : 2; }   // 8: 24 KB of LDS, six workgroups per CU
+
+// col: this thread's first column of the workgroup's first chunk; all BURST chunks exist in full.
+template <int VEC, bool WEIGHTED, bool MEANS, int BURST, int J = 0>
+__device__ __forceinline__ void burst_columns(const RowSet &rs, const int32_t *rows, const double *weights, int m,
+                                              int64_t col, float (&o)[burst_in_registers(BURST)][VEC], float *parked)
+{
+    // compile-time recursion instead of an unrolled loop: the results must stay a register array
+    if constexpr (J < BURST) {
+        if constexpr (J < burst_in_registers(BURST)) {
+            combine_columns<VEC, WEIGHTED, MEANS>(rs, rows, weights, m, col + J * (kBlock * VEC), VEC, true, o[J]);
+        } else {
+            float v[VEC];
+            combine_columns<VEC, WEIGHTED, MEANS>(rs, rows, weights, m, col + J * (kBlock * VEC), VEC, true, v);
+            float *slot = parked + ((J - burst_in_registers(BURST)) * kBlock + threadIdx.x) * VEC;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) slot[i] = v[i];
+        }
+        burst_columns<VEC, WEIGHTED, MEANS, BURST, J + 1>(rs, rows, weights, m, col, o, parked);
+    }
+}
+
+constexpr int kBurstMinRows = 16;
+constexpr int kBurstWavesPerSimd = 6;   // launch bound of the burst kernel = its workgroups per CU
+
+template <int VEC, bool WEIGHTED, bool MEANS, int BURST>
+__global__ __launch_bounds__(kBlock, kBurstWavesPerSimd) void combine_rows_burst_kernel(
+    RowSet rs, const int32_t *rows, const double *weights, int m, int64_t chunk0, int64_t chunks, float *out)
+{
+    constexpr int REG = burst_in_registers(BURST);
+    __shared__ __attribute__((aligned(16))) float parked[(BURST > REG ? BURST - REG : 1) * kBlock * VEC];
+    const int64_t first = chunk0 + (int64_t)blockIdx.x * BURST;
+    const int64_t col = (first * kBlock + threadIdx.x) * VEC;
+    if (first + BURST > chunks || (first + BURST) * kBlock * VEC > rs.d) {   // uniform
+        // the workgroup at the ragged end: chunk by chunk, stored as they come
+        for (int j = 0; j < BURST && first + j < chunks; ++j) {
+            const int64_t c = col + j * (kBlock * VEC);
+            const int64_t left = rs.d - c;
+            if (left <= 0) continue;
+            const int valid = left >= VEC ? VEC : (int)left;
+            float v[VEC];
+            combine_columns<VEC, WEIGHTED, MEANS>(rs, rows, weights, m, c, valid,
+                                                  (first + j + 1) * kBlock * VEC <= rs.d, v);
+            store_floats<VEC>(out + c, valid, v);
+        }
+        return;
+    }
+    float o[REG][VEC];
+    burst_columns<VEC, WEIGHTED, MEANS, BURST>(rs, rows, weights, m, col, o, parked);
+#pragma unroll
+    for (int j = 0; j < BURST; ++j) {
+        if (j < REG) {
+            store_floats<VEC>(out + col + j * (kBlock * VEC), VEC, o[j < REG ? j : 0]);
+        } else {
+            float v[VEC];
+            int at = ((j - REG) * kBlock + threadIdx.x) * VEC;
+            asm volatile("" : "+v"(at));   // or the compiler keeps the value in a register after all
+            const float *slot = parked + at;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) v[i] = slot[i];
+            store_floats<VEC>(out + col + j * (kBlock * VEC), VEC, v);
+        }
+    }
+}
+
+template <bool WEIGHTED, bool MEANS, int BURST>
+hipError_t launch_combine_burst(const RowSet &rs, const int32_t *rows, const double *weights, int m,
+                                float *out, int64_t chunks, int64_t resident, hipStream_t s)
+{
+    // as many launches as it takes for each to be resident as a whole
+    const int64_t per_launch = resident * BURST;
+    for (int64_t chunk0 = 0; chunk0 < chunks; chunk0 += per_launch) {
+        const int64_t end = chunk0 + per_launch < chunks ? chunk0 + per_launch : chunks;
+        const unsigned grid = (unsigned)((end - chunk0 + BURST - 1) / BURST);
+        combine_rows_burst_kernel<4, WEIGHTED, MEANS, BURST><<<grid, kBlock, 0, s>>>(rs, rows, weights, m, chunk0, end, out);
+    }
+    return hipGetLastError();
+}
+
+template <bool WEIGHTED, bool MEANS>
+hipError_t launch_combine_as(const RowSet &rs, const int32_t *rows, const double *weights, int m,
+                             float *out, int64_t chunks, hipStream_t s)
+{
+    // the fewest chunks per workgroup with which the grid is resident at once (one chunk each is
+    // the plain kernel); beyond eight, several launches
+    const int64_t resident = (int64_t)num_compute_units() * kBurstWavesPerSimd;
+    // Rows of the matrix read per output row.  Stores among the loads slow the loads down by about
+    // a tenth however few they are, a closing stretch of stores costs its own time (10 us for
+    // d = 11.17M): holding the results back pays from about 16 rows on (3 of 5 block means = 9 rows:
+    // 0.078 ms chunk by chunk, 0.083 held back; 40 rows: 0.306 and 0.280).
+    const int64_t reads = MEANS ? ((int64_t)m * rs.n_votes + rs.count - 1) / rs.count : m;
+    if (chunks <= resident || reads < kBurstMinRows) {
+        combine_rows_kernel<4, WEIGHTED, MEANS><<<(unsigned)chunks, kBlock, 0, s>>>(rs, rows, weights, m, out);
+        return hipGetLastError();
+    }
+    if (chunks <= 2 * resident) return launch_combine_burst<WEIGHTED, MEANS, 2>(rs, rows, weights, m, out, chunks, resident, s);
+    if (chunks <= 4 * resident) return launch_combine_burst<WEIGHTED, MEANS, 4>(rs, rows, weights, m, out, chunks, resident, s);
+    return launch_combine_burst<WEIGHTED, MEANS, 8>(rs, rows, weights, m, out, chunks, resident, s);
 }
 
 template <bool WEIGHTED>
@@ -362,16 +478,8 @@ hipError_t launch_combine(const RowSet &rs, const int32_t *rows, const double *w
     constexpr int vec = 4;   // columns per lane
     const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
     TraceScope t(WEIGHTED ? "weighted_sum" : "rows_mean", s);
-#define DETOX_CR(V)                                                                               \
-    do {                                                                                          \
-        if (rs.means())                                                                           \
-            combine_rows_kernel<V, WEIGHTED, true><<<(unsigned)chunks, kBlock, 0, s>>>(rs, rows, weights, m, out); \
-        else                                                                                      \
-            combine_rows_kernel<V, WEIGHTED, false><<<(unsigned)chunks, kBlock, 0, s>>>(rs, rows, weights, m, out); \
-    } while (0)
-    DETOX_CR(4);
-#undef DETOX_CR
-    return hipGetLastError();
+    return rs.means() ? launch_combine_as<WEIGHTED, true>(rs, rows, weights, m, out, chunks, s)
+                      : launch_combine_as<WEIGHTED, false>(rs, rows, weights, m, out, chunks, s);
 }
 
 // out[b] = table[pick[b]], pick clamped to [0, table_len) so that a bad entry cannot fault.

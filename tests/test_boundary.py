@@ -86,11 +86,11 @@ def test_argument_validation_happens_on_the_host(dx):
                                       dx.workspace_bytes("step_robust_blocks", 15, 10, 2) - 256, None) == EWS
     assert L.detox_step_robust_blocks(p, 45, 10, 10, 3, None, 2, None, 0, 3, 3, p, p, 10, p, p, p, big, None) == EPRECOND
     # the variant on the library's own scratch array: a step that needs more than the array holds
-    # is refused on the host (40 rows for the aggregator: 3 row tiles of Gram partials)
+    # is refused on the host (120 rows for the aggregator: 8 row tiles of Gram partials)
     header = open(os.path.join(ROOT, "include", "detox.h")).read()
     assert int(re.search(r"DETOX_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << 20\)", header).group(1)) << 20 < \
-        dx.workspace_bytes("step", 120, 10, 40)
-    assert L.detox_step_static(p, 120, 10, 10, 3, 5, None, 40, None, 2, -1, -1, 50, ctypes.c_double(1e-8),
+        dx.workspace_bytes("step", 360, 10, 120)
+    assert L.detox_step_static(p, 360, 10, 10, 3, 5, None, 120, None, 2, -1, -1, 50, ctypes.c_double(1e-8),
                                p, None, 0, p, p, None) == EWS
     assert L.detox_step_static(p, 45, 10, 10, 3, 5, None, 16, None, 0, 1, 3, 50, ctypes.c_double(1e-8),
                                p, p, 10, p, p, None) == EINVAL

@@ -141,6 +141,26 @@ def test_bulyan_on_replicated_matrix_and_heavy_tails(dx):
     assert rel_l2(host(out), ref_out) <= TOL
 
 
+@pytest.mark.parametrize("d", [1_600_003, 2_000_003, 3_145_727, 4_000_037, 6_291_456, 6_300_001])
+def test_averages_of_many_rows_at_middle_sizes(dx, d):
+    """Mean of 20 selected rows and weighted sum of 24 rows where the averaging kernel holds 2, 4
+    or 8 chunks of 1024 columns per workgroup back before it stores them (d from 1.6M on, on a
+    256-CU chip), with a ragged last chunk and without one."""
+    X = workloads.distinct_rows(77, 24, d, sigma=0.03)
+    X[3] += 0.05
+    ref_out, ref_sel, _ = oracle.multikrum(X, 2, 20)
+    Xd = dev_matrix(X)
+    out, sel, _ = dx.robust_multikrum(Xd, 2, 20)
+    assert host(sel).tolist() == ref_sel.tolist()
+    assert rel_l2(host(out), ref_out) <= TOL
+    edges = np.r_[0:2048, d - 2048:d]
+    np.testing.assert_allclose(host(out)[edges], ref_out[edges], rtol=1e-5, atol=1e-9)
+    ref = oracle.geomedian(X, iters=3, eps=1e-8)
+    got = host(dx.robust_geomedian(Xd, iters=3, eps=1e-8))
+    assert rel_l2(got, ref) <= TOL
+    np.testing.assert_allclose(got[edges], ref[edges], rtol=1e-4, atol=1e-8)
+
+
 @pytest.mark.parametrize("count", [1, 2, 3, 7, 8, 9, 21, 45])
 def test_geomedian(dx, count):
     X = workloads.distinct_rows(50 + count, count, 20011, sigma=0.03)

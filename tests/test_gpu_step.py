@@ -148,9 +148,14 @@ def test_full_size_resnet18_shape(dx):
 
 
 def _sample_columns(d, width=4096, pieces=6, seed=0):
-    """Column windows spread over [0, d), including both ends (the ragged tail too)."""
+    """Column windows spread over [0, d), including both ends (the ragged tail too) and, where
+    d reaches that far, the column at which the averaging kernels start their second launch on
+    a 256-CU chip (1536 workgroups x 8 chunks x 1024 columns)."""
     rng = np.random.default_rng(seed)
     starts = [0, d - width] + [int(x) for x in rng.integers(0, d - width, size=pieces - 2)]
+    seam = 1536 * 8 * 1024
+    if d > seam + width:
+        starts.append(seam - width // 2)
     return [(s, s + width) for s in sorted(starts)]
 
 

@@ -68,8 +68,9 @@ def test_static_scratch_step_equals_the_step_with_a_workspace(dx, spec):
 def test_static_scratch_step_refuses_what_does_not_fit(dx):
     from paper_1907_12205_amd.binding import StepBuffers
     w = workloads.config(3, d=1000)
-    G = dev_matrix(np.tile(w.matrix(), (3, 1)))          # 135 rows, 45 node groups
-    buf = StepBuffers(135, 1000, 3, 45, G.device, materialise=False, workspace=False)
+    G = dev_matrix(np.tile(w.matrix(), (8, 1)))          # 360 rows, 120 node groups
+    assert dx.workspace_bytes("step", 360, 1000, 120) > 16 << 20
+    buf = StepBuffers(360, 1000, 3, 120, G.device, materialise=False, workspace=False)
     with pytest.raises(dx.DetoxError) as err:
-        dx.detox_step_static(G, 3, 5, 45, "coord_median", buf)
+        dx.detox_step_static(G, 3, 5, 120, "coord_median", buf)
     assert err.value.code == 3
