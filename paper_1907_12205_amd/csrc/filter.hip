@@ -150,8 +150,24 @@ __device__ inline int32_t winner_from_bits(unsigned long long bits, const int32_
 // ---------------------------------------------------------------------------------------
 enum FusedMode { kFilterOnly = 0, kMeans = 1, kGram = 2, kMedian = 3, kTrimmedMean = 4, kVotesGram = 5, kSignVote = 6 };
 
+// Registers per lane that the median / trimmed-mean modes take without holding results back: a
+// bound fitted to the compiler's counts (four columns per lane).  Where it leaves room below the
+// 128 registers of four wavefronts per SIMD (the residency these modes run at), results wait in
+// the spare registers, four per trip, and the kernel is held to 128.
+constexpr int fused_register_estimate(int R, int NB) { return 12 * R - 9 + 6 * NB; }
+constexpr int hold_registers(int R, int NB, int MODE)
+{
+    if (MODE != kMedian && MODE != kTrimmedMean) return 0;
+    const int spare = (124 - fused_register_estimate(R, NB)) / 4;
+    return spare < 0 ? 0 : (spare > 12 ? 12 : spare);
+}
+constexpr int fused_waves_per_simd(int R, int NB, int MODE)
+{
+    return (MODE == kMedian || MODE == kTrimmedMean) && fused_register_estimate(R, NB) <= 124 ? 4 : 1;
+}
+
 template <int R, int VEC, int NB, int MODE>
-__global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
+__global__ __launch_bounds__(kBlock, fused_waves_per_simd(R, NB, MODE)) void fused_all_kernel(FilterParams p)
 {
     constexpr bool MEAN = MODE != kFilterOnly && MODE != kVotesGram && MODE != kSignVote;
     constexpr bool REGS = MODE == kGram || MODE == kMedian || MODE == kTrimmedMean;   // means of all blocks in registers
@@ -164,6 +180,15 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
     constexpr int kTileLd = 68;
     __shared__ __attribute__((aligned(16))) float vtile[MODE == kVotesGram ? kBlock / kWave : 1][16][kTileLd];
     [[maybe_unused]] f32x4_t macc = {0.0f, 0.0f, 0.0f, 0.0f};
+    // The modes that write a result vector hold their results back and store them after the last
+    // trip: stores scattered among the loads of this pass cost several times their bytes (the
+    // pass reads 45 rows of d = 11.17M in 0.30 ms; with one row of results stored trip by trip it
+    // took 0.36).  The first kHoldLds trips of a workgroup wait in LDS, the next kHoldReg in
+    // registers; only what comes after that is stored at once.
+    constexpr bool HOLD = MODE == kMedian || MODE == kTrimmedMean;
+        constexpr int kHoldLds = 7, kHoldReg = hold_registers(R, NB, MODE);
+    __shared__ __attribute__((aligned(16))) float parked[HOLD ? kHoldLds * kBlock * VEC : 1];
+    [[maybe_unused]] float held[kHoldReg > 0 ? kHoldReg : 1][VEC] = {};
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock) sbits[j] = 0ull;
     __syncthreads();
 
@@ -174,11 +199,29 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
     for (int i = 0; i < NP; ++i) gacc[i] = 0.0;
 
     const int64_t chunks = (p.d + (int64_t)kBlock * VEC - 1) / ((int64_t)kBlock * VEC);
-    for (int64_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
+    int trip = 0;
+    for (int64_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x, ++trip) {
         const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
         const int64_t left = p.d - col;
         const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
         const bool full = (chunk + 1) * kBlock * VEC <= p.d;   // uniform
+        [[maybe_unused]] auto emit = [&](const float (&v)[VEC]) {
+            if (HOLD && trip < kHoldLds) {
+                float *slot = parked + (trip * kBlock + (int)threadIdx.x) * VEC;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) slot[i] = v[i];
+            } else if (HOLD && trip < kHoldLds + kHoldReg) {
+                // constant indices only, so that the array stays in registers
+#pragma unroll
+                for (int h = 0; h < kHoldReg; ++h)
+                    if (trip - kHoldLds == h) {   // uniform
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) held[h][i] = v[i];
+                    }
+            } else if (valid > 0) {
+                store_floats<VEC>(p.out + col, valid, v);
+            }
+        };
         // one vote group: votes, pair bits, and (MEAN) its mean
         auto do_block = [&](int64_t b, float (&acc)[VEC]) {
             const int64_t lo = (b * p.n_votes) / B, hi = ((b + 1) * p.n_votes) / B;
@@ -354,7 +397,7 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
                     if (a >= p.trim_g && a < NB - p.trim_g) s += (double)key_value(k[a][i]);
                 tm[i] = (float)(s / (double)(NB - 2 * p.trim_g));
             }
-            if (valid > 0) store_floats<VEC>(p.out + col, valid, tm);
+            emit(tm);
         }
         if constexpr (MODE == kMedian) {
             uint32_t k[NB][VEC];
@@ -366,7 +409,29 @@ __global__ __launch_bounds__(kBlock) void fused_all_kernel(FilterParams p)
             float med[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) med[i] = median_of_sorted<NB, VEC>(k, i);
-            if (valid > 0) store_floats<VEC>(p.out + col, valid, med);
+            emit(med);
+        }
+    }
+    if constexpr (HOLD) {
+        for (int h = 0; h < kHoldLds; ++h) {
+            const int64_t chunk = blockIdx.x + (int64_t)h * gridDim.x;
+            if (chunk >= chunks) break;
+            const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
+            const int64_t left = p.d - col;
+            const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+            float v[VEC];
+            const float *slot = parked + (h * kBlock + (int)threadIdx.x) * VEC;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) v[i] = slot[i];
+            if (valid > 0) store_floats<VEC>(p.out + col, valid, v);
+        }
+#pragma unroll
+        for (int h = 0; h < kHoldReg; ++h) {
+            const int64_t chunk = blockIdx.x + (int64_t)(kHoldLds + h) * gridDim.x;
+            const int64_t col = (chunk * kBlock + threadIdx.x) * VEC;
+            const int64_t left = p.d - col;
+            const int valid = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+            if (chunk < chunks && valid > 0) store_floats<VEC>(p.out + col, valid, held[h]);
         }
     }
     __syncthreads();
