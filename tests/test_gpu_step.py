@@ -139,6 +139,15 @@ def test_full_size_resnet18_shape(dx):
     assert rel_l2(host(b.out), ref_out) <= TOL
     b2 = dx.detox_step(Gd, 3, 5, spec["B"], "multikrum", f=spec["f"], m=spec["m"], materialise=False)
     assert host(b2.out).tobytes() == host(b.out).tobytes()      # the launch configuration bench.py times
+    # the one-pass median and trimmed mean (results held back in LDS and registers until a
+    # workgroup's last trip): every column
+    ref_med = oracle.detox_step(G, 3, spec["B"], "coord_median")[0]
+    med = dx.detox_step(Gd, 3, 5, spec["B"], "coord_median", materialise=False)
+    assert host(med.out).tobytes() == ref_med.tobytes()
+    ref_tm = oracle.detox_step(G, 3, spec["B"], "trimmed_mean", f=1)[0]
+    tm = dx.detox_step(Gd, 3, 5, spec["B"], "trimmed_mean", f=1, materialise=False)
+    assert rel_l2(host(tm.out), ref_tm) <= TOL
+    assert np.abs(host(tm.out) - ref_tm).max() <= 1e-5 * np.abs(ref_tm).max()
     v = w.vanilla[0]
     ref_out, ref_sel, ref_scores = oracle.multikrum(G, v["f"], v["m"])
     out, sel, scores = dx.robust_multikrum(Gd, v["f"], v["m"])
@@ -172,7 +181,10 @@ def test_full_size_heavy_tailed_shape(dx):
     med = dx.detox_step(Gd, 3, 5, 5, "coord_median", materialise=False)
     assert host(med.winner).tolist() == ref_w.tolist()
     got = host(med.out)
-    for a, b in wins:
+    # also the columns of workgroup 0's trips around the points where the one-pass kernel changes
+    # where it keeps its results (LDS up to trip 6, registers up to trip 18, stored at once after)
+    trips = [(t << 20, (t << 20) + 4096) for t in (5, 6, 7, 8, 12, 17, 18, 19, 20, 23)]
+    for a, b in wins + trips:
         sub = np.ascontiguousarray(G[:, a:b])
         ref = oracle.detox_step(sub, 3, 5, "coord_median")[0]
         assert got[a:b].tobytes() == ref.tobytes()
