@@ -156,6 +156,29 @@ def test_full_size_resnet18_shape(dx):
     assert rel_l2(host(out), ref_out) <= TOL
 
 
+@pytest.mark.parametrize("r,groups,B,d", [(3, 3, 3, 1_048_577), (3, 3, 3, 7_340_033), (2, 4, 4, 8_400_001),
+                                          (5, 5, 5, 3_500_003), (7, 2, 2, 9_000_001)])
+def test_one_pass_median_and_trimmed_mean_at_middle_sizes(dx, r, groups, B, d):
+    """The one-pass kernels keep a workgroup's results in LDS for its first seven trips and in
+    registers for up to twelve more: sizes of 2 to 9 trips per workgroup on a 256-CU chip, with
+    a ragged last chunk, every column against the oracle (one group without a majority, so the
+    repair pass runs as well)."""
+    rng = np.random.default_rng(d)
+    base = (rng.standard_normal((groups, d)) * 0.05).astype(np.float32)
+    G = np.repeat(base, r, axis=0)
+    G[0] = 3.0                                       # a Byzantine row inside group 0
+    if r >= 3:
+        G[r + 1, d // 3:] += 1.0; G[r + 2, : d // 3] -= 1.0   # group 1: no vector majority
+    Gd = dev_matrix(G)
+    ref, ref_w, _ = oracle.detox_step(G, r, B, "coord_median")
+    got = dx.detox_step(Gd, r, 1, B, "coord_median", materialise=False)
+    assert host(got.winner).tolist() == ref_w.tolist()
+    assert host(got.out).tobytes() == ref.tobytes()
+    ref = oracle.detox_step(G, r, B, "trimmed_mean", f=(B - 1) // 2)[0]
+    got = dx.detox_step(Gd, r, 1, B, "trimmed_mean", f=(B - 1) // 2, materialise=False)
+    assert np.abs(host(got.out) - ref).max() <= 1e-5 * np.abs(ref).max()
+
+
 def _sample_columns(d, width=4096, pieces=6, seed=0):
     """Column windows spread over [0, d), including both ends (the ragged tail too) and, where
     d reaches that far, the column at which the averaging kernels start their second launch on
