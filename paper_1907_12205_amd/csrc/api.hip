@@ -158,8 +158,13 @@ int bulyan_impl(const RowSet &rs, int f, float *out, int32_t *selected, void *ws
     AggWs a = carve_aggregator(ws, rs.count, rs.d);
     const int theta = rs.count - 2 * f, beta = theta - 2 * f;
     hipError_t e = gram_for(rs, a, fg, s);
-    if (e == hipSuccess) e = launch_bulyan_select(a.Gm, rs.count, f, a.sc, selected, s);
-    if (e == hipSuccess) e = launch_bulyan_trim(rs, selected, a.trim_rows, theta, beta, out, s);
+    // rows read through an index table: the selection kernel leaves the table entries of the
+    // selected rows for the trim (one small launch less)
+    const bool through_table = !rs.means() && rs.index != nullptr;
+    if (e == hipSuccess)
+        e = launch_bulyan_select(a.Gm, rs.count, f, a.sc, selected, through_table ? rs.index : nullptr,
+                                 through_table ? a.trim_rows : nullptr, s);
+    if (e == hipSuccess) e = launch_bulyan_trim(rs, selected, a.trim_rows, through_table, theta, beta, out, s);
     return status_of(e);
 }
 

@@ -220,8 +220,11 @@ hipError_t launch_sqdist_from_gram(const double *Gm, int64_t count, double *D, h
 hipError_t launch_multikrum_select(const double *Gm, int64_t count, int f, int m,
                                    const SelectScratch &sc, int32_t *selected, double *scores_out,
                                    hipStream_t s);
+//   table, composed (dev, may both be null): composed[i] = table[selected[i]] is written as well
+//   (the rows of the matrix behind the selected logical rows, for the trim that follows).
 hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const SelectScratch &sc,
-                                int32_t *selected, hipStream_t s);
+                                int32_t *selected, const int32_t *table, int32_t *composed,
+                                hipStream_t s);
 hipError_t launch_weiszfeld(const double *Gm, int64_t count, int iters, double eps,
                             double *weights, hipStream_t s);
 // out[b] = table[pick[b]] for b < n (e.g. winner[vote_perm[b]]: the row table of the votes taken
@@ -239,9 +242,10 @@ hipError_t launch_coord_median(const RowSet &rs, float *out, const int *run_if, 
 // Coordinate-wise trimmed mean of all logical rows: the g smallest and g largest values dropped.
 hipError_t launch_trimmed_mean(const RowSet &rs, int g, float *out, const int *run_if, hipStream_t s);
 // Per coordinate: median of the theta listed logical rows, mean of the beta values closest to it.
-//   scratch: dev, theta int32 (used when rs carries an index table).
-hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, int theta,
-                              int beta, float *out, hipStream_t s);
+//   scratch: dev, theta int32 (used when rs carries an index table); composed: it already holds
+//   index[rows[i]] (launch_bulyan_select wrote it).
+hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, bool composed,
+                              int theta, int beta, float *out, hipStream_t s);
 
 // ---- signvote.hip ----------------------------------------------------------
 // Two levels of coordinate-wise majority vote over bit-packed sign rows read through winner[].

@@ -119,7 +119,9 @@ __device__ inline int nth_set_bit(unsigned long long lo, unsigned long long hi, 
 // values up to the nb-th set bit, taken in ascending position (= ascending distance).
 __global__ __launch_bounds__(kRowThreads) void bulyan_select_kernel(int count, int f,
                                                                     SelectScratch sc,
-                                                                    int32_t *selected)
+                                                                    int32_t *selected,
+                                                                    const int32_t *table,
+                                                                    int32_t *composed)
 {
     extern __shared__ double lds[];
     const int nbrs = count - 1;
@@ -210,7 +212,10 @@ __global__ __launch_bounds__(kRowThreads) void bulyan_select_kernel(int count, i
         if (threadIdx.x == 0) picked[it] = best;
     }
     __syncthreads();
-    for (int it = threadIdx.x; it < theta; it += blockDim.x) selected[it] = picked[it];
+    for (int it = threadIdx.x; it < theta; it += blockDim.x) {
+        selected[it] = picked[it];
+        if (table != nullptr) composed[it] = table[picked[it]];   // picked rows lie in [0, count)
+    }
 }
 
 constexpr int kWzLanesPerRow = 4;                          // lanes that share a row of the matrix
@@ -557,7 +562,8 @@ hipError_t prepare_selection_kernels()
 }
 
 hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const SelectScratch &sc,
-                                int32_t *selected, hipStream_t s)
+                                int32_t *selected, const int32_t *table, int32_t *composed,
+                                hipStream_t s)
 {
     {
         TraceScope t("sort_rows", s);
@@ -569,7 +575,8 @@ hipError_t launch_bulyan_select(const double *Gm, int64_t count, int f, const Se
     e = prepare_selection_kernels();   // more than 64 KB of LDS has to be asked for (once per device)
     if (e != hipSuccess) return e;
     TraceScope t("bulyan_select", s);
-    bulyan_select_kernel<<<1, kRowThreads, lds, s>>>((int)count, f, sc, selected);
+    bulyan_select_kernel<<<1, kRowThreads, lds, s>>>((int)count, f, sc, selected,
+                                                     composed != nullptr ? table : nullptr, composed);
     return hipGetLastError();
 }
 

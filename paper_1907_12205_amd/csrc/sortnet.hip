@@ -284,16 +284,19 @@ const int32_t *identity_table()
 
 // rows: logical rows to use (dev, n entries; null = 0..n-1).  scratch: dev, n int32, needed only
 // when both a row list and an index table are present (their composition is written there).
-hipError_t order_stat(int mode, int n, RowSet rs, const int32_t *rows, int32_t *scratch, int beta,
-                      float *out, const int *run_if, hipStream_t s)
+//   composed: scratch already holds index[rows[i]].
+hipError_t order_stat(int mode, int n, RowSet rs, const int32_t *rows, int32_t *scratch, bool composed,
+                      int beta, float *out, const int *run_if, hipStream_t s)
 {
     if (n < 1 || n > kMaxCount) return hipErrorInvalidValue;
     const int32_t *phys = rows;
     if (!rs.means() && rs.index) {
         if (rows) {
             if (!scratch) return hipErrorInvalidValue;
-            hipError_t e = launch_compose_index(rs.index, rs.count, rows, n, scratch, s);   // index[rows[i]]
-            if (e != hipSuccess) return e;
+            if (!composed) {
+                hipError_t e = launch_compose_index(rs.index, rs.count, rows, n, scratch, s);   // index[rows[i]]
+                if (e != hipSuccess) return e;
+            }
             phys = scratch;
         } else {
             phys = rs.index;
@@ -320,18 +323,18 @@ hipError_t order_stat(int mode, int n, RowSet rs, const int32_t *rows, int32_t *
 
 hipError_t launch_coord_median(const RowSet &rs, float *out, const int *run_if, hipStream_t s)
 {
-    return order_stat(kStatMedian, rs.count, rs, nullptr, nullptr, 0, out, run_if, s);
+    return order_stat(kStatMedian, rs.count, rs, nullptr, nullptr, false, 0, out, run_if, s);
 }
 
-hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, int theta,
-                              int beta, float *out, hipStream_t s)
+hipError_t launch_bulyan_trim(const RowSet &rs, const int32_t *rows, int32_t *scratch, bool composed,
+                              int theta, int beta, float *out, hipStream_t s)
 {
-    return order_stat(kStatBulyanTrim, theta, rs, rows, scratch, beta, out, nullptr, s);
+    return order_stat(kStatBulyanTrim, theta, rs, rows, scratch, composed, beta, out, nullptr, s);
 }
 
 hipError_t launch_trimmed_mean(const RowSet &rs, int g, float *out, const int *run_if, hipStream_t s)
 {
-    return order_stat(g == rs.count / 4 ? kStatTrimmedQuarter : kStatTrimmedMean, rs.count, rs, nullptr, nullptr, g,
+    return order_stat(g == rs.count / 4 ? kStatTrimmedQuarter : kStatTrimmedMean, rs.count, rs, nullptr, nullptr, false, g,
                       out, run_if, s);
 }
 
