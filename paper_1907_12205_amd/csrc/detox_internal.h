@@ -16,6 +16,7 @@ constexpr int kFusedMaxGrid = 2048;    // its largest grid (sizes the per-workgr
 constexpr int kPassGramMaxVotes = 16;  // votes whose Gram matrix the filter pass can form on the side
 constexpr int kMeansOnTheFlyMaxRows = 32;  // block means later kernels re-form from the winner rows instead of reading them
 constexpr int kPassGramMaxWaves = 4096;  // wavefront tiles it may write (sizes the workspace)
+constexpr int kShortRowsMaxD = 1024;   // up to here the Gram matrix of more than 8 rows is formed in fp64 (gram.hip)
 constexpr int kRowParMaxD = 2048;      // widest rows the row-parallel filter / block mean take
 constexpr int kManyGeomedianMaxD = 128;       // widest rows of the streaming Weiszfeld kernels
 constexpr int kManyGeomedianMaxParts = 1024;  // most workgroups (partial sums) of one of its launches

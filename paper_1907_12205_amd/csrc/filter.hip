@@ -795,8 +795,9 @@ hipError_t launch_filter(FilterParams p, FilterWant want, const SmallSelect *tai
         if (fused && p.B <= 8 && want == FilterWant::kMedian) mode = kMedian, nb = (int)p.B;
         if (fused && p.B <= 8 && want == FilterWant::kTrimmed) mode = kTrimmedMean, nb = (int)p.B;
         // 9 .. 16 votes, each its own block and none wanted in memory: their Gram matrix on the side
+        // (not for short rows: their Gram matrix is formed in fp64 afterwards, see gram.hip)
         if (fused && want == FilterWant::kGram && p.B == p.n_votes && p.B > 8 && p.B <= kPassGramMaxVotes &&
-            p.Zhat == nullptr && p.vote_gram_partials != nullptr)
+            p.Zhat == nullptr && p.vote_gram_partials != nullptr && p.d > kShortRowsMaxD)
             mode = kVotesGram;
         // packed signs: both vote levels in the pass (else: votes only, the caller votes afterwards)
         if (want == FilterWant::kSignVote)

@@ -3,7 +3,8 @@
 // Section 4, "Improved speed") and of the Gram-space Weiszfeld iteration.
 //
 //   count <= 8 : fp64 FMAs on the vector ALUs, all pairs held in registers per thread.
-//   count  > 8 : bf16 MFMA 16x16x32 tiles on fp32 operands cut into three bf16 pieces (upper
+//   count  > 8 : (rows longer than kShortRowsMaxD; shorter ones: fp64, one workgroup per pair)
+//                bf16 MFMA 16x16x32 tiles on fp32 operands cut into three bf16 pieces (upper
 //                triangle of the tile grid), one accumulator set per wavefront over a strided
 //                share of the columns, added up within the workgroup at the end.
 // Either way every workgroup writes its partial sums to the workspace and a second
@@ -648,6 +649,53 @@ __global__ void gram_mfma_reduce2_kernel(const double *slices, int T, int count,
     Gm[col * count + row] = s;
 }
 
+// Short rows (d <= kShortRowsMaxD), more than 8 of them: one workgroup per pair (a <= b), fp64
+// products and sums in a fixed order.  With so few columns the matrix-core kernels would have
+// nothing to win, and their fp32 entries can matter: in a handful of dimensions a Weiszfeld
+// iterate may all but coincide with one of the rows, and its distance to that row is then the
+// small difference of Gram entries.
+template <bool MEANS>
+__global__ __launch_bounds__(kBlock) void gram_pairs_f64_kernel(RowSet rs, double *Gm, const int *run_if)
+{
+    if (run_if && *run_if == 0) return;   // uniform
+    const int count = rs.count;
+    int a = 0, rest = blockIdx.x;
+    while (rest >= count - a) {
+        rest -= count - a;
+        ++a;
+    }
+    const int b = a + rest;
+    double s = 0.0;
+    for (int64_t c = threadIdx.x; c < rs.d; c += kBlock) {
+        float xa[1], xb[1];
+        row_load<MEANS, 1>(rs, a, c, 1, xa);
+        row_load<MEANS, 1>(rs, b, c, 1, xb);
+        s = fma((double)xa[0], (double)xb[0], s);
+    }
+    __shared__ double red[kBlock / kWave];
+    s = wave_sum_fixed(s);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kBlock / kWave; ++w) t += red[w];
+        Gm[a * count + b] = t;
+        Gm[b * count + a] = t;
+    }
+}
+
+hipError_t launch_pairs_f64(const RowSet &rs, double *Gm, const int *run_if, hipStream_t s)
+{
+    TraceScope t(run_if ? "gram_f64_pairs_if_redo" : "gram_f64_pairs", s);
+    const unsigned pairs = (unsigned)(rs.count * (rs.count + 1) / 2);
+    if (rs.means())
+        gram_pairs_f64_kernel<true><<<pairs, kBlock, 0, s>>>(rs, Gm, run_if);
+    else
+        gram_pairs_f64_kernel<false><<<pairs, kBlock, 0, s>>>(rs, Gm, run_if);
+    return hipGetLastError();
+}
+
 template <int C>
 hipError_t launch_small(const RowSet &rs, double *partials, int grid, const int *run_if,
                         const SmallSelect &tail, unsigned *arrived, hipStream_t s)
@@ -735,6 +783,7 @@ hipError_t gram_mfma(const RowSet &rs, void *partials, const int *run_if, const 
 {
     const int T = (rs.count + 15) / 16;
     if (T < 1 || T > 8) return hipErrorInvalidValue;
+    if (rs.d <= kShortRowsMaxD && alt == nullptr) return launch_pairs_f64(rs, Gm, run_if, s);
     const MfmaWs w = carve_mfma(partials, T);
     const bool direct = rows_16_byte_aligned(rs.base, rs.ld) && !rs.means();
     int grid = num_compute_units() * (direct ? direct_blocks_per_cu(T) : staged_blocks_per_cu(T));

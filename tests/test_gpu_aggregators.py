@@ -56,14 +56,38 @@ def test_pairwise_sqdist(dx, count):
 
 
 @pytest.mark.parametrize("count", [9, 33, 105, 128])
-@pytest.mark.parametrize("d", [1, 3, 31, 32, 33, 63, 64, 65, 97])
+@pytest.mark.parametrize("d", [1, 3, 31, 32, 33, 63, 64, 65, 97, 1000, 1024])
 def test_pairwise_sqdist_on_very_short_rows(dx, count, d):
-    """Fewer columns than one tile of the matrix-core kernels, and just around one and two tiles."""
+    """Up to 1024 columns the Gram matrix of more than 8 rows is formed in fp64."""
+    X = workloads.distinct_rows(count + d, count, d, sigma=0.03, mean=0.5)
+    ref = oracle.pairwise_sqdist(X)
+    for ld in (None, (d + 63) // 64 * 64, d + 1):
+        D = host(dx.robust_pairwise_sqdist(dev_matrix(X, ld, 0)))
+        assert (D == D.T).all() and (np.diag(D) == 0).all()
+        assert np.abs(D - ref).max() <= 1e-11 * ref.max() + 1e-300, (count, d, ld)
+
+
+@pytest.mark.parametrize("count", [9, 33, 105, 128])
+@pytest.mark.parametrize("d", [1025, 1031, 1055, 1056, 1057, 1087, 1088, 1089, 1121])
+def test_pairwise_sqdist_on_the_shortest_rows_of_the_matrix_core_kernels(dx, count, d):
+    """Just above 1024 columns: few tiles per wavefront, ragged last tiles of every length class."""
     X = workloads.distinct_rows(count + d, count, d, sigma=0.03, mean=0.5)
     ref = oracle.pairwise_sqdist(X)
     for ld in (None, (d + 63) // 64 * 64):
         D = host(dx.robust_pairwise_sqdist(dev_matrix(X, ld, 0)))
         assert np.abs(D - ref).max() <= 2e-6 * ref.max() + 1e-300, (count, d, ld)
+
+
+def test_geomedian_in_one_dimension_when_an_iterate_nearly_hits_a_row(dx):
+    """Nine values on a line for which the second Weiszfeld iterate lands 2e-6 from one of them
+    (the values' spread is 0.06): the weight of that value is the reciprocal of a distance that
+    is the small difference of Gram entries, which the fp64 Gram matrix of short rows resolves."""
+    z = np.array([0.0186256, -0.00200855, -0.04061466, -0.01330629, 0.0087603, 0.00847142,
+                  0.00571794, 0.00715502, 0.01970924], dtype=np.float32).reshape(9, 1)
+    for iters in (2, 3, 7, 50):
+        ref = oracle.geomedian(z, iters=iters, eps=1e-8)
+        got = host(dx.robust_geomedian(dev_matrix(z), iters=iters, eps=1e-8))
+        assert abs(float(got[0]) - float(ref[0])) <= 1e-6 * abs(float(ref[0])), (iters, got, ref)
 
 
 @pytest.mark.parametrize("count", [6, 15, 45, 105])
