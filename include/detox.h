@@ -140,7 +140,10 @@ int detox_filter_block_mean(const float *G, int64_t n, int64_t d, int64_t ld, in
 /* Pairwise squared distances D[a][b] = ||x_a - x_b||^2 (the O(p^2 d) term of
  * Section 4, "Improved speed").  Computed as G_aa + G_bb - 2 G_ab from a
  * split-d Gram matrix whose partial sums are added in fp64; bit-identical rows
- * give exactly 0 and exactly equal distances to every third row.
+ * give exactly 0 and exactly equal distances to every third row.  Up to 8 rows,
+ * and for rows of at most 1024 columns, the products are fp64 as well; beyond
+ * that they are fp32 products of the rows less one of them (distances do not
+ * change under a common shift): distances good to about 1e-7 of the largest.
  *   X          dev, count x d (ld), 1 <= count <= DETOX_MAX_COUNT
  *   D          dev, count x count doubles, out (symmetric, zero diagonal)    */
 int robust_pairwise_sqdist(const float *X, int64_t count, int64_t d, int64_t ld, double *D,
