@@ -390,7 +390,7 @@ def main():
             ws_h = torch.empty(max(dx.robust_blocks_workspace_bytes(n, d, r, 1), dx.robust_blocks_workspace_bytes(n, d, r, 2)),
                                dtype=torch.uint8, device=G.device)
             timed(f"DETOX A0=Multi-Krum(f=2,m=3) on {groups // 2}+{groups - groups // 2} votes, A1=mean",
-                  lambda: dx.detox_step_robust_blocks(G, r, 2, "multikrum", 2, 3, out=out_o, ws=ws_h), n + 2 * 3 + 2 + 2 + 1)
+                  lambda: dx.detox_step_robust_blocks(G, r, 2, "multikrum", 2, 3, out=out_o, ws=ws_h), n + 2 * 3 + 2 + 1)
             timed(f"DETOX A0=Bulyan(f=2) on all {groups} votes",
                   lambda: dx.detox_step_robust_blocks(G, r, 1, "bulyan", 2, out=out_o, ws=ws_h), n + (groups - 4) + 1)
         timed(f"vanilla coord-median over {n} rows", lambda: dx.robust_coord_median(G, out=out_o), n + 1)

@@ -612,6 +612,11 @@ int detox_step_robust_blocks(const float *G, int64_t n, int64_t d, int64_t ld, i
     if (select_at_once) {
         e = launch_cut_multikrum(all.Gm, (int)groups, (int)B, f, m, all.sc.scores, selected, s);
         if (e != hipSuccess) return status_of(e);
+        if (B > 1) {
+            // the averages of all groups and their mean in one pass over the selected votes
+            const RowSet votes{G, d, ld, (int)n, (int)groups, table, nullptr, nullptr, 0};
+            return status_of(launch_blocks_mean(votes, (int)B, selected, f, m, block_out, ldb, out, s));
+        }
     }
     for (int64_t b = 0; b < B; ++b) {
         const int64_t lo = (b * groups) / B, hi = ((b + 1) * groups) / B;

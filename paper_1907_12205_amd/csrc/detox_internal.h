@@ -234,6 +234,12 @@ hipError_t launch_compose_index(const int32_t *table, int table_len, const int32
                                 int32_t *out, hipStream_t s);
 // out[c] = fp32( sum_i (double) row[rows[i]][c] / m ), logical rows listed in device memory.
 hipError_t launch_rows_mean(const RowSet &rs, const int32_t *rows, int m, float *out, hipStream_t s);
+// The logical rows of rs cut into B runs (run b = rows b*count/B .. (b+1)*count/B - 1), rows[] the
+// m_b selected rows of every run (positions within the run, written at the run's offset; m_b = m,
+// or the run's length less f if m < 0):  block_out[b] = fp32( sum_i (double) row_i / m_b ) and
+// out = fp32( sum_b (double) block_out[b] / B ), in one pass.
+hipError_t launch_blocks_mean(const RowSet &rs, int B, const int32_t *rows, int f, int m, float *block_out,
+                              int64_t ldb, float *out, hipStream_t s);
 // out[c] = fp32( sum_j weights[j] * (double) row[j][c] ) over all logical rows.
 hipError_t launch_weighted_sum(const RowSet &rs, const double *weights, float *out, hipStream_t s);
 

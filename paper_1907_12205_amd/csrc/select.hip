@@ -441,6 +441,38 @@ __global__ __launch_bounds__(kBlock, kBurstWavesPerSimd) void combine_rows_burst
     }
 }
 
+// The averages of a step whose vote groups each select some of their votes and whose second level is
+// the mean: every run's average goes to block_out and, rounded to fp32 as it is stored, into the
+// average of the runs.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void blocks_mean_kernel(RowSet rs, int B, const int32_t *rows, int f, int m,
+                                                             float *block_out, int64_t ldb, float *out)
+{
+    const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+    const int64_t left = rs.d - col;
+    if (left <= 0) return;
+    const int valid = left >= VEC ? VEC : (int)left;
+    const bool full = ((int64_t)blockIdx.x + 1) * kBlock * VEC <= rs.d;   // uniform
+    double total[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) total[i] = 0.0;
+    for (int b = 0; b < B; ++b) {
+        const int lo = (int)(((int64_t)b * rs.count) / B), hi = (int)(((int64_t)(b + 1) * rs.count) / B);
+        RowSet run = rs;
+        run.index = rs.index + lo;
+        run.count = hi - lo;
+        float z[VEC];
+        combine_columns<VEC, false, false>(run, rows + lo, nullptr, m < 0 ? hi - lo - f : m, col, valid, full, z);
+        store_floats<VEC>(block_out + b * ldb + col, valid, z);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) total[i] += (double)z[i];
+    }
+    float o[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[i] = (float)(total[i] / (double)B);
+    store_floats<VEC>(out + col, valid, o);
+}
+
 template <bool WEIGHTED, bool MEANS, int BURST>
 hipError_t launch_combine_burst(const RowSet &rs, const int32_t *rows, const double *weights, int m,
                                 float *out, int64_t chunks, int64_t resident, hipStream_t s)
@@ -600,6 +632,18 @@ hipError_t launch_rows_mean(const RowSet &rs, const int32_t *rows, int m, float 
 hipError_t launch_weighted_sum(const RowSet &rs, const double *weights, float *out, hipStream_t s)
 {
     return launch_combine<true>(rs, nullptr, weights, rs.count, out, s);
+}
+
+hipError_t launch_blocks_mean(const RowSet &rs, int B, const int32_t *rows, int f, int m, float *block_out,
+                              int64_t ldb, float *out, hipStream_t s)
+{
+    if (rs.means() || rs.index == nullptr || rows == nullptr || block_out == nullptr || B < 1 || B > rs.count)
+        return hipErrorInvalidValue;
+    constexpr int vec = 4;   // columns per lane
+    const int64_t chunks = (rs.d + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
+    TraceScope t("blocks_mean", s);
+    blocks_mean_kernel<vec><<<(unsigned)chunks, kBlock, 0, s>>>(rs, B, rows, f, m, block_out, ldb, out);
+    return hipGetLastError();
 }
 
 }  // namespace detox
