@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kBlock, fused_waves_per_simd(R, NB, MODE)) void fus
     // took 0.36).  The first kHoldLds trips of a workgroup wait in LDS, the next kHoldReg in
     // registers; only what comes after that is stored at once.
     constexpr bool HOLD = MODE == kMedian || MODE == kTrimmedMean;
-        constexpr int kHoldLds = 7, kHoldReg = hold_registers(R, NB, MODE);
+    constexpr int kHoldLds = 7, kHoldReg = hold_registers(R, NB, MODE);
     __shared__ __attribute__((aligned(16))) float parked[HOLD ? kHoldLds * kBlock * VEC : 1];
     [[maybe_unused]] float held[kHoldReg > 0 ? kHoldReg : 1][VEC] = {};
     for (int j = threadIdx.x; j < p.n_votes; j += kBlock) sbits[j] = 0ull;
