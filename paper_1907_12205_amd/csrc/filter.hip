@@ -485,18 +485,24 @@ __global__ __launch_bounds__(kBlock, fused_waves_per_simd(R, NB, MODE)) void fus
         if (bits) atomicOr(&sbits[j0], bits);
     }
     __syncthreads();
+    // (n_votes <= blockDim.x: at most one group per thread; its store waits until after the barrier)
     int bad = 0;
-    for (int j = threadIdx.x; j < n_votes; j += blockDim.x) {
-        const int32_t win = winner_from_bits(sbits[j], group_rows, r, j);
-        winner[j] = win;
-        bad |= win < 0;
+    int32_t win = 0;
+    const bool has_group = (int)threadIdx.x < n_votes;
+    if (has_group) {
+        win = winner_from_bits(sbits[threadIdx.x], group_rows, r, threadIdx.x);
+        bad = win < 0;
     }
     bad = __syncthreads_or(bad);
-    if (threadIdx.x == 0) redo[0] = bad ? 1 : 0, redo[1] = 0;   // [1]: arrival counter of the redo kernel
-    if (bad || q.gram_partials == nullptr) return;   // uniform
+    const bool more = !bad && q.gram_partials != nullptr;   // uniform
     __shared__ double Gl[kSmallCount * kSmallCount];
-    small_gram_reduce(q, gv, Gl);
-    if (q.krum_m > 0) small_multikrum(q, Gl);
+    if (more) {
+        small_gram_reduce(q, gv, Gl);
+        if (q.krum_m > 0) small_multikrum(q, Gl);
+        small_gram_store(q, Gl);
+    }
+    if (has_group) winner[threadIdx.x] = win;
+    if (threadIdx.x == 0) redo[0] = bad ? 1 : 0, redo[1] = 0;   // [1]: arrival counter of the redo kernel
 }
 
 // ---------------------------------------------------------------------------------------

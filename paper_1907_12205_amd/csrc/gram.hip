@@ -109,6 +109,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(RowSet rs, double *p
     tail.count = C;
     small_gram_reduce<kBlock>(tail, small_gram_load<kBlock>(tail), Gl);
     if (tail.krum_m > 0) small_multikrum(tail, Gl);
+    small_gram_store(tail, Gl);
     if (threadIdx.x == 0) *arrived = 0u;
 }
 

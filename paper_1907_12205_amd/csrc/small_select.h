@@ -43,8 +43,10 @@ __device__ inline double small_gram_load(const SmallSelect &q)
     return s;
 }
 
-// Second half: the slice sums of every pair are added in slice order; Gm goes to LDS and to
-// global memory.  Ends with a barrier.
+// Second half: the slice sums of every pair are added in slice order; Gm goes to LDS.  Ends with a
+// barrier.  Nothing is stored to memory here or in small_multikrum before their last barrier: a
+// barrier waits for the stores issued before it, a microsecond each time on a lone workgroup.
+// small_gram_store writes the matrix out and belongs after the last barrier of the kernel.
 template <int THREADS = kPostThreads>
 __device__ inline void small_gram_reduce(const SmallSelect &q, double mine,
                                          double (&Gl)[kSmallCount * kSmallCount])
@@ -65,10 +67,13 @@ __device__ inline void small_gram_reduce(const SmallSelect &q, double mine,
         const int b = a + rest;
         Gl[a * q.count + b] = s;
         Gl[b * q.count + a] = s;
-        q.Gm[a * q.count + b] = s;
-        q.Gm[b * q.count + a] = s;
     }
     __syncthreads();
+}
+
+__device__ inline void small_gram_store(const SmallSelect &q, const double (&Gl)[kSmallCount * kSmallCount])
+{
+    if ((int)threadIdx.x < q.count * q.count) q.Gm[threadIdx.x] = Gl[threadIdx.x];
 }
 
 // Multi-Krum on a Gram matrix held in LDS, count <= 8, by counting ranks (no data-dependent
@@ -105,7 +110,6 @@ __device__ inline void small_multikrum(const SmallSelect &q, const double (&Gl)[
         double s = 0.0;
         for (int i = 0; i < count - q.krum_f - 2; ++i) s += sorted[threadIdx.x][i];
         score[threadIdx.x] = s;
-        q.scores[threadIdx.x] = s;
     }
     __syncthreads();
     if (threadIdx.x < count) {
@@ -118,6 +122,7 @@ __device__ inline void small_multikrum(const SmallSelect &q, const double (&Gl)[
             if (kc < ka || (kc == ka && c < me)) ++rank;
         }
         if (rank < q.krum_m) q.selected[rank] = me;
+        q.scores[me] = sa;
     }
 }
 
