@@ -470,18 +470,31 @@ __global__ __launch_bounds__(kBlock, fused_waves_per_simd(R, NB, MODE)) void fus
     int32_t *winner, int *redo, SmallSelect q)
 {
     __shared__ unsigned long long sbits[kFusedMaxVotes];
-    const double gv = small_gram_load(q);   // issued first: overlaps the vote bookkeeping below
-    for (int j = threadIdx.x; j < n_votes; j += blockDim.x) sbits[j] = 0ull;
-    __syncthreads();
     // thread (j, slice): group j = tid % pad, every slices-th workgroup starting at tid / pad
     int pad = 1;
     while (pad < n_votes) pad *= 2;            // n_votes <= blockDim.x, so pad <= blockDim.x
     const int slices = (int)blockDim.x / pad;
     const int j0 = threadIdx.x % pad, slice = threadIdx.x / pad;
-    if (j0 < n_votes) {
+    // All loads of this kernel are issued before the first of them is waited for, sixteen slots at
+    // a time: it starts right after a kernel boundary, where every dependent trip to memory costs
+    // microseconds.  (A slot beyond the last re-reads a valid one and is left out.)
+    const bool has_slot = j0 < n_votes && slice < blocks;
+    const int jj = j0 < n_votes ? j0 : 0;
+    unsigned long long first[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int w = slice + u * slices;
+        first[u] = partials[(int64_t)(w < blocks ? w : (slice < blocks ? slice : 0)) * n_votes + jj];
+    }
+    const double gv = small_gram_load(q);   // its loads join those above
+    for (int j = threadIdx.x; j < n_votes; j += blockDim.x) sbits[j] = 0ull;
+    __syncthreads();
+    if (has_slot) {
         unsigned long long bits = 0ull;
-#pragma unroll 8
-        for (int w = slice; w < blocks; w += slices) bits |= partials[(int64_t)w * n_votes + j0];
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (slice + u * slices < blocks) bits |= first[u];
+        for (int w = slice + 16 * slices; w < blocks; w += slices) bits |= partials[(int64_t)w * n_votes + j0];
         if (bits) atomicOr(&sbits[j0], bits);
     }
     __syncthreads();

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(RowSet rs, double *p
         double s = 0.0;
 #pragma unroll
         for (int w = 0; w < kBlock / kWave; ++w) s += red[w][threadIdx.x];
-        partials[(int64_t)blockIdx.x * NP + threadIdx.x] = s;
+        partials[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = s;   // [pair][slot]: coalesced for the readers
     }
     if (arrived == nullptr) return;   // uniform
     // The workgroup that finishes last adds up everybody's partials and, if asked, goes on to
@@ -104,8 +104,8 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(RowSet rs, double *p
     __shared__ double Gl[kSmallCount * kSmallCount];
     tail.gram_partials = partials;
     tail.gram_blocks = (int)gridDim.x;
-    tail.slot_stride = NP;
-    tail.pair_stride = 1;
+    tail.slot_stride = 1;
+    tail.pair_stride = (int)gridDim.x;
     tail.count = C;
     small_gram_reduce<kBlock>(tail, small_gram_load<kBlock>(tail), Gl);
     if (tail.krum_m > 0) small_multikrum(tail, Gl);
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_reduce_kernel(const double 
     const int np = count * (count + 1) / 2;
     const int pair = blockIdx.x;
     double s = 0.0;
-    for (int w = threadIdx.x; w < blocks; w += kBlock) s += partials[(int64_t)w * np + pair];
+    for (int w = threadIdx.x; w < blocks; w += kBlock) s += partials[(int64_t)pair * blocks + w];
     __shared__ double red[kBlock];
     red[threadIdx.x] = s;
     __syncthreads();

@@ -22,9 +22,12 @@ struct SmallSelect {
     int32_t *selected;             // dev, krum_m
 };
 
-// Gm[a][b] (LDS and global) = sum over the workgroup slots, in a fixed order, by a workgroup of
-// THREADS threads (blockDim.x == THREADS).
-// First half (no barrier): thread (pair p, slice k) adds the slots of its slice in slot order.
+// Gm[a][b] = sum over the workgroup slots, in a fixed order, by a workgroup of THREADS threads
+// (blockDim.x == THREADS).
+// First half (no barrier): thread (pair p, slice k) adds the slots k, k + slices, k + 2 slices, ..
+// in that order: neighbouring lanes read neighbouring slots, so with slot_stride = 1 (the layout
+// the filter pass writes) a load instruction touches a few cache lines, not one per lane -- one
+// compute unit does all of this, and its cache takes a cycle per line and instruction.
 // Can be issued early so that the loads overlap other work.
 template <int THREADS = kPostThreads>
 __device__ inline double small_gram_load(const SmallSelect &q)
@@ -34,12 +37,20 @@ __device__ inline double small_gram_load(const SmallSelect &q)
     const int slices = THREADS / np;
     const int p = threadIdx.x / slices, k = threadIdx.x % slices;
     if (p >= np) return 0.0;
-    const int per = (q.gram_blocks + slices - 1) / slices;
-    const int w0 = k * per, w1 = w0 + per < q.gram_blocks ? w0 + per : q.gram_blocks;
+    // sixteen loads in flight (a slot beyond the last re-reads the first and is left out):
+    // right after a kernel boundary every dependent trip to memory costs microseconds
     double s = 0.0;
-#pragma unroll 8
-    for (int w = w0; w < w1; ++w)
-        s += q.gram_partials[(int64_t)w * q.slot_stride + (int64_t)p * q.pair_stride];
+    for (int w = k; w < q.gram_blocks; w += 16 * slices) {
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int ww = w + u * slices < q.gram_blocks ? w + u * slices : k;
+            v[u] = q.gram_partials[(int64_t)ww * q.slot_stride + (int64_t)p * q.pair_stride];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (w + u * slices < q.gram_blocks) s += v[u];
+    }
     return s;
 }
 
