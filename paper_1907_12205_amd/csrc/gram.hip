@@ -609,7 +609,7 @@ __global__ __launch_bounds__(kWave * direct_waves_per_block(T),
 // Adds the tile sets in the workspace (one per workgroup, or per wavefront of the filter pass) in
 // fp64, in two fixed-order levels: kReduceSlices contiguous ranges of them are summed side by side (threads run along the tile elements, so every
 // load is coalesced), then the slice sums are added in slice order and scattered into the matrix.
-constexpr int kReduceSlices = 32;
+constexpr int kReduceSlices = 64;
 
 // alt (may be null): tiles written by the filter pass; they are the ones to add unless *redo.
 __global__ __launch_bounds__(kBlock) void gram_mfma_reduce1_kernel(const float *partials, int waves,
@@ -623,9 +623,16 @@ __global__ __launch_bounds__(kBlock) void gram_mfma_reduce1_kernel(const float *
     const int slice = blockIdx.y;
     const int per = (waves + kReduceSlices - 1) / kReduceSlices;
     const int w0 = slice * per, w1 = w0 + per < waves ? w0 + per : waves;
+    // sixteen loads in flight (a slot beyond the slice re-reads its last one and is left out)
     double s = 0.0;
-#pragma unroll 8
-    for (int w = w0; w < w1; ++w) s += (double)partials[(int64_t)w * elems + e];
+    for (int w = w0; w < w1; w += 16) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = partials[(int64_t)(w + u < w1 ? w + u : w1 - 1) * elems + e];
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (w + u < w1) s += (double)v[u];
+    }
     slices[(int64_t)slice * elems + e] = s;
 }
 
@@ -635,6 +642,7 @@ __global__ void gram_mfma_reduce2_kernel(const double *slices, int T, int count,
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= nt * 256) return;
     double s = 0.0;
+#pragma unroll 16
     for (int k = 0; k < kReduceSlices; ++k) s += slices[(int64_t)k * (nt * 256) + e];
     const int tile = e / 256, v = (e % 256) / 64, lane = e % 64;
     int ti = 0, rest = tile;
