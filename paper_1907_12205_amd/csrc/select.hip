@@ -179,6 +179,13 @@ __global__ __launch_bounds__(kRowThreads) void bulyan_select_kernel(int count, i
 #pragma unroll
                 for (int u = 0; u < 16; ++u) s += v[u];
             }
+            for (; i0 + 3 <= last; i0 += 4) {     // then fours, then what is left
+                double v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = mine[i0 + u];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) s += v[u];
+            }
             for (; i0 <= last; ++i0) s += mine[i0];
             key = s != s ? INFINITY : s;
         }
