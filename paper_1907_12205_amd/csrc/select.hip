@@ -405,7 +405,7 @@ __device__ __forceinline__ void burst_columns(const RowSet &rs, const int32_t *r
     }
 }
 
-constexpr int kBurstMinRows = 16;
+constexpr int kBurstMinRows = 13;
 constexpr int kBurstWavesPerSimd = 6;   // launch bound of the burst kernel = its workgroups per CU
 
 template <int VEC, bool WEIGHTED, bool MEANS, int BURST>
@@ -503,8 +503,8 @@ hipError_t launch_combine_as(const RowSet &rs, const int32_t *rows, const double
     const int64_t resident = (int64_t)num_compute_units() * kBurstWavesPerSimd;
     // Rows of the matrix read per output row.  Stores among the loads slow the loads down by about
     // a tenth however few they are, a closing stretch of stores costs its own time (10 us for
-    // d = 11.17M): holding the results back pays from about 16 rows on (3 of 5 block means = 9 rows:
-    // 0.078 ms chunk by chunk, 0.083 held back; 40 rows: 0.306 and 0.280).
+    // d = 11.17M): holding the results back pays from about 13 rows on (3 of 5 block means = 9 rows:
+    // 0.078 ms chunk by chunk, 0.083 held back; 15 rows: 0.1225 and 0.119; 40 rows: 0.306 and 0.280).
     const int64_t reads = MEANS ? ((int64_t)m * rs.n_votes + rs.count - 1) / rs.count : m;
     if (chunks <= resident || reads < kBurstMinRows) {
         combine_rows_kernel<4, WEIGHTED, MEANS><<<(unsigned)chunks, kBlock, 0, s>>>(rs, rows, weights, m, out);
