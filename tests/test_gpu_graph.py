@@ -52,6 +52,34 @@ def test_captured_step_replays_bit_for_bit(dx, aggregator, B, kw):
         assert torch.equal(buf.winner, want_w), f"replay {i}"
 
 
+def test_captured_average_of_many_rows_replays_bit_for_bit(dx):
+    """Vanilla Multi-Krum and the geometric median on 24 rows of 2.1M columns: their averaging
+    kernel holds results back in LDS and registers and may take several launches; captured and
+    replayed it must give the eager result."""
+    import torch
+    X = torch.from_numpy(workloads.distinct_rows(5, 24, 2_100_003, sigma=0.03)).cuda()
+    out = torch.empty(X.shape[1], device=X.device)
+    need = max(dx.workspace_bytes("multikrum", 24, X.shape[1]), dx.workspace_bytes("geomedian", 24, X.shape[1]))
+    ws = torch.empty(need, dtype=torch.uint8, device=X.device)
+    for call in (lambda: dx.robust_multikrum(X, 2, 20, out=out, ws=ws, with_scores=False),
+                 lambda: dx.robust_geomedian(X, iters=3, eps=1e-8, out=out, ws=ws)):
+        call()
+        torch.cuda.synchronize()
+        want = out.clone()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                call()
+        for i in range(3):
+            out.zero_()
+            scratch = torch.randn(1 << 16, device=X.device).sum()      # eager work between replays
+            graph.replay()
+            torch.cuda.synchronize()
+            assert scratch.isfinite()
+            assert torch.equal(out, want), f"replay {i}"
+
+
 def test_captured_step_sees_new_inputs(dx):
     """A replay reads the buffers as they are at replay time: changing a Byzantine row so that a
     group loses its majority switches the replay onto the repair path (the conditional kernels)."""
