@@ -52,25 +52,23 @@ __global__ __launch_bounds__(kRowThreads) void sort_rows_kernel(const double *Gm
     __shared__ double drow[kMaxCount];
     __shared__ double srow[kMaxCount];
     const int a = blockIdx.x, b = threadIdx.x;
+    // results go to memory after the last barrier (a barrier waits for the stores before it)
+    double x = 0.0;
+    int rank = 0;
     if (b < count) {
-        const double x = a <= b ? sq_dist(Gm, count, a, b) : sq_dist(Gm, count, b, a);
+        x = a <= b ? sq_dist(Gm, count, a, b) : sq_dist(Gm, count, b, a);
         drow[b] = x;
-        sc.D[a * count + b] = x;
     }
     __syncthreads();
     if (b < count && b != a) {
-        const double x = drow[b];
-        int rank = 0;
+        // no branch in the loop, so that it unrolls and its LDS loads are in flight together
+#pragma unroll 8
         for (int c = 0; c < count; ++c) {
-            if (c == a || c == b) continue;
             const double y = drow[c];
-            if (dbl_before(y, x) || (!dbl_before(x, y) && c < b)) ++rank;
+            const bool first = dbl_before(y, x) || (!dbl_before(x, y) && c < b);
+            rank += (c != a && c != b && first) ? 1 : 0;
         }
         srow[rank] = x;
-        // laid out as the Bulyan selection copies them into LDS: lists (count-1)|1 doubles apart
-        // (never more than count), and for every row b its position in the list of row a
-        sc.sorted[a * ((count - 1) | 1) + rank] = x;
-        sc.sorted_idx[a * count + b] = rank;
     }
     __syncthreads();
     if (nb > 0 && b == 0) {
@@ -78,6 +76,15 @@ __global__ __launch_bounds__(kRowThreads) void sort_rows_kernel(const double *Gm
         for (int i = 0; i < nb; ++i) s += srow[i];
         sc.scores[a] = s;
         if (scores_out) scores_out[a] = s;
+    }
+    if (b < count) {
+        sc.D[a * count + b] = x;
+        if (b != a) {
+            // laid out as the Bulyan selection copies them into LDS: lists (count-1)|1 doubles apart
+            // (never more than count), and for every row b its position in the list of row a
+            sc.sorted[a * ((count - 1) | 1) + rank] = x;
+            sc.sorted_idx[a * count + b] = rank;
+        }
     }
 }
 
@@ -91,8 +98,9 @@ __global__ __launch_bounds__(kRowThreads) void top_m_kernel(const double *scores
     __syncthreads();
     if (a >= count) return;
     int rank = 0;
-    for (int c = 0; c < count; ++c)
-        if (c != a && score_before(s[c], c, s[a], a)) ++rank;
+    const double mine = s[a];
+#pragma unroll 8
+    for (int c = 0; c < count; ++c) rank += (c != a && score_before(s[c], c, mine, a)) ? 1 : 0;
     if (rank < m) selected[rank] = a;
 }
 
